@@ -1,0 +1,176 @@
+"""ctypes front end of the fp64 CPU oracle (oracle/twig_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests, by the smoke check and by the
+CPU-baseline leg of the benchmark.  The GPU package never imports this, and
+this never imports the GPU package.
+
+Tensors cross as CPU torch tensors (fp32, or bf16 viewed as 16-bit patterns);
+results come back as torch tensors.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import List, Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "twig_oracle.c")
+_LIB = os.path.join(_HERE, "libtwig_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (plain -O2, OpenMP over independent units)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(["gcc", "-O2", "-std=c99", "-fPIC", "-shared", "-fopenmp",
+                               "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"])
+    return _LIB
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        _lib = ctypes.CDLL(build())
+        _lib.orc_max_threads.restype = ctypes.c_int
+        _lib.orc_rbar.restype = ctypes.c_int
+    return _lib
+
+
+def set_threads(n: int) -> None:
+    lib().orc_set_threads(int(n))
+
+
+def max_threads() -> int:
+    return int(lib().orc_max_threads())
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return 0
+    if t.dtype == torch.bfloat16:
+        return 1
+    raise TypeError(f"oracle takes fp32 or bf16 inputs, got {t.dtype}")
+
+
+def _p(t: torch.Tensor):
+    assert t.device.type == "cpu" and t.is_contiguous()
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _i32(xs) -> torch.Tensor:
+    return torch.as_tensor(xs, dtype=torch.int32).contiguous()
+
+
+def _i64(xs) -> torch.Tensor:
+    return torch.as_tensor(xs, dtype=torch.int64).contiguous()
+
+
+def _check(rc: int, what: str) -> None:
+    if rc != 0:
+        raise ValueError(f"oracle {what}: invalid argument (code {rc})")
+
+
+def ttp_score(q_sel: torch.Tensor, k: torch.Tensor, n_q: Sequence[int], q_pos0: Sequence[int],
+              n_tot: Sequence[int], k_row_off: Sequence[int], v_start: int, M: int, scale: float,
+              causal: bool = True) -> torch.Tensor:
+    """scores [B][M] in fp64."""
+    B, n_q_max, H, d_h = q_sel.shape
+    assert k.shape[1:] == (H, d_h) and k.dtype == q_sel.dtype
+    out = torch.zeros(B, M, dtype=torch.float64)
+    a, b_, c, d = _i32(n_q), _i32(q_pos0), _i32(n_tot), _i64(k_row_off)
+    rc = lib().orc_ttp_score(_p(q_sel), _p(k), _dtype_code(k), B, H, d_h, n_q_max, _p(a), _p(b_),
+                             _p(c), _p(d), int(v_start), int(M), ctypes.c_double(scale),
+                             int(bool(causal)), _p(out))
+    _check(rc, "ttp_score")
+    return out
+
+
+def ttp_select(scores: torch.Tensor, R: int) -> torch.Tensor:
+    """kept [B][R] int32, ascending; scores fp32 [B][M]."""
+    assert scores.dtype == torch.float32 and scores.dim() == 2
+    B, M = scores.shape
+    kept = torch.empty(B, max(R, 0), dtype=torch.int32)
+    rc = lib().orc_ttp_select(_p(scores.contiguous()), B, M, int(R), _p(kept))
+    _check(rc, "ttp_select")
+    return kept
+
+
+def ttp_compact(kept: torch.Tensor, v_start: int, M: int, src: torch.Tensor) -> torch.Tensor:
+    """src [n_tot][...] of any dtype -> dst [v_start + R + n_tot - v_start - M][...]."""
+    kept = _i32(kept)
+    R, n_tot = int(kept.numel()), int(src.shape[0])
+    src = src.contiguous()
+    row_bytes = src[0].numel() * src.element_size() if n_tot else 0
+    n_out = n_tot - M + R
+    dst = torch.empty((max(n_out, 0),) + tuple(src.shape[1:]), dtype=src.dtype)
+    rc = lib().orc_ttp_compact(_p(kept), R, int(v_start), int(M), n_tot, _p(src), _p(dst),
+                               ctypes.c_size_t(row_bytes))
+    _check(rc, "ttp_compact")
+    return dst
+
+
+def tree_ancestors(parent: Sequence[int]) -> List[int]:
+    par = _i32(parent)
+    T = int(par.numel())
+    anc = torch.zeros(max(T, 1), dtype=torch.int64)
+    rc = lib().orc_tree_ancestors(_p(par), T, _p(anc))
+    _check(rc, "tree_ancestors")
+    return [int(x) & ((1 << 64) - 1) for x in anc[:T].tolist()]
+
+
+def cache_rows(ctx_len: Sequence[int], n_nodes: Sequence[int], row_off: Optional[Sequence[int]],
+               page_table: Optional[Sequence[Sequence[int]]], page_rows: int):
+    """Pool row of each cache row of each instance.  Contiguous: instance b
+    starts at row_off[b].  Paged: cache row r lives in page
+    page_table[b][r // page_rows] at slot r % page_rows."""
+    rows, offs = [], []
+    for b, (c, t) in enumerate(zip(ctx_len, n_nodes)):
+        offs.append(len(rows))
+        for r in range(c + t):
+            if page_table is None:
+                rows.append(row_off[b] + r)
+            else:
+                rows.append(page_table[b][r // page_rows] * page_rows + r % page_rows)
+    return _i64(rows), _i64(offs)
+
+
+def tree_verify_attn(q: torch.Tensor, k_pool: torch.Tensor, v_pool: torch.Tensor,
+                     ctx_len: Sequence[int], n_nodes: Sequence[int], parent, scale: float,
+                     row_off: Optional[Sequence[int]] = None, page_table=None,
+                     page_rows: int = 16) -> torch.Tensor:
+    """out [B][T_max][H][d_h] fp64 (rows past n_nodes[b] are zero)."""
+    B, T_max, H, d_h = q.shape
+    assert k_pool.shape[1:] == (H, d_h) and v_pool.shape == k_pool.shape
+    assert k_pool.dtype == q.dtype == v_pool.dtype
+    rows, offs = cache_rows(ctx_len, n_nodes, row_off, page_table, page_rows)
+    if rows.numel() and int(rows.max()) >= k_pool.shape[0]:
+        raise ValueError("oracle tree_verify_attn: cache row outside the pool")
+    par = _i32(parent).view(B, T_max)
+    out = torch.zeros(B, T_max, H, d_h, dtype=torch.float64)
+    a, c = _i32(n_nodes), _i32(ctx_len)
+    rc = lib().orc_tree_verify_attn(_p(q), _p(k_pool), _p(v_pool), _dtype_code(q), B, H, d_h, T_max,
+                                    _p(a), _p(c), _p(rows), _p(offs), _p(par),
+                                    ctypes.c_double(scale), _p(out))
+    _check(rc, "tree_verify_attn")
+    return out
+
+
+def tree_accept(draft, argmax, parent, n_nodes: Sequence[int]):
+    """(n_acc [B], path [B][T_max], bonus [B]) int32."""
+    d, a, p = _i32(draft), _i32(argmax), _i32(parent)
+    B, T_max = d.shape
+    assert a.shape == d.shape == p.shape
+    n = _i32(n_nodes)
+    n_acc = torch.empty(B, dtype=torch.int32)
+    path = torch.empty(B, T_max, dtype=torch.int32)
+    bonus = torch.empty(B, dtype=torch.int32)
+    rc = lib().orc_tree_accept(_p(d), _p(a), _p(p), _p(n), T_max, B, _p(n_acc), _p(path), _p(bonus))
+    _check(rc, "tree_accept")
+    return n_acc, path, bonus
+
+
+def rbar(M: int, K: int, R: int, K_f: int, L: int) -> int:
+    return int(lib().orc_rbar(int(M), int(K), int(R), int(K_f), int(L)))

@@ -1,0 +1,311 @@
+/*
+ * CPU oracle for the pruned-cache decode path of TwigVLM / TwigVLM++.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain, fp64 statement of
+ * what the GPU library must compute.  It is used by the tests, by the smoke
+ * check and by the CPU-baseline leg of the benchmark, never by the product
+ * path, and it shares no source with the HIP kernels.
+ *
+ * Every function takes host pointers.  Floating-point inputs are either fp32
+ * (dtype 0) or bf16 bit patterns in uint16 (dtype 1); both are widened exactly
+ * to fp64 and all arithmetic is fp64.  Rows of a key/value tensor are
+ * token-major: row r holds H heads of d_h contiguous elements.
+ *
+ * Parity pins (tests/test_oracle_*.py): every function below is checked
+ * against closed forms, library attention routines, brute force and
+ * exhaustive enumeration; none is "parity unpinned".
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+static double widen(const void* base, int dtype, int64_t idx) {
+    if (dtype == 0) return (double)((const float*)base)[idx];
+    uint32_t bits = (uint32_t)((const uint16_t*)base)[idx] << 16;
+    float f;
+    memcpy(&f, &bits, sizeof f);
+    return (double)f;
+}
+
+void orc_set_threads(int n) {
+#ifdef _OPENMP
+    if (n > 0) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}
+
+int orc_max_threads(void) {
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/*
+ * Pruning score (Sec. 3.1 Eq. 2 attention map; Sec. 3.1 Eq. 3 text-to-visual
+ * column sums; head averaging as in Sec. 5.1 Eq. 7).
+ *
+ * For sequence b, head h and scoring row i (absolute position p = q_pos0[b]+i)
+ * the attention row is softmax_j(scale * q . k_j) over keys j <= p when causal,
+ * over all n_tot[b] keys otherwise.  score[b][m] is the mean over heads and
+ * scoring rows of the attention weight on visual key v_start + m.
+ *
+ *   q_sel  [B][n_q_max][H][d_h]   rows beyond n_q[b] unused
+ *   k      rows of sequence b start at row k_row_off[b]
+ *   scores [B][M] fp64
+ */
+int orc_ttp_score(const void* q_sel, const void* k, int dtype, int B, int H, int d_h, int n_q_max,
+                  const int32_t* n_q, const int32_t* q_pos0, const int32_t* n_tot,
+                  const int64_t* k_row_off, int v_start, int M, double scale, int causal,
+                  double* scores) {
+    if (!q_sel || !k || !scores || B < 0 || M < 0) return -1;
+    for (int b = 0; b < B; ++b) {
+        if (v_start < 0 || v_start + M > n_tot[b] || n_q[b] < 1 || n_q[b] > n_q_max) return -1;
+        if (q_pos0[b] < 0 || q_pos0[b] + n_q[b] > n_tot[b]) return -1;
+    }
+    int nthr = orc_max_threads();
+    for (int b = 0; b < B; ++b) {
+        int nt = n_tot[b];
+        double* part = (double*)calloc((size_t)nthr * (size_t)M, sizeof(double));
+        if (!part) return -3;
+#pragma omp parallel
+        {
+#ifdef _OPENMP
+            int tid = omp_get_thread_num();
+#else
+            int tid = 0;
+#endif
+            double* acc = part + (size_t)tid * M;
+            double* s = (double*)malloc((size_t)nt * sizeof(double));
+#pragma omp for collapse(2) schedule(static)
+            for (int h = 0; h < H; ++h) {
+                for (int i = 0; i < n_q[b]; ++i) {
+                    int p = q_pos0[b] + i;
+                    int nvis = causal ? p + 1 : nt;
+                    int64_t qo = (((int64_t)b * n_q_max + i) * H + h) * d_h;
+                    double mx = -INFINITY;
+                    for (int j = 0; j < nvis; ++j) {
+                        int64_t ko = ((k_row_off[b] + j) * H + h) * (int64_t)d_h;
+                        double dot = 0.0;
+                        for (int c = 0; c < d_h; ++c)
+                            dot += widen(q_sel, dtype, qo + c) * widen(k, dtype, ko + c);
+                        s[j] = scale * dot;
+                        if (s[j] > mx) mx = s[j];
+                    }
+                    double l = 0.0;
+                    for (int j = 0; j < nvis; ++j) {
+                        s[j] = exp(s[j] - mx);
+                        l += s[j];
+                    }
+                    for (int m = 0; m < M; ++m) {
+                        int j = v_start + m;
+                        if (j < nvis) acc[m] += s[j] / l;
+                    }
+                }
+            }
+            free(s);
+        }
+        for (int m = 0; m < M; ++m) {
+            double t = 0.0;
+            for (int th = 0; th < nthr; ++th) t += part[(size_t)th * M + m];
+            scores[(size_t)b * M + m] = t / ((double)H * (double)n_q[b]);
+        }
+        free(part);
+    }
+    return 0;
+}
+
+/*
+ * Top-R keep (the TopR operator of Sec. 3.1 Eq. 3).  Order: higher score
+ * first, equal scores (fp32 ==, so -0 equals +0) lower index first.  The R
+ * best indices are returned in ascending index order.  kept [B][R].
+ */
+typedef struct { float s; int32_t m; } orc_pair;
+
+static int pair_cmp(const void* a, const void* b) {
+    const orc_pair* x = (const orc_pair*)a;
+    const orc_pair* y = (const orc_pair*)b;
+    if (x->s > y->s) return -1;
+    if (x->s < y->s) return 1;
+    return (x->m > y->m) - (x->m < y->m);
+}
+
+static int int_cmp(const void* a, const void* b) {
+    int32_t x = *(const int32_t*)a, y = *(const int32_t*)b;
+    return (x > y) - (x < y);
+}
+
+int orc_ttp_select(const float* scores, int B, int M, int R, int32_t* kept) {
+    if (B < 0 || M < 0 || R < 0 || R > M) return -1;
+    if ((B > 0 && M > 0 && !scores) || (B > 0 && R > 0 && !kept)) return -1;
+    orc_pair* pr = (orc_pair*)malloc(sizeof(orc_pair) * (size_t)(M > 0 ? M : 1));
+    if (!pr) return -3;
+    for (int b = 0; b < B; ++b) {
+        for (int m = 0; m < M; ++m) {
+            pr[m].s = scores[(size_t)b * M + m];
+            pr[m].m = m;
+        }
+        /* the comparator is a total order on (score, index), so any sort is stable here */
+        qsort(pr, (size_t)M, sizeof(orc_pair), pair_cmp);
+        for (int r = 0; r < R; ++r) kept[(size_t)b * R + r] = pr[r].m;
+        qsort(kept + (size_t)b * R, (size_t)R, sizeof(int32_t), int_cmp);
+    }
+    free(pr);
+    return 0;
+}
+
+/*
+ * Stable compaction (Sec. 3.1 Eq. 3: the kept visual rows, in their original
+ * order, followed by every text row; rows in front of the visual span are
+ * kept like text).  dst has v_start + R + (n_tot - v_start - M) rows.
+ */
+int orc_ttp_compact(const int32_t* kept, int R, int v_start, int M, int n_tot, const void* src,
+                    void* dst, size_t row_bytes) {
+    if (R < 0 || R > M || v_start < 0 || v_start + M > n_tot) return -1;
+    if (!src || !dst || (R > 0 && !kept)) return -1;
+    for (int r = 0; r < R; ++r)
+        if (kept[r] < 0 || kept[r] >= M) return -1;
+    const char* s = (const char*)src;
+    char* d = (char*)dst;
+    int64_t o = 0;
+    for (int r = 0; r < v_start; ++r) memcpy(d + (o++) * row_bytes, s + (int64_t)r * row_bytes, row_bytes);
+    for (int r = 0; r < R; ++r)
+        memcpy(d + (o++) * row_bytes, s + (int64_t)(v_start + kept[r]) * row_bytes, row_bytes);
+    for (int r = v_start + M; r < n_tot; ++r)
+        memcpy(d + (o++) * row_bytes, s + (int64_t)r * row_bytes, row_bytes);
+    return 0;
+}
+
+/*
+ * Ancestor-or-self sets of a draft tree as bit masks (tree attention of
+ * Sec. 5.4 / App. A: a node sees its ancestors; the diagonal is included as
+ * in any causal mask).  Node 0 is the root with parent -1, parent[i] < i.
+ */
+int orc_tree_ancestors(const int32_t* parent, int T, uint64_t* anc) {
+    if (!parent || !anc || T < 1 || T > 64 || parent[0] != -1) return -1;
+    for (int i = 1; i < T; ++i)
+        if (parent[i] < 0 || parent[i] >= i) return -1;
+    for (int i = 0; i < T; ++i) {
+        uint64_t m = 0;
+        for (int u = i; u >= 0; u = parent[u]) m |= (uint64_t)1 << u;
+        anc[i] = m;
+    }
+    return 0;
+}
+
+/*
+ * Tree verification attention (Sec. 3.1 Eq. 2 restricted by the
+ * topology-aware mask of Sec. 5.4 / App. A).  For instance b, tree row t and
+ * head h the visible keys are the ctx_len[b] committed rows plus the tree rows
+ * of t's ancestors and t itself; tree row u's key/value is cache row
+ * ctx_len[b] + u.  Cache row r of instance b is pool row rows[rows_off[b] + r].
+ *
+ *   q   [B][T_max][H][d_h]       out [B][T_max][H][d_h] fp64 (rows >= n_nodes[b] untouched)
+ */
+int orc_tree_verify_attn(const void* q, const void* k_pool, const void* v_pool, int dtype, int B,
+                         int H, int d_h, int T_max, const int32_t* n_nodes, const int32_t* ctx_len,
+                         const int64_t* rows, const int64_t* rows_off, const int32_t* parent,
+                         double scale, double* out) {
+    if (!q || !k_pool || !v_pool || !out || !parent || T_max < 1 || T_max > 64) return -1;
+    for (int b = 0; b < B; ++b) {
+        if (n_nodes[b] < 1 || n_nodes[b] > T_max || ctx_len[b] < 0) return -1;
+        uint64_t tmp[64];
+        if (orc_tree_ancestors(parent + (size_t)b * T_max, n_nodes[b], tmp)) return -1;
+    }
+#pragma omp parallel for collapse(2) schedule(dynamic)
+    for (int b = 0; b < B; ++b) {
+        for (int h = 0; h < H; ++h) {
+            int T = n_nodes[b], C = ctx_len[b];
+            uint64_t anc[64];
+            orc_tree_ancestors(parent + (size_t)b * T_max, T, anc);
+            const int64_t* rw = rows + rows_off[b];
+            double* s = (double*)malloc((size_t)(C + T) * sizeof(double));
+            for (int t = 0; t < T; ++t) {
+                int64_t qo = (((int64_t)b * T_max + t) * H + h) * d_h;
+                double mx = -INFINITY;
+                for (int j = 0; j < C + T; ++j) {
+                    int vis = j < C || ((anc[t] >> (j - C)) & 1);
+                    if (!vis) { s[j] = -INFINITY; continue; }
+                    int64_t ko = (rw[j] * H + h) * (int64_t)d_h;
+                    double dot = 0.0;
+                    for (int c = 0; c < d_h; ++c)
+                        dot += widen(q, dtype, qo + c) * widen(k_pool, dtype, ko + c);
+                    s[j] = scale * dot;
+                    if (s[j] > mx) mx = s[j];
+                }
+                double l = 0.0;
+                for (int j = 0; j < C + T; ++j) {
+                    s[j] = (s[j] == -INFINITY) ? 0.0 : exp(s[j] - mx);
+                    l += s[j];
+                }
+                double* o = out + qo;
+                for (int c = 0; c < d_h; ++c) o[c] = 0.0;
+                for (int j = 0; j < C + T; ++j) {
+                    if (s[j] == 0.0) continue;
+                    int64_t vo = (rw[j] * H + h) * (int64_t)d_h;
+                    double w = s[j] / l;
+                    for (int c = 0; c < d_h; ++c) o[c] += w * widen(v_pool, dtype, vo + c);
+                }
+            }
+            free(s);
+        }
+    }
+    return 0;
+}
+
+/*
+ * Greedy acceptance walk (Sec. 5.4, App. A and the last steps of Alg. 2; a
+ * chain is the sequence case of Alg. 1).  argmax[i] is the target model's
+ * prediction for the token that follows node i.  Starting from the root, a
+ * child is accepted when its draft id equals the argmax id of the node it
+ * hangs under.  When several children of one node carry the matching id the
+ * walk explores each and keeps the deepest end point, ties toward the lower
+ * node index.  n_acc counts accepted draft nodes (root excluded), path lists
+ * them root-side first (unused slots -1), bonus is argmax at the end point.
+ */
+static void walk(const int32_t* draft, const int32_t* argmx, const int32_t* parent, int T, int cur,
+                 int depth, int* best, int* best_depth) {
+    if (depth > *best_depth || (depth == *best_depth && cur < *best)) {
+        *best = cur;
+        *best_depth = depth;
+    }
+    for (int c = cur + 1; c < T; ++c)
+        if (parent[c] == cur && draft[c] == argmx[cur])
+            walk(draft, argmx, parent, T, c, depth + 1, best, best_depth);
+}
+
+int orc_tree_accept(const int32_t* draft, const int32_t* argmx, const int32_t* parent,
+                    const int32_t* n_nodes, int T_max, int B, int32_t* n_acc, int32_t* path,
+                    int32_t* bonus) {
+    if (!draft || !argmx || !parent || !n_nodes || !n_acc || !path || !bonus) return -1;
+    if (T_max < 1 || T_max > 64) return -1;
+    for (int b = 0; b < B; ++b) {
+        const int32_t* par = parent + (size_t)b * T_max;
+        int T = n_nodes[b];
+        uint64_t tmp[64];
+        if (T < 1 || T > T_max || orc_tree_ancestors(par, T, tmp)) return -1;
+        int best = 0, best_depth = -1;
+        walk(draft + (size_t)b * T_max, argmx + (size_t)b * T_max, par, T, 0, 0, &best, &best_depth);
+        n_acc[b] = best_depth;
+        bonus[b] = argmx[(size_t)b * T_max + best];
+        int32_t* p = path + (size_t)b * T_max;
+        for (int i = 0; i < T_max; ++i) p[i] = -1;
+        for (int u = best, d = best_depth; u > 0; u = par[u]) p[--d] = u;
+    }
+    return 0;
+}
+
+/*
+ * Average number of retained visual tokens with FinalWipe (Sec. 4.2 Eq. 6;
+ * Eq. 4 is the case K_f = L), rounded to the nearest integer.
+ */
+int orc_rbar(int M, int K, int R, int K_f, int L) {
+    double x = ((double)M * K + (double)R * (K_f - K)) / (double)L;
+    return (int)floor(x + 0.5);
+}

@@ -1,0 +1,453 @@
+"""Pins for the CPU oracle: every oracle function is checked against something
+other than itself -- closed forms, torch's library attention routine, numpy's
+stable sort, brute force over tiny cases, exhaustive enumeration, and the one
+family of numbers the paper prints (tests/golden/rbar_table.txt).  Each check
+is chosen so that a dropped term, a wrong sign or index, or a transposed
+operand in the oracle fails it.  CPU only.
+"""
+import itertools
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+import torch.nn.functional as F
+
+import oracle
+from paper_2503_14075_amd import workloads as W
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _rand(seed, stream, shape, std=1.0, dtype=torch.float32):
+    return W.normal(seed, stream, shape, std, dtype)
+
+
+# ----------------------------------------------------------------------------
+# ttp_score  (Sec. 3.1 Eq. 2-3, head mean)
+# ----------------------------------------------------------------------------
+def _library_attention_map(q, k, pos0, scale, causal):
+    """Attention map through torch's fused attention routine: with V = identity
+    the routine's output *is* the map A.  q [n_q][H][d], k [n][H][d] -> [H][n_q][n]."""
+    n_q, n = q.shape[0], k.shape[0]
+    qq = q.double().permute(1, 0, 2)[None]
+    kk = k.double().permute(1, 0, 2)[None]
+    eye = torch.eye(n, dtype=torch.float64).expand(1, q.shape[1], n, n)
+    mask = None
+    if causal:
+        pos = pos0 + torch.arange(n_q)[:, None]
+        mask = torch.arange(n)[None, :] <= pos
+    return F.scaled_dot_product_attention(qq, kk, eye, attn_mask=mask, scale=scale)[0]
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("causal", [True, False])
+def test_score_matches_library_attention_map(dtype, causal):
+    H, d, M, N, n_q, v0 = 3, 16, 37, 9, 5, 2
+    n_tot = v0 + M + N
+    q = _rand(11, 1, (1, n_q, H, d), 1.0, dtype)
+    k = _rand(11, 2, (n_tot, H, d), 1.0, dtype)
+    pos0 = n_tot - n_q
+    got = oracle.ttp_score(q, k, [n_q], [pos0], [n_tot], [0], v0, M, 0.3, causal)[0]
+    A = _library_attention_map(q[0], k, pos0, 0.3, causal)
+    want = A[:, :, v0:v0 + M].sum(dim=(0, 1)) / (H * n_q)
+    assert torch.allclose(got, want, rtol=0, atol=1e-12)
+
+
+def test_score_uniform_keys_closed_form():
+    # identical keys -> uniform attention: causal row at position p gives 1/(p+1) to each visible key
+    H, d, M, N, n_q = 2, 8, 20, 6, 4
+    n_tot = M + N
+    k = _rand(3, 1, (1, H, d)).expand(n_tot, H, d).contiguous()
+    q = _rand(3, 2, (1, n_q, H, d))
+    pos0 = n_tot - n_q
+    got = oracle.ttp_score(q, k, [n_q], [pos0], [n_tot], [0], 0, M, 0.5, True)[0]
+    want = sum(1.0 / (pos0 + i + 1) for i in range(n_q)) / n_q
+    assert torch.allclose(got, torch.full((M,), want, dtype=torch.float64), atol=1e-14)
+    got = oracle.ttp_score(q, k, [n_q], [pos0], [n_tot], [0], 0, M, 0.5, False)[0]
+    assert torch.allclose(got, torch.full((M,), 1.0 / n_tot, dtype=torch.float64), atol=1e-14)
+
+
+def test_score_mass_and_dominant_key_and_permutation():
+    H, d, M, N, n_q = 4, 8, 30, 10, 10
+    n_tot = M + N
+    q = _rand(5, 1, (1, n_q, H, d))
+    k = _rand(5, 2, (n_tot, H, d))
+    # whole sequence as the span: every attention row sums to one
+    full = oracle.ttp_score(q, k, [n_q], [M], [n_tot], [0], 0, n_tot, 0.35, True)[0]
+    assert abs(float(full.sum()) - 1.0) < 1e-13
+    vis = oracle.ttp_score(q, k, [n_q], [M], [n_tot], [0], 0, M, 0.35, True)[0]
+    assert torch.equal(vis, full[:M])          # span position only selects columns
+    # a span that does not start at zero selects the shifted columns
+    sh = oracle.ttp_score(q, k, [n_q], [M], [n_tot], [0], 7, 11, 0.35, True)[0]
+    assert torch.equal(sh, full[7:18])
+    # heads and (non-causal) scoring rows may be permuted freely
+    hp = torch.tensor([2, 0, 3, 1])
+    rp = torch.randperm(n_q, generator=torch.Generator().manual_seed(1))
+    base = oracle.ttp_score(q, k, [n_q], [M], [n_tot], [0], 0, M, 0.35, False)[0]
+    perm = oracle.ttp_score(q[:, rp][:, :, hp].contiguous(), k[:, hp].contiguous(), [n_q], [M],
+                            [n_tot], [0], 0, M, 0.35, False)[0]
+    assert torch.allclose(base, perm, atol=1e-15)
+    # one key aligned with every query and a large scale takes all the mass
+    k2 = k.clone()
+    k2[13] = 0
+    qs = torch.ones(1, n_q, H, d)
+    k2[13] = 50.0
+    dom = oracle.ttp_score(qs, k2, [n_q], [M], [n_tot], [0], 0, M, 1.0, True)[0]
+    assert dom[13] > 1 - 1e-9 and float(dom.sum()) <= 1 + 1e-12
+
+
+def test_score_single_query_textbook_softmax_and_batch_offsets():
+    # n_q = 1, H = 1: one softmax over the keys, typed out with numpy
+    d, M, N = 8, 12, 3
+    n_tot = M + N
+    q = _rand(7, 1, (2, 1, 1, d))
+    k = _rand(7, 2, (2 * n_tot + 5, 1, d))
+    offs = [5, 5 + n_tot]                  # two sequences at different pool offsets
+    got = oracle.ttp_score(q, k, [1, 1], [n_tot - 1] * 2, [n_tot] * 2, offs, 0, M, 0.7, True)
+    for b in range(2):
+        kk = k[offs[b]:offs[b] + n_tot, 0].double().numpy()
+        s = 0.7 * kk @ q[b, 0, 0].double().numpy()
+        e = np.exp(s - s.max())
+        assert np.allclose(got[b].numpy(), (e / e.sum())[:M], atol=1e-14)
+
+
+def test_score_ragged_rows_use_only_their_own_count():
+    H, d, M = 2, 8, 10
+    n_tot = [M + 4, M + 7]
+    q = _rand(9, 1, (2, 7, H, d))
+    k = _rand(9, 2, (sum(n_tot), H, d))
+    got = oracle.ttp_score(q, k, [4, 7], [M, M], n_tot, [0, n_tot[0]], 0, M, 0.3, True)
+    for b, (nq, off) in enumerate(zip([4, 7], [0, n_tot[0]])):
+        A = _library_attention_map(q[b, :nq], k[off:off + n_tot[b]], M, 0.3, True)
+        assert torch.allclose(got[b], A[:, :, :M].sum(dim=(0, 1)) / (H * nq), atol=1e-13)
+
+
+def test_score_rejects_bad_spans():
+    q = torch.zeros(1, 2, 1, 4)
+    k = torch.zeros(10, 1, 4)
+    with pytest.raises(ValueError):
+        oracle.ttp_score(q, k, [2], [8], [10], [0], 5, 6, 1.0, True)     # span past the end
+    with pytest.raises(ValueError):
+        oracle.ttp_score(q, k, [3], [7], [10], [0], 0, 6, 1.0, True)     # more rows than supplied
+
+
+# ----------------------------------------------------------------------------
+# ttp_select  (TopR of Sec. 3.1 Eq. 3; ties toward the lower index)
+# ----------------------------------------------------------------------------
+def _repeated_max(scores, R):
+    s = [float(x) for x in scores]
+    taken = []
+    for _ in range(R):
+        best = None
+        for m, x in enumerate(s):
+            if m in taken:
+                continue
+            if best is None or x > s[best]:
+                best = m
+        taken.append(best)
+    return sorted(taken)
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_select_vs_stable_argsort_and_repeated_max(seed):
+    g = torch.Generator().manual_seed(seed)
+    M = 97
+    # few distinct values -> many ties, including -0.0 / +0.0
+    vals = torch.tensor([-1.5, -0.0, 0.0, 0.25, 0.25, 3.0])
+    sc = vals[torch.randint(0, len(vals), (4, M), generator=g)].float()
+    for R in (0, 1, 13, 50, M - 1, M):
+        got = oracle.ttp_select(sc, R)
+        for b in range(4):
+            x = sc[b].numpy()
+            order = np.argsort(-(x + 0.0), kind="stable")      # +0.0 folds -0 into +0
+            assert got[b].tolist() == sorted(order[:R].tolist())
+            if R <= 13:
+                assert got[b].tolist() == _repeated_max(x, R)
+
+
+def test_select_closed_forms():
+    M, R = 40, 7
+    assert oracle.ttp_select(torch.zeros(1, M), R)[0].tolist() == list(range(R))
+    dec = torch.arange(M, 0, -1).float()[None]
+    inc = torch.arange(M).float()[None]
+    assert oracle.ttp_select(dec, R)[0].tolist() == list(range(R))
+    assert oracle.ttp_select(inc, R)[0].tolist() == list(range(M - R, M))
+    assert oracle.ttp_select(inc, M)[0].tolist() == list(range(M))
+    assert oracle.ttp_select(inc, 0).shape == (1, 0)
+    sc = torch.zeros(1, M)
+    sc[0, [5, 9, 31]] = torch.tensor([1e-30, -1e-30, 2.0])     # tiny magnitudes and a negative
+    assert oracle.ttp_select(sc, 3)[0].tolist() == [0, 5, 31]
+    with pytest.raises(ValueError):
+        oracle.ttp_select(inc, M + 1)
+
+
+# ----------------------------------------------------------------------------
+# ttp_compact
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16, torch.uint8])
+def test_compact_identity_subsequence_and_library_gather(dtype):
+    v0, M, N = 3, 25, 6
+    n_tot = v0 + M + N
+    src = torch.randint(0, 255, (n_tot, 10), generator=torch.Generator().manual_seed(1)).to(dtype)
+    assert torch.equal(oracle.ttp_compact(torch.arange(M), v0, M, src), src)      # keep all
+    kept = torch.tensor([0, 4, 5, 17, 24])
+    dst = oracle.ttp_compact(kept, v0, M, src)
+    idx = torch.cat([torch.arange(v0), v0 + kept, torch.arange(v0 + M, n_tot)])
+    assert torch.equal(dst, src.index_select(0, idx))
+    assert torch.equal(dst[-N:], src[-N:]) and torch.equal(dst[:v0], src[:v0])
+    wipe = oracle.ttp_compact(torch.tensor([], dtype=torch.int32), v0, M, src)     # R = 0 drops the span
+    assert torch.equal(wipe, torch.cat([src[:v0], src[v0 + M:]]))
+
+
+def test_compact_composes():
+    M, N = 30, 4
+    src = _rand(2, 1, (M + N, 6))
+    k1 = torch.tensor([1, 3, 4, 8, 20, 21, 29])
+    k2 = torch.tensor([0, 2, 5, 6])
+    twice = oracle.ttp_compact(k2, 0, len(k1), oracle.ttp_compact(k1, 0, M, src))
+    once = oracle.ttp_compact(k1[k2], 0, M, src)
+    assert torch.equal(twice, once)
+    with pytest.raises(ValueError):
+        oracle.ttp_compact(torch.tensor([M]), 0, M, src)
+
+
+# ----------------------------------------------------------------------------
+# tree_ancestors / tree_verify_attn  (Sec. 5.4, App. A)
+# ----------------------------------------------------------------------------
+def test_ancestors_by_hand():
+    #        0
+    #      / | \
+    #     1  2  3
+    #     |     |
+    #     4     5
+    #     |
+    #     6
+    par = [-1, 0, 0, 0, 1, 3, 4]
+    want = [0b1, 0b11, 0b101, 0b1001, 0b10011, 0b101001, 0b1010011]
+    assert oracle.tree_ancestors(par) == want
+    assert oracle.tree_ancestors([-1] + list(range(63)))[63] == (1 << 64) - 1
+    for bad in ([0, 0], [-1, 1], [-1, -1], [-1, 0, 3]):
+        with pytest.raises(ValueError):
+            oracle.tree_ancestors(bad)
+
+
+def _causal_library(q_rows, k_rows, v_rows, scale):
+    """Plain causal attention of the last len(q_rows) positions over all rows, via
+    torch's routine.  q [t][H][d], k/v [n][H][d] -> [t][H][d] fp64."""
+    t, n = q_rows.shape[0], k_rows.shape[0]
+    mask = torch.arange(n)[None, :] <= (n - t + torch.arange(t))[:, None]
+    o = F.scaled_dot_product_attention(q_rows.double().permute(1, 0, 2)[None],
+                                       k_rows.double().permute(1, 0, 2)[None],
+                                       v_rows.double().permute(1, 0, 2)[None],
+                                       attn_mask=mask, scale=scale)
+    return o[0].permute(1, 0, 2)
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_verify_chain_equals_causal_decode(dtype):
+    H, d, C, T = 3, 16, 21, 7
+    q = _rand(21, 1, (1, T, H, d), 1.0, dtype)
+    k = _rand(21, 2, (C + T + 4, H, d), 1.0, dtype)
+    v = _rand(21, 3, (C + T + 4, H, d), 1.0, dtype)
+    par = [-1] + list(range(T - 1))
+    got = oracle.tree_verify_attn(q, k, v, [C], [T], [par], 0.25, row_off=[4])[0]
+    want = _causal_library(q[0], k[4:], v[4:], 0.25)
+    assert torch.allclose(got, want, atol=1e-12)
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_verify_tree_equals_per_branch_causal_runs(seed):
+    H, d, C, T = 2, 8, 13, 12
+    par = W.random_parent_tree(W.HostRng(seed, 1), T, 4)
+    q = _rand(seed, 1, (1, T, H, d))
+    k = _rand(seed, 2, (C + T, H, d))
+    v = _rand(seed, 3, (C + T, H, d))
+    got = oracle.tree_verify_attn(q, k, v, [C], [T], [par], 0.4, row_off=[0])[0]
+    leaves = [i for i in range(T) if i not in par]
+    seen = set()
+    for leaf in leaves:
+        chain = []
+        u = leaf
+        while u >= 0:
+            chain.append(u)
+            u = par[u]
+        chain.reverse()
+        rows = list(range(C)) + [C + u for u in chain]
+        want = _causal_library(q[0, chain], k[rows], v[rows], 0.4)
+        for pos, u in enumerate(chain):
+            assert torch.allclose(got[u], want[pos], atol=1e-12)
+            seen.add(u)
+    assert seen == set(range(T))
+
+
+def test_verify_closed_forms_constant_v_constant_k_star_and_single():
+    H, d, C, T = 2, 8, 9, 6
+    par = [-1, 0, 0, 1, 1, 2]
+    q = _rand(31, 1, (1, T, H, d))
+    k = _rand(31, 2, (C + T, H, d))
+    v = _rand(31, 3, (C + T, H, d))
+    # all value rows equal -> every output equals that row whatever the mask
+    vc = v[:1].expand(C + T, H, d).contiguous()
+    got = oracle.tree_verify_attn(q, k, vc, [C], [T], [par], 0.3, row_off=[0])[0]
+    assert torch.allclose(got, vc[0].double().expand(T, H, d), atol=1e-13)
+    # all key rows equal -> uniform weights -> mean of the visible value rows
+    kc = k[:1].expand(C + T, H, d).contiguous()
+    got = oracle.tree_verify_attn(q, kc, v, [C], [T], [par], 0.3, row_off=[0])[0]
+    anc = {0: [0], 1: [0, 1], 2: [0, 2], 3: [0, 1, 3], 4: [0, 1, 4], 5: [0, 2, 5]}
+    for t in range(T):
+        rows = list(range(C)) + [C + u for u in anc[t]]
+        assert torch.allclose(got[t], v[rows].double().mean(0), atol=1e-13)
+    # star: each leaf sees context + root + itself only
+    star = [-1, 0, 0, 0, 0, 0]
+    got = oracle.tree_verify_attn(q, k, v, [C], [T], [star], 0.3, row_off=[0])[0]
+    for t in range(1, T):
+        rows = list(range(C)) + [C, C + t]
+        want = _causal_library(q[0, [t]], k[rows], v[rows], 0.3)
+        assert torch.allclose(got[t], want[0], atol=1e-12)
+    # T = 1: ordinary one-token decode attention, typed out with numpy for one head
+    got = oracle.tree_verify_attn(q[:, :1].contiguous(), k, v, [C], [1], [[-1]], 0.3, row_off=[0])[0]
+    s = 0.3 * k[:C + 1, 1].double().numpy() @ q[0, 0, 1].double().numpy()
+    e = np.exp(s - s.max())
+    assert np.allclose(got[0, 1].numpy(), (e / e.sum()) @ v[:C + 1, 1].double().numpy(), atol=1e-13)
+    # empty context: only the tree rows are keys
+    got = oracle.tree_verify_attn(q, k, v, [0], [T], [par], 0.3, row_off=[C])[0]
+    want = _causal_library(q[0, [0, 1, 3]], k[[C, C + 1, C + 3]], v[[C, C + 1, C + 3]], 0.3)
+    assert torch.allclose(got[3], want[2], atol=1e-12)
+
+
+def test_verify_paged_equals_contiguous_and_ragged_batch():
+    H, d, pr = 2, 8, 4
+    ctx, nn = [10, 3], [5, 7]
+    pars = [[-1, 0, 0, 1, 3, -1, -1], [-1, 0, 1, 1, 0, 4, 5]]     # first tree uses 5 of 7 slots
+    pars[0][5:] = [0, 0]                                            # padding entries are ignored
+    q = _rand(41, 1, (2, 7, H, d))
+    rows = [c + t for c, t in zip(ctx, nn)]
+    off = [0, rows[0]]
+    k = _rand(41, 2, (sum(rows), H, d))
+    v = _rand(41, 3, (sum(rows), H, d))
+    cont = oracle.tree_verify_attn(q, k, v, ctx, nn, pars, 0.5, row_off=off)
+    # scatter the same rows into shuffled pages
+    n_pages = [(r + pr - 1) // pr for r in rows]
+    ids = list(range(sum(n_pages)))
+    W.HostRng(1, 2).shuffle(ids)
+    pt, kk = [], 0
+    for n in n_pages:
+        pt.append(ids[kk:kk + n] + [0] * (max(n_pages) - n))
+        kk += n
+    kp = torch.zeros(sum(n_pages) * pr, H, d)
+    vp = torch.zeros_like(kp)
+    for b in range(2):
+        for r in range(rows[b]):
+            dst = pt[b][r // pr] * pr + r % pr
+            kp[dst], vp[dst] = k[off[b] + r], v[off[b] + r]
+    paged = oracle.tree_verify_attn(q, kp, vp, ctx, nn, pars, 0.5, page_table=pt, page_rows=pr)
+    assert torch.equal(cont, paged)
+    # instance 0 alone gives the same rows; rows past n_nodes stay zero
+    solo = oracle.tree_verify_attn(q[:1, :5].contiguous(), k, v, ctx[:1], nn[:1], [pars[0][:5]], 0.5,
+                                   row_off=off[:1])
+    assert torch.equal(solo[0], cont[0, :5])
+    assert float(cont[0, 5:].abs().max()) == 0.0
+
+
+# ----------------------------------------------------------------------------
+# tree_accept  (Sec. 5.4, App. A, Alg. 2; chain = Alg. 1)
+# ----------------------------------------------------------------------------
+def _enumerate_paths(draft, argmx, par):
+    """Every root->node path; keep the fully matched ones; longest wins, then lowest index."""
+    best, best_len, best_path = 0, 0, []
+    for i in range(len(par)):
+        path, u = [], i
+        while u > 0:
+            path.append(u)
+            u = par[u]
+        path.reverse()
+        if all(draft[u] == argmx[par[u]] for u in path):
+            if len(path) > best_len:
+                best, best_len, best_path = i, len(path), path
+    return best_len, best_path, argmx[best]
+
+
+def _all_trees(T):
+    for tail in itertools.product(*[range(i) for i in range(1, T)]):
+        yield [-1] + list(tail)
+
+
+def _run_accept_cases(cases, T):
+    d = [c[0] for c in cases]
+    a = [c[1] for c in cases]
+    p = [c[2] for c in cases]
+    n_acc, path, bonus = oracle.tree_accept(d, a, p, [T] * len(cases))
+    for i, (dr, am, pa) in enumerate(cases):
+        ln, pth, bo = _enumerate_paths(dr, am, pa)
+        assert int(n_acc[i]) == ln, (dr, am, pa)
+        assert path[i].tolist() == pth + [-1] * (T - ln), (dr, am, pa)
+        assert int(bonus[i]) == bo, (dr, am, pa)
+
+
+def test_accept_exhaustive_small_trees_binary_alphabet():
+    for T in (1, 2, 3, 4, 5):
+        cases = []
+        for par in _all_trees(T):
+            for dr in itertools.product((0, 1), repeat=T):
+                for am in itertools.product((0, 1), repeat=T):
+                    cases.append((list(dr), list(am), par))
+        _run_accept_cases(cases, T)
+
+
+@pytest.mark.parametrize("T,alpha", [(6, 2), (7, 3), (7, 2), (12, 3)])
+def test_accept_sampled_larger_trees(T, alpha):
+    rng = W.HostRng(T * 10 + alpha, 0)
+    cases = []
+    for _ in range(6000):
+        par = W.random_parent_tree(rng, T, T)
+        dr = [rng.randint(0, alpha - 1) for _ in range(T)]
+        am = [rng.randint(0, alpha - 1) for _ in range(T)]
+        cases.append((dr, am, par))
+    _run_accept_cases(cases, T)
+
+
+def test_accept_chain_is_longest_matching_prefix_and_special_cases():
+    rng = W.HostRng(5, 5)
+    T = 9
+    par = [-1] + list(range(T - 1))
+    for _ in range(500):
+        dr = [rng.randint(0, 2) for _ in range(T)]
+        am = [rng.randint(0, 2) for _ in range(T)]
+        # sequence case: drafts dr[1..], target predictions am[0..]; stop at the first mismatch
+        n = 0
+        while n + 1 < T and dr[n + 1] == am[n]:
+            n += 1
+        n_acc, path, bonus = oracle.tree_accept([dr], [am], [par], [T])
+        assert int(n_acc[0]) == n and int(bonus[0]) == am[n]
+        assert path[0].tolist() == list(range(1, n + 1)) + [-1] * (T - n)
+    # nothing matches -> only the bonus token of the root
+    par = [-1, 0, 0, 1, 2]
+    n_acc, path, bonus = oracle.tree_accept([[9, 1, 2, 3, 4]], [[5, 6, 7, 8, 9]], [par], [5])
+    assert (int(n_acc[0]), int(bonus[0]), path[0].tolist()) == (0, 5, [-1] * 5)
+    # full match down to leaf 4 (0 -> 2 -> 4)
+    n_acc, path, bonus = oracle.tree_accept([[0, 1, 50, 3, 70]], [[50, 6, 70, 8, 99]], [par], [5])
+    assert (int(n_acc[0]), int(bonus[0]), path[0].tolist()) == (2, 99, [2, 4, -1, -1, -1])
+    # duplicate sibling ids: both children of the root match, only the second continues
+    par = [-1, 0, 0, 2]
+    n_acc, path, bonus = oracle.tree_accept([[0, 7, 7, 8]], [[7, 1, 8, 3]], [par], [4])
+    assert (int(n_acc[0]), int(bonus[0]), path[0].tolist()) == (2, 3, [2, 3, -1, -1])
+    # equal depth -> lower node index
+    n_acc, path, bonus = oracle.tree_accept([[0, 7, 7, 8]], [[7, 1, 2, 3]], [par], [4])
+    assert (int(n_acc[0]), int(bonus[0]), path[0].tolist()) == (1, 1, [1, -1, -1, -1])
+    # only the first n_nodes entries count
+    n_acc, _, _ = oracle.tree_accept([[0, 7, 7, 8]], [[7, 1, 8, 3]], [par], [3])
+    assert int(n_acc[0]) == 1
+
+
+# ----------------------------------------------------------------------------
+# the numbers the paper prints (Sec. 4.2 Eq. 6)
+# ----------------------------------------------------------------------------
+def test_rbar_matches_printed_settings():
+    rows = [ln.split() for ln in open(os.path.join(GOLDEN, "rbar_table.txt"))
+            if ln.strip() and not ln.startswith("#")]
+    assert len(rows) == 8
+    for M, K, R, K_f, L, want in (map(int, r) for r in rows):
+        assert oracle.rbar(M, K, R, K_f, L) == want
+    assert oracle.rbar(576, 2, 64, 32, 32) == round((576 * 2 + 64 * 30) / 32)   # Eq. 4 form
