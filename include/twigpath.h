@@ -1,0 +1,188 @@
+/*
+ * twigpath -- C ABI of the MI355X (gfx950) decode hot path of TwigVLM /
+ * TwigVLM++: twig-guided token pruning (score, top-R select, stable
+ * compaction) and tree-based self-speculative verification (ancestor masks,
+ * tree-masked attention, greedy acceptance walk).
+ *
+ * Conventions for every call
+ *   - Pointers marked [dev] are device memory owned by the caller; pointers
+ *     marked [host] are read on the host during the call and not retained.
+ *   - The library allocates no device memory and keeps no state between calls.
+ *     Scratch space comes in through (ws, ws_bytes); tw_workspace_bytes() tells
+ *     how much a call needs.
+ *   - A call only enqueues work on `stream` (a hipStream_t passed as void*;
+ *     NULL = the default stream) and returns.  Nothing synchronises, nothing is
+ *     read back.  Outputs are valid once the caller has synchronised the stream.
+ *   - The return value is a tw_status.  No exception crosses the boundary and
+ *     nothing is printed.  Contents of device arrays cannot be checked without
+ *     a synchronisation, so they are preconditions; when one is violated the
+ *     kernels stay inside the buffers described by the arguments (indices are
+ *     clamped) but the result is unspecified.
+ *   - Same inputs give bit-identical outputs from run to run (no
+ *     order-dependent floating-point atomics anywhere).
+ *
+ * Tensor layout: token-major rows.  A row of a key, value or query tensor is H
+ * heads of d_h contiguous elements (bf16 or fp32).  d_h must be a multiple of
+ * 8 and at most 128; the matrix-core path is taken for bf16 with d_h 64 or 128.
+ */
+#ifndef TWIGPATH_H
+#define TWIGPATH_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    TW_OK = 0,
+    TW_ERR_INVALID_ARG = -1, /* null pointer, negative size, R > M, span outside the sequence ... */
+    TW_ERR_UNSUPPORTED = -2, /* T_max > 64, d_h not supported, dtype combination not built */
+    TW_ERR_WORKSPACE = -3,   /* ws is NULL or ws_bytes too small */
+    TW_ERR_LAUNCH = -4       /* the HIP runtime reported an error for a launch */
+} tw_status;
+
+typedef enum { TW_F32 = 0, TW_BF16 = 1 } tw_dtype;
+
+typedef enum { TW_CALL_TTP_SCORE = 1, TW_CALL_TREE_VERIFY_ATTN = 2 } tw_call;
+
+#define TW_MAX_TREE 64 /* tree rows per sequence, root included */
+
+/*
+ * One layer's K (or V) for a batch of B sequences, living in one pool of
+ * pool_rows rows.  Contiguous mode (page_table == NULL): cache row r of
+ * sequence b is pool row row_off[b] + r.  Paged mode: it is slot r % page_rows
+ * of page page_table[b * max_pages + r / page_rows].  The struct itself is
+ * host memory; base, row_off and page_table point to device memory.
+ */
+typedef struct tw_kv_view {
+    const void* base;          /* [dev] pool_rows * H * d_h elements */
+    int32_t dtype;             /* tw_dtype */
+    int32_t H, d_h;
+    int64_t pool_rows;
+    const int32_t* row_off;    /* [dev] [B], contiguous mode */
+    const int32_t* page_table; /* [dev] [B][max_pages], paged mode, else NULL */
+    int32_t max_pages, page_rows;
+} tw_kv_view;
+
+/* Library version, 1000*major + minor. */
+int32_t tw_version(void);
+
+/*
+ * Scratch bytes needed by a call.  `which` is a tw_call.  For
+ * TW_CALL_TTP_SCORE: rows = n_q_max, max_rows = n_tot_max.  For
+ * TW_CALL_TREE_VERIFY_ATTN: rows = T_max, max_rows = max_ctx_len + T_max.
+ * Returns 0 for calls that need none or for invalid arguments.
+ */
+size_t tw_workspace_bytes(int32_t which, int32_t B, int32_t rows, int32_t H, int32_t d_h,
+                          int32_t max_rows);
+
+/*
+ * Pruning score (Sec. 3.1 Eq. 2 and Eq. 3; head mean as in Sec. 5.1 Eq. 7).
+ * For sequence b, the n_q[b] scoring rows are query rows at absolute positions
+ * q_pos0[b] .. q_pos0[b]+n_q[b]-1 (the last text rows).  Each row's attention
+ * is softmax_j(scale * q.k_j) over keys j <= its position (causal != 0) or over
+ * all n_tot[b] keys (causal == 0).  scores[b][m] is the mean over heads and
+ * scoring rows of the weight on visual key v_start + m.
+ *
+ *   q_sel   [dev] [B][n_q_max][H][d_h], same dtype as k
+ *   k       [host struct] contiguous view of the scoring layer's keys
+ *   n_q     [dev] [B] or NULL (= n_q_max for every sequence)
+ *   q_pos0  [dev] [B];  n_tot [dev] [B];  n_tot_max = host upper bound of n_tot
+ *   scores  [dev] [B][M] fp32 out
+ * Preconditions on device contents: 1 <= n_q[b] <= n_q_max,
+ * q_pos0[b] + n_q[b] <= n_tot[b] <= n_tot_max, v_start + M <= n_tot[b].
+ * Errors: INVALID_ARG for null pointers, negative sizes, v_start + M > n_tot_max,
+ * paged k view; UNSUPPORTED for d_h; WORKSPACE.
+ */
+int32_t tw_ttp_score(const void* q_sel, int32_t n_q_max, const int32_t* n_q, const int32_t* q_pos0,
+                     const tw_kv_view* k, const int32_t* n_tot, int32_t n_tot_max, int32_t B,
+                     int32_t v_start, int32_t M, float scale, int32_t causal, float* scores,
+                     void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Top-R keep (TopR of Sec. 3.1 Eq. 3).  kept[b] receives the indices of the R
+ * largest scores[b][.], ties toward the lower index, in ascending index order.
+ * -0.0 and +0.0 compare equal; scores must be finite.
+ *   scores [dev] [B][M] fp32;  kept [dev] [B][R] int32 out.
+ * R == M returns 0..M-1, R == 0 writes nothing.  Errors: INVALID_ARG for
+ * R < 0, R > M, null pointers with non-empty sizes; UNSUPPORTED for M > 2^20.
+ */
+int32_t tw_ttp_select(const float* scores, int32_t B, int32_t M, int32_t R, int32_t* kept,
+                      void* stream);
+
+/*
+ * Stable compaction (Sec. 3.1 Eq. 3, Sec. 4.2 Eq. 5: kept visual rows in their
+ * original order, then every text row; rows before the visual span are kept
+ * like text).  Destination row r takes source row
+ *   r                          for r < v_start,
+ *   v_start + kept[r-v_start]  for v_start <= r < v_start + R,
+ *   r - R + M                  otherwise,
+ * for each of n_tensors (src, dst) pairs with rows of row_bytes bytes; src has
+ * n_tot rows, dst has n_tot - M + R rows and must not overlap src.  R = 0 is
+ * FinalWipe (Sec. 4.2).
+ *   kept [dev] [R] ascending, values in [0, M);  src, dst [host] tables of
+ *   n_tensors device pointers.
+ * Errors: INVALID_ARG for null tables or entries, R > M, v_start + M > n_tot,
+ * row_bytes == 0.
+ */
+int32_t tw_ttp_compact(const int32_t* kept, int32_t R, int32_t v_start, int32_t M, int32_t n_tot,
+                       const void* const* src, void* const* dst, int32_t n_tensors,
+                       size_t row_bytes, void* stream);
+
+/*
+ * Ancestor-or-self bit masks of draft trees (tree attention, Sec. 5.4 and
+ * App. A).  Node 0 is the root (parent -1); parent[i] < i for i > 0.
+ *   parent [dev] [B][T_max];  n_nodes [dev] [B];  masks [dev] [B][T_max] uint64 out
+ * (entries past n_nodes[b] are written as 0).
+ */
+int32_t tw_tree_ancestor_masks(const int32_t* parent, const int32_t* n_nodes, int32_t T_max,
+                               int32_t B, uint64_t* masks, void* stream);
+
+/*
+ * Tree verification attention (Sec. 3.1 Eq. 2 under the topology-aware causal
+ * mask of Sec. 5.4 / App. A; verification step of Alg. 2).  For sequence b,
+ * tree row t and head h:
+ *   out[b][t][h][:] = sum_j softmax_j(scale * q[b][t][h].K[j][h]) * V[j][h][:]
+ * over the ctx_len[b] committed cache rows plus the tree rows of t's ancestors
+ * and t itself; tree row u's key/value sit at cache row ctx_len[b] + u.
+ *
+ *   q        [dev] [B][T_max][H][d_h], dtype of the views
+ *   k, v     [host structs] same dtype/H/d_h/paging mode
+ *   ctx_len  [dev] [B];  max_ctx_len = host upper bound
+ *   parent   [dev] [B][T_max];  n_nodes [dev] [B], 1 <= n_nodes[b] <= T_max
+ *   out      [dev] [B][T_max][H][d_h] fp32 (rows past n_nodes[b] are not written)
+ * Errors: INVALID_ARG, UNSUPPORTED (T_max > 64, d_h, view mismatch), WORKSPACE.
+ */
+int32_t tw_tree_verify_attn(const void* q, const tw_kv_view* k, const tw_kv_view* v,
+                            const int32_t* ctx_len, int32_t max_ctx_len, const int32_t* parent,
+                            const int32_t* n_nodes, int32_t T_max, int32_t B, float scale,
+                            float* out, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Greedy acceptance walk with bonus token (Sec. 5.4, App. A, last steps of
+ * Alg. 2; a chain is the sequence case of Alg. 1).  argmax[b][i] is the target
+ * model's prediction for the token after node i.  A non-root node is matched
+ * when draft[node] == argmax[parent[node]]; the accepted end point is the
+ * deepest node whose whole path from the root is matched (ties toward the
+ * lower node index; with distinct sibling tokens this is the walk from the
+ * root).  n_acc[b] = accepted draft nodes (root excluded), path[b][0..n_acc)
+ * = their node indices from the root side, remaining slots -1,
+ * bonus[b] = argmax at the end point.  All arrays [dev] int32.
+ */
+int32_t tw_tree_accept(const int32_t* draft, const int32_t* argmax, const int32_t* parent,
+                       const int32_t* n_nodes, int32_t T_max, int32_t B, int32_t* n_acc,
+                       int32_t* path, int32_t* bonus, void* stream);
+
+/* Host helper: TW_OK when parent[0] == -1 and 0 <= parent[i] < i for 0 < i < T <= 64. */
+int32_t tw_validate_tree(const int32_t* parent_host, int32_t T);
+
+/* Host helper: average retained visual tokens with FinalWipe (Sec. 4.2 Eq. 6;
+ * K_f = L gives Sec. 3.1 Eq. 4), rounded to the nearest integer. */
+int32_t tw_rbar(int32_t M, int32_t K, int32_t R, int32_t K_f, int32_t L);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TWIGPATH_H */

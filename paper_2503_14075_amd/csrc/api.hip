@@ -1,0 +1,218 @@
+// C-ABI entry points of libtwigpath: argument validation, launch planning and
+// dispatch.  Every call enqueues on the caller's stream and returns.
+#include "twig_internal.h"
+
+using namespace tw;
+
+namespace {
+
+bool dh_ok(int d_h) { return d_h >= 8 && d_h <= 128 && d_h % 8 == 0; }
+
+int view_status(const tw_kv_view* v, bool allow_paged) {
+    if (!v || !v->base || v->pool_rows <= 0 || v->H <= 0) return TW_ERR_INVALID_ARG;
+    if (v->dtype != TW_F32 && v->dtype != TW_BF16) return TW_ERR_UNSUPPORTED;
+    if (!dh_ok(v->d_h)) return TW_ERR_UNSUPPORTED;
+    if (v->page_table) {
+        if (!allow_paged || v->max_pages <= 0 || v->page_rows <= 0) return TW_ERR_INVALID_ARG;
+    } else if (!v->row_off) {
+        return TW_ERR_INVALID_ARG;
+    }
+    return TW_OK;
+}
+
+}  // namespace
+
+namespace tw {
+
+// Split the cache rows of each (sequence, head) over several workgroups until
+// the launch has about four workgroups per compute unit, but never below 64
+// rows per split.
+int verify_plan_splits(int B, int H, int T_max, int max_rows) {
+    (void)T_max;
+    const long pairs = (long)B * H;
+    if (pairs <= 0) return 1;
+    long want = (1024 + pairs - 1) / pairs;
+    long cap = max_rows / 64;
+    if (cap < 1) cap = 1;
+    if (cap > 64) cap = 64;
+    if (want > cap) want = cap;
+    return want < 1 ? 1 : (int)want;
+}
+
+size_t verify_workspace_bytes(int B, int H, int T_max, int d_h, int max_rows) {
+    const int ns = verify_plan_splits(B, H, T_max, max_rows);
+    if (ns == 1) return 0;
+    return (size_t)ns * B * H * T_max * (d_h + 2) * sizeof(float);
+}
+
+}  // namespace tw
+
+extern "C" {
+
+int32_t tw_version(void) { return 1000; }
+
+size_t tw_workspace_bytes(int32_t which, int32_t B, int32_t rows, int32_t H, int32_t d_h,
+                          int32_t max_rows) {
+    if (B <= 0 || rows <= 0 || H <= 0 || d_h <= 0 || max_rows <= 0) return 0;
+    if (which == TW_CALL_TTP_SCORE) return score_workspace_bytes(B, H, rows, max_rows);
+    if (which == TW_CALL_TREE_VERIFY_ATTN) return verify_workspace_bytes(B, H, rows, d_h, max_rows);
+    return 0;
+}
+
+int32_t tw_ttp_score(const void* q_sel, int32_t n_q_max, const int32_t* n_q, const int32_t* q_pos0,
+                     const tw_kv_view* k, const int32_t* n_tot, int32_t n_tot_max, int32_t B,
+                     int32_t v_start, int32_t M, float scale, int32_t causal, float* scores,
+                     void* ws, size_t ws_bytes, void* stream) {
+    if (B < 0 || M < 0 || n_q_max < 1 || n_tot_max < 1 || v_start < 0) return TW_ERR_INVALID_ARG;
+    if (B == 0 || M == 0) return TW_OK;
+    if (!q_sel || !q_pos0 || !n_tot || !scores) return TW_ERR_INVALID_ARG;
+    const int vs = view_status(k, false);
+    if (vs != TW_OK) return vs;
+    if ((int64_t)v_start + M > n_tot_max || n_q_max > n_tot_max) return TW_ERR_INVALID_ARG;
+    const size_t need = score_workspace_bytes(B, k->H, n_q_max, n_tot_max);
+    if (!ws || ws_bytes < need) return TW_ERR_WORKSPACE;
+    ScoreArgs a;
+    a.q_sel = q_sel;
+    a.k = to_dev(*k);
+    a.n_q = n_q;
+    a.q_pos0 = q_pos0;
+    a.n_tot = n_tot;
+    a.scores = scores;
+    a.ws = (float*)ws;
+    a.n_q_max = n_q_max;
+    a.n_tot_max = n_tot_max;
+    a.B = B;
+    a.H = k->H;
+    a.d_h = k->d_h;
+    a.v_start = v_start;
+    a.M = M;
+    a.causal = causal != 0;
+    a.scale = scale;
+    return launch_score(a, k->dtype, (hipStream_t)stream) == hipSuccess ? TW_OK : TW_ERR_LAUNCH;
+}
+
+int32_t tw_ttp_select(const float* scores, int32_t B, int32_t M, int32_t R, int32_t* kept,
+                      void* stream) {
+    if (B < 0 || M < 0 || R < 0 || R > M) return TW_ERR_INVALID_ARG;
+    if (M > (1 << 20)) return TW_ERR_UNSUPPORTED;
+    if (B == 0 || R == 0) return TW_OK;
+    if (!scores || !kept) return TW_ERR_INVALID_ARG;
+    return launch_select(scores, B, M, R, kept, (hipStream_t)stream) == hipSuccess ? TW_OK
+                                                                                   : TW_ERR_LAUNCH;
+}
+
+int32_t tw_ttp_compact(const int32_t* kept, int32_t R, int32_t v_start, int32_t M, int32_t n_tot,
+                       const void* const* src, void* const* dst, int32_t n_tensors,
+                       size_t row_bytes, void* stream) {
+    if (R < 0 || M < 0 || R > M || v_start < 0 || n_tot < 0 || n_tensors < 0) return TW_ERR_INVALID_ARG;
+    if ((int64_t)v_start + M > n_tot) return TW_ERR_INVALID_ARG;
+    if (n_tensors == 0) return TW_OK;
+    if (!src || !dst || row_bytes == 0 || (R > 0 && !kept)) return TW_ERR_INVALID_ARG;
+    for (int t = 0; t < n_tensors; ++t)
+        if (!src[t] || !dst[t]) return TW_ERR_INVALID_ARG;
+    for (int t0 = 0; t0 < n_tensors; t0 += kCompactMaxTensors) {
+        const int n = n_tensors - t0 < kCompactMaxTensors ? n_tensors - t0 : kCompactMaxTensors;
+        CompactTable tab;
+        for (int t = 0; t < kCompactMaxTensors; ++t) {
+            tab.src[t] = t < n ? src[t0 + t] : nullptr;
+            tab.dst[t] = t < n ? dst[t0 + t] : nullptr;
+        }
+        if (launch_compact(kept, R, v_start, M, n_tot, tab, n, row_bytes, (hipStream_t)stream) !=
+            hipSuccess)
+            return TW_ERR_LAUNCH;
+    }
+    return TW_OK;
+}
+
+int32_t tw_tree_ancestor_masks(const int32_t* parent, const int32_t* n_nodes, int32_t T_max,
+                               int32_t B, uint64_t* masks, void* stream) {
+    if (B < 0 || T_max < 1) return TW_ERR_INVALID_ARG;
+    if (T_max > TW_MAX_TREE) return TW_ERR_UNSUPPORTED;
+    if (B == 0) return TW_OK;
+    if (!parent || !n_nodes || !masks) return TW_ERR_INVALID_ARG;
+    return launch_ancestor_masks(parent, n_nodes, T_max, B, masks, (hipStream_t)stream) == hipSuccess
+               ? TW_OK
+               : TW_ERR_LAUNCH;
+}
+
+int32_t tw_tree_verify_attn(const void* q, const tw_kv_view* k, const tw_kv_view* v,
+                            const int32_t* ctx_len, int32_t max_ctx_len, const int32_t* parent,
+                            const int32_t* n_nodes, int32_t T_max, int32_t B, float scale,
+                            float* out, void* ws, size_t ws_bytes, void* stream) {
+    if (B < 0 || T_max < 1 || max_ctx_len < 0) return TW_ERR_INVALID_ARG;
+    if (T_max > TW_MAX_TREE) return TW_ERR_UNSUPPORTED;
+    if (B == 0) return TW_OK;
+    if (!q || !ctx_len || !parent || !n_nodes || !out) return TW_ERR_INVALID_ARG;
+    int vs = view_status(k, true);
+    if (vs != TW_OK) return vs;
+    vs = view_status(v, true);
+    if (vs != TW_OK) return vs;
+    if (k->dtype != v->dtype || k->H != v->H || k->d_h != v->d_h) return TW_ERR_UNSUPPORTED;
+    if ((k->page_table == nullptr) != (v->page_table == nullptr)) return TW_ERR_UNSUPPORTED;
+    const int64_t max_rows64 = (int64_t)max_ctx_len + T_max;
+    if (max_rows64 > (1ll << 30)) return TW_ERR_UNSUPPORTED;
+    const int max_rows = (int)max_rows64;
+    VerifyArgs a;
+    a.q = q;
+    a.out = out;
+    a.k = to_dev(*k);
+    a.v = to_dev(*v);
+    a.ctx_len = ctx_len;
+    a.parent = parent;
+    a.n_nodes = n_nodes;
+    a.T_max = T_max;
+    a.B = B;
+    a.H = k->H;
+    a.d_h = k->d_h;
+    a.max_rows = max_rows;
+    a.scale = scale;
+    a.n_splits = verify_plan_splits(B, a.H, T_max, max_rows);
+    a.part_o = nullptr;
+    a.part_ml = nullptr;
+    if (a.n_splits > 1) {
+        const size_t need = verify_workspace_bytes(B, a.H, T_max, a.d_h, max_rows);
+        if (!ws || ws_bytes < need) return TW_ERR_WORKSPACE;
+        a.part_o = (float*)ws;
+        a.part_ml = a.part_o + (size_t)a.n_splits * B * a.H * T_max * a.d_h;
+    }
+    hipStream_t s = (hipStream_t)stream;
+    hipError_t e;
+    if (verify_mfma_supported(a, k->dtype))
+        e = launch_verify_mfma(a, s);
+    else
+        e = launch_verify_generic(a, k->dtype, s);
+    if (e != hipSuccess) return TW_ERR_LAUNCH;
+    if (a.n_splits > 1 && launch_verify_combine(a, s) != hipSuccess) return TW_ERR_LAUNCH;
+    return TW_OK;
+}
+
+int32_t tw_tree_accept(const int32_t* draft, const int32_t* argmax, const int32_t* parent,
+                       const int32_t* n_nodes, int32_t T_max, int32_t B, int32_t* n_acc,
+                       int32_t* path, int32_t* bonus, void* stream) {
+    if (B < 0 || T_max < 1) return TW_ERR_INVALID_ARG;
+    if (T_max > TW_MAX_TREE) return TW_ERR_UNSUPPORTED;
+    if (B == 0) return TW_OK;
+    if (!draft || !argmax || !parent || !n_nodes || !n_acc || !path || !bonus) return TW_ERR_INVALID_ARG;
+    return launch_accept(draft, argmax, parent, n_nodes, T_max, B, n_acc, path, bonus,
+                         (hipStream_t)stream) == hipSuccess
+               ? TW_OK
+               : TW_ERR_LAUNCH;
+}
+
+int32_t tw_validate_tree(const int32_t* parent_host, int32_t T) {
+    if (!parent_host || T < 1) return TW_ERR_INVALID_ARG;
+    if (T > TW_MAX_TREE) return TW_ERR_UNSUPPORTED;
+    if (parent_host[0] != -1) return TW_ERR_INVALID_ARG;
+    for (int i = 1; i < T; ++i)
+        if (parent_host[i] < 0 || parent_host[i] >= i) return TW_ERR_INVALID_ARG;
+    return TW_OK;
+}
+
+int32_t tw_rbar(int32_t M, int32_t K, int32_t R, int32_t K_f, int32_t L) {
+    if (L <= 0) return -1;
+    const long num = (long)M * K + (long)R * (K_f - K);
+    // nearest integer of num / L for non-negative num: floor((2*num + L) / (2*L))
+    return (int32_t)((2 * num + L) / (2L * L));
+}
+
+}  // extern "C"

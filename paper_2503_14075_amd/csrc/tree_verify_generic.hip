@@ -1,0 +1,174 @@
+// Tree verification attention, generic path (fp32 or bf16 inputs, any
+// supported d_h): plain fp32 vector arithmetic with LDS-staged K/V tiles.
+// This is the path for fp32 caches and unusual head sizes; bf16 caches with
+// d_h 64/128 take the matrix-core kernel in tree_verify_mfma.hip.
+//
+// Work split: grid (H, B, n_splits).  A workgroup owns one (sequence, head)
+// and one contiguous range of cache rows; four lanes share a tree node (each
+// owns every fourth output column).  Softmax is the usual online form; when
+// the cache is split over several workgroups the unnormalised partial
+// (max, sum, output) triples go to the workspace and verify_combine_kernel
+// merges them in split order.
+#include "twig_internal.h"
+
+namespace tw {
+
+constexpr int kGenThreads = 256;
+constexpr int kGenTile = 16;
+
+template <typename TIn>
+__device__ __forceinline__ float ld_elem(const TIn* p);
+template <>
+__device__ __forceinline__ float ld_elem<float>(const float* p) { return *p; }
+template <>
+__device__ __forceinline__ float ld_elem<uint16_t>(const uint16_t* p) { return bf16_to_f32(*p); }
+
+template <typename TIn>
+__global__ __launch_bounds__(kGenThreads) void verify_generic_kernel(VerifyArgs a) {
+    extern __shared__ float smem[];
+    __shared__ int s_parent[TW_MAX_TREE];
+    __shared__ unsigned long long s_anc[TW_MAX_TREE];
+    const int d_h = a.d_h, ld = d_h + 1, cq = d_h / 4;
+    float* sQ = smem;                        // [64][ld]   pre-multiplied by scale
+    float* sK = sQ + TW_MAX_TREE * ld;       // [kGenTile][ld]
+    float* sV = sK + kGenTile * ld;          // [kGenTile][d_h]
+    float* sP = sV + kGenTile * d_h;         // [64][kGenTile + 1]
+    const int h = blockIdx.x, b = blockIdx.y, split = blockIdx.z;
+    const int tid = threadIdx.x;
+    int T = a.n_nodes[b];
+    T = T < 1 ? 1 : (T > a.T_max ? a.T_max : T);
+    int C = a.ctx_len[b];
+    C = C < 0 ? 0 : (C > a.max_rows - a.T_max ? a.max_rows - a.T_max : C);
+    const int n_rows = C + T;
+    // rows of this split: equal shares rounded up to whole tiles
+    int per = (n_rows + a.n_splits - 1) / a.n_splits;
+    per = (per + kGenTile - 1) / kGenTile * kGenTile;
+    const int r_begin = min(split * per, n_rows), r_end = min(r_begin + per, n_rows);
+
+    if (tid < TW_MAX_TREE) s_parent[tid] = tid < T ? a.parent[(int64_t)b * a.T_max + tid] : 0;
+    __syncthreads();
+    if (tid < TW_MAX_TREE) s_anc[tid] = tid < T ? ancestor_mask(s_parent, tid) : 0ull;
+    const TIn* q = (const TIn*)a.q;
+    for (int idx = tid; idx < TW_MAX_TREE * d_h; idx += kGenThreads) {
+        const int t = idx / d_h, c = idx % d_h;
+        sQ[t * ld + c] =
+            t < T ? a.scale * ld_elem<TIn>(q + (((int64_t)b * a.T_max + t) * a.H + h) * d_h + c) : 0.f;
+    }
+    __syncthreads();
+
+    const int t = tid >> 2, qd = tid & 3;   // node, column phase
+    const uint64_t anc = s_anc[t];
+    float run_m = -INFINITY, run_l = 0.f;   // run_l: this lane's share of the row sum
+    float o[32];
+#pragma unroll
+    for (int cc = 0; cc < 32; ++cc) o[cc] = 0.f;
+    const TIn* kb = (const TIn*)a.k.base;
+    const TIn* vb = (const TIn*)a.v.base;
+
+    for (int base = r_begin; base < r_end; base += kGenTile) {
+        __syncthreads();
+        for (int idx = tid; idx < kGenTile * d_h; idx += kGenThreads) {
+            const int r = idx / d_h, c = idx % d_h;
+            float kv = 0.f, vv = 0.f;
+            if (base + r < r_end) {
+                kv = ld_elem<TIn>(kb + (pool_row(a.k, b, base + r) * a.H + h) * d_h + c);
+                vv = ld_elem<TIn>(vb + (pool_row(a.v, b, base + r) * a.H + h) * d_h + c);
+            }
+            sK[r * ld + c] = kv;
+            sV[r * d_h + c] = vv;
+        }
+        __syncthreads();
+        float s[4], tile_m = -INFINITY;
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+            const int jr = qd + 4 * jj, r = base + jr;
+            float dot = 0.f;
+            for (int c = 0; c < d_h; ++c) dot = fmaf(sQ[t * ld + c], sK[jr * ld + c], dot);
+            const bool vis = r < r_end && (r < C || ((anc >> (r - C)) & 1ull));
+            s[jj] = vis ? dot : -INFINITY;
+            tile_m = fmaxf(tile_m, s[jj]);
+        }
+        tile_m = fmaxf(tile_m, __shfl_xor(tile_m, 1, 64));
+        tile_m = fmaxf(tile_m, __shfl_xor(tile_m, 2, 64));
+        const float m_new = fmaxf(run_m, tile_m);
+        const float alpha = m_new == -INFINITY ? 1.f : expf(run_m - m_new);   // exp(-inf) = 0 on first hit
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+            const float p = s[jj] == -INFINITY ? 0.f : expf(s[jj] - m_new);
+            sP[t * (kGenTile + 1) + qd + 4 * jj] = p;
+            run_l = (jj == 0 ? run_l * alpha : run_l) + p;
+        }
+        run_m = m_new;
+        __syncthreads();
+#pragma unroll
+        for (int cc = 0; cc < 32; ++cc) o[cc] *= alpha;
+        for (int jr = 0; jr < kGenTile; ++jr) {
+            const float p = sP[t * (kGenTile + 1) + jr];
+#pragma unroll
+            for (int cc = 0; cc < 32; ++cc)
+                if (cc < cq) o[cc] = fmaf(p, sV[jr * d_h + qd + 4 * cc], o[cc]);
+        }
+    }
+    float l = run_l;
+    l += __shfl_xor(l, 1, 64);
+    l += __shfl_xor(l, 2, 64);
+    if (t >= T) return;
+    if (a.n_splits == 1) {
+        float* out = a.out + (((int64_t)b * a.T_max + t) * a.H + h) * d_h;
+        const float inv = 1.f / l;
+#pragma unroll
+        for (int cc = 0; cc < 32; ++cc)
+            if (cc < cq) out[qd + 4 * cc] = o[cc] * inv;
+    } else {
+        const int64_t slot = (((int64_t)split * a.B + b) * a.H + h) * a.T_max + t;
+        float* po = a.part_o + slot * d_h;
+#pragma unroll
+        for (int cc = 0; cc < 32; ++cc)
+            if (cc < cq) po[qd + 4 * cc] = o[cc];
+        if (qd == 0) {
+            a.part_ml[slot * 2] = run_m;
+            a.part_ml[slot * 2 + 1] = l;
+        }
+    }
+}
+
+// Merge the per-split partial results in split order.  grid (T_max, H, B), d_h lanes.
+__global__ void verify_combine_kernel(VerifyArgs a) {
+    const int t = blockIdx.x, h = blockIdx.y, b = blockIdx.z, c = threadIdx.x;
+    int T = a.n_nodes[b];
+    T = T < 1 ? 1 : (T > a.T_max ? a.T_max : T);
+    if (t >= T || c >= a.d_h) return;
+    float m = -INFINITY;
+    for (int s = 0; s < a.n_splits; ++s) {
+        const int64_t slot = (((int64_t)s * a.B + b) * a.H + h) * a.T_max + t;
+        m = fmaxf(m, a.part_ml[slot * 2]);
+    }
+    float l = 0.f, acc = 0.f;
+    for (int s = 0; s < a.n_splits; ++s) {
+        const int64_t slot = (((int64_t)s * a.B + b) * a.H + h) * a.T_max + t;
+        const float ms = a.part_ml[slot * 2];
+        if (ms == -INFINITY) continue;   // a split in which this node saw no key
+        const float w = expf(ms - m);
+        l += a.part_ml[slot * 2 + 1] * w;
+        acc += a.part_o[slot * a.d_h + c] * w;
+    }
+    a.out[(((int64_t)b * a.T_max + t) * a.H + h) * a.d_h + c] = acc / l;
+}
+
+hipError_t launch_verify_generic(const VerifyArgs& a, int dtype, hipStream_t s) {
+    const dim3 grid(a.H, a.B, a.n_splits);
+    const size_t lds = ((size_t)TW_MAX_TREE * (a.d_h + 1) + (size_t)kGenTile * (a.d_h + 1) +
+                        (size_t)kGenTile * a.d_h + (size_t)TW_MAX_TREE * (kGenTile + 1)) * sizeof(float);
+    if (dtype == TW_F32)
+        hipLaunchKernelGGL(verify_generic_kernel<float>, grid, dim3(kGenThreads), lds, s, a);
+    else
+        hipLaunchKernelGGL(verify_generic_kernel<uint16_t>, grid, dim3(kGenThreads), lds, s, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_verify_combine(const VerifyArgs& a, hipStream_t s) {
+    hipLaunchKernelGGL(verify_combine_kernel, dim3(a.T_max, a.H, a.B), dim3(a.d_h), 0, s, a);
+    return hipGetLastError();
+}
+
+}  // namespace tw

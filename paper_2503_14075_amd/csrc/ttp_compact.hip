@@ -1,0 +1,66 @@
+// Stable compaction of hidden-state and KV rows after token pruning
+// (Sec. 3.1 Eq. 3, Sec. 4.2 Eq. 5; R = 0 is FinalWipe).  A pure row gather:
+// one workgroup moves one destination row of one tensor with 16-byte lanes,
+// one launch covers every tensor of the pointer table.
+#include "twig_internal.h"
+
+namespace tw {
+
+constexpr int kCompactThreads = 256;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+
+__device__ __forceinline__ int compact_src_row(const int32_t* kept, int R, int v_start, int M, int r) {
+    if (r < v_start) return r;
+    if (r < v_start + R) {
+        int m = kept[r - v_start];
+        m = m < 0 ? 0 : (m >= M ? M - 1 : m);
+        return v_start + m;
+    }
+    return r - R + M;
+}
+
+template <bool kVec16>
+__global__ __launch_bounds__(kCompactThreads) void compact_kernel(const int32_t* __restrict__ kept,
+                                                                  int R, int v_start, int M,
+                                                                  CompactTable tab,
+                                                                  size_t row_bytes) {
+    const int r = blockIdx.x;
+    const int sr = compact_src_row(kept, R, v_start, M, r);
+    const char* src = (const char*)tab.src[blockIdx.y] + (size_t)sr * row_bytes;
+    char* dst = (char*)tab.dst[blockIdx.y] + (size_t)r * row_bytes;
+    if (kVec16) {
+        const u32x4* s4 = (const u32x4*)src;
+        u32x4* d4 = (u32x4*)dst;
+        const size_t n = row_bytes >> 4;
+        // two independent 16-byte loads in flight per lane
+        size_t i = threadIdx.x;
+        for (; i + kCompactThreads < n; i += 2 * kCompactThreads) {
+            const u32x4 a = __builtin_nontemporal_load(s4 + i);
+            const u32x4 c = __builtin_nontemporal_load(s4 + i + kCompactThreads);
+            __builtin_nontemporal_store(a, d4 + i);
+            __builtin_nontemporal_store(c, d4 + i + kCompactThreads);
+        }
+        if (i < n) __builtin_nontemporal_store(__builtin_nontemporal_load(s4 + i), d4 + i);
+    } else {
+        for (size_t i = threadIdx.x; i < row_bytes; i += kCompactThreads) dst[i] = src[i];
+    }
+}
+
+hipError_t launch_compact(const int32_t* kept, int R, int v_start, int M, int n_tot,
+                          const CompactTable& tab, int n_tensors, size_t row_bytes, hipStream_t s) {
+    const int n_out = n_tot - M + R;
+    if (n_out <= 0 || n_tensors <= 0) return hipSuccess;
+    bool vec = (row_bytes % 16) == 0;
+    for (int t = 0; t < n_tensors; ++t)
+        vec = vec && ((uintptr_t)tab.src[t] % 16 == 0) && ((uintptr_t)tab.dst[t] % 16 == 0);
+    dim3 grid(n_out, n_tensors);
+    if (vec)
+        hipLaunchKernelGGL(compact_kernel<true>, grid, dim3(kCompactThreads), 0, s, kept, R, v_start, M,
+                           tab, row_bytes);
+    else
+        hipLaunchKernelGGL(compact_kernel<false>, grid, dim3(kCompactThreads), 0, s, kept, R, v_start,
+                           M, tab, row_bytes);
+    return hipGetLastError();
+}
+
+}  // namespace tw

@@ -1,0 +1,118 @@
+// Internal declarations shared by the HIP translation units of libtwigpath.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "twigpath.h"
+
+namespace tw {
+
+// Device-side copy of a tw_kv_view.
+struct KvDev {
+    const void* base;
+    const int32_t* row_off;
+    const int32_t* page_table;
+    int64_t pool_rows;
+    int32_t max_pages, page_rows;
+    int32_t H, d_h;
+};
+
+inline KvDev to_dev(const tw_kv_view& v) {
+    KvDev d;
+    d.base = v.base;
+    d.row_off = v.row_off;
+    d.page_table = v.page_table;
+    d.pool_rows = v.pool_rows;
+    d.max_pages = v.max_pages;
+    d.page_rows = v.page_rows > 0 ? v.page_rows : 1;
+    d.H = v.H;
+    d.d_h = v.d_h;
+    return d;
+}
+
+// Pool row of cache row r of sequence b, clamped into the pool.
+__device__ __forceinline__ int64_t pool_row(const KvDev& kv, int b, int r) {
+    int64_t row;
+    if (kv.page_table) {
+        int pi = r / kv.page_rows;
+        pi = pi < kv.max_pages ? pi : kv.max_pages - 1;
+        row = (int64_t)kv.page_table[(int64_t)b * kv.max_pages + pi] * kv.page_rows + (r % kv.page_rows);
+    } else {
+        row = (int64_t)kv.row_off[b] + r;
+    }
+    row = row < 0 ? 0 : row;
+    return row < kv.pool_rows ? row : kv.pool_rows - 1;
+}
+
+__device__ __forceinline__ float bf16_to_f32(uint16_t x) { return __uint_as_float((uint32_t)x << 16); }
+
+// Ancestor-or-self mask of node i from a parent array held in shared memory.
+// Parents are clamped to [0, i) so the walk always ends at the root.
+__device__ __forceinline__ uint64_t ancestor_mask(const int* s_parent, int i) {
+    uint64_t m = 1ull << i;
+    int u = i;
+    while (u > 0) {
+        int p = s_parent[u];
+        p = p < 0 ? 0 : (p >= u ? u - 1 : p);
+        m |= 1ull << p;
+        u = p;
+    }
+    return m;
+}
+
+// --- verification attention -------------------------------------------------
+struct VerifyArgs {
+    const void* q;
+    float* out;
+    KvDev k, v;
+    const int32_t* ctx_len;
+    const int32_t* parent;
+    const int32_t* n_nodes;
+    float* part_o;   // [n_splits][B][H][T_max][d_h] unnormalised partial outputs
+    float* part_ml;  // [n_splits][B][H][T_max][2] running max, running sum
+    int32_t T_max, B, H, d_h;
+    int32_t n_splits, max_rows;
+    float scale;
+};
+
+int verify_plan_splits(int B, int H, int T_max, int max_rows);
+size_t verify_workspace_bytes(int B, int H, int T_max, int d_h, int max_rows);
+hipError_t launch_verify_generic(const VerifyArgs& a, int dtype, hipStream_t s);
+bool verify_mfma_supported(const VerifyArgs& a, int dtype);
+hipError_t launch_verify_mfma(const VerifyArgs& a, hipStream_t s);
+hipError_t launch_verify_combine(const VerifyArgs& a, hipStream_t s);
+
+// --- pruning score -----------------------------------------------------------
+struct ScoreArgs {
+    const void* q_sel;
+    KvDev k;
+    const int32_t* n_q;
+    const int32_t* q_pos0;
+    const int32_t* n_tot;
+    float* scores;
+    float* ws;
+    int32_t n_q_max, n_tot_max, B, H, d_h, v_start, M, causal;
+    float scale;
+};
+size_t score_workspace_bytes(int B, int H, int n_q_max, int n_tot_max);
+hipError_t launch_score(const ScoreArgs& a, int dtype, hipStream_t s);
+
+// --- select / compact / tree -------------------------------------------------
+hipError_t launch_select(const float* scores, int B, int M, int R, int32_t* kept, hipStream_t s);
+
+constexpr int kCompactMaxTensors = 64;
+struct CompactTable {
+    const void* src[kCompactMaxTensors];
+    void* dst[kCompactMaxTensors];
+};
+hipError_t launch_compact(const int32_t* kept, int R, int v_start, int M, int n_tot,
+                          const CompactTable& tab, int n_tensors, size_t row_bytes, hipStream_t s);
+
+hipError_t launch_ancestor_masks(const int32_t* parent, const int32_t* n_nodes, int T_max, int B,
+                                 uint64_t* masks, hipStream_t s);
+hipError_t launch_accept(const int32_t* draft, const int32_t* argmax, const int32_t* parent,
+                         const int32_t* n_nodes, int T_max, int B, int32_t* n_acc, int32_t* path,
+                         int32_t* bonus, hipStream_t s);
+
+}  // namespace tw

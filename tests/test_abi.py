@@ -1,0 +1,114 @@
+"""The C-ABI library loads, exports every symbol the header declares, and its
+argument validation returns the documented status without launching anything.
+CPU only (no compute call reaches a kernel here)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2503_14075_amd import binding as tw
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "twigpath.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(tw_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported():
+    names = _declared_symbols()
+    assert set(names) == set(tw.EXPORTS)
+    lib = ctypes.CDLL(tw.LIB_PATH)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_host_helpers():
+    assert tw.version() >= 1000
+    assert tw.validate_tree([-1]) == tw.TW_OK
+    assert tw.validate_tree([-1, 0, 1, 1, 0]) == tw.TW_OK
+    assert tw.validate_tree([0, 0]) == tw.TW_ERR_INVALID_ARG
+    assert tw.validate_tree([-1, 1]) == tw.TW_ERR_INVALID_ARG
+    assert tw.validate_tree([-1, -1]) == tw.TW_ERR_INVALID_ARG
+    assert tw.validate_tree([-1] + [0] * 64) == tw.TW_ERR_UNSUPPORTED
+    rows = [ln.split() for ln in open(os.path.join(ROOT, "tests", "golden", "rbar_table.txt"))
+            if ln.strip() and not ln.startswith("#")]
+    for M, K, R, K_f, L, want in (map(int, r) for r in rows):
+        assert tw.rbar(M, K, R, K_f, L) == want
+
+
+def test_workspace_sizes():
+    # one sequence, 32 heads: the 282-row cache is split, partials need room
+    n = tw.workspace_bytes(tw.TW_CALL_TREE_VERIFY_ATTN, 1, 26, 32, 128, 282)
+    assert n > 0 and n % (32 * 26 * 130 * 4) == 0
+    # 128 sequences fill the chip without splitting
+    assert tw.workspace_bytes(tw.TW_CALL_TREE_VERIFY_ATTN, 128, 26, 32, 128, 282) == 0
+    assert tw.workspace_bytes(tw.TW_CALL_TTP_SCORE, 1, 64, 32, 128, 640) >= 32 * 64 * 640 * 4
+    assert tw.workspace_bytes(99, 1, 1, 1, 8, 1) == 0
+    assert tw.workspace_bytes(tw.TW_CALL_TTP_SCORE, 0, 64, 32, 128, 640) == 0
+
+
+def _view(base=0x1000, dtype=tw.TW_BF16, H=32, d_h=128, rows=1000, row_off=0x2000, pt=None,
+          max_pages=0, page_rows=0):
+    return tw.KvView(base, dtype, H, d_h, rows, row_off, pt, max_pages, page_rows)
+
+
+def test_argument_validation_without_launch():
+    lib = tw.raw()
+    P = 0x1000     # never dereferenced: every call below is rejected before any launch
+    assert lib.tw_ttp_select(P, 1, 10, 11, P, None) == tw.TW_ERR_INVALID_ARG
+    assert lib.tw_ttp_select(P, 1, 10, -1, P, None) == tw.TW_ERR_INVALID_ARG
+    assert lib.tw_ttp_select(None, 1, 10, 5, P, None) == tw.TW_ERR_INVALID_ARG
+    assert lib.tw_ttp_select(P, 1, (1 << 20) + 1, 5, P, None) == tw.TW_ERR_UNSUPPORTED
+    assert lib.tw_ttp_select(P, 0, 10, 5, P, None) == tw.TW_OK          # empty batch
+    assert lib.tw_ttp_select(P, 3, 10, 0, None, None) == tw.TW_OK       # nothing kept
+
+    vp2 = (ctypes.c_void_p * 2)(P, P)
+    assert lib.tw_ttp_compact(P, 5, 0, 4, 10, vp2, vp2, 2, 64, None) == tw.TW_ERR_INVALID_ARG    # R > M
+    assert lib.tw_ttp_compact(P, 2, 8, 4, 10, vp2, vp2, 2, 64, None) == tw.TW_ERR_INVALID_ARG    # span past end
+    assert lib.tw_ttp_compact(P, 2, 0, 4, 10, vp2, vp2, 2, 0, None) == tw.TW_ERR_INVALID_ARG     # empty rows
+    assert lib.tw_ttp_compact(None, 2, 0, 4, 10, vp2, vp2, 2, 64, None) == tw.TW_ERR_INVALID_ARG
+    bad = (ctypes.c_void_p * 2)(P, None)
+    assert lib.tw_ttp_compact(P, 2, 0, 4, 10, bad, vp2, 2, 64, None) == tw.TW_ERR_INVALID_ARG
+    assert lib.tw_ttp_compact(P, 2, 0, 4, 10, vp2, vp2, 0, 64, None) == tw.TW_OK
+
+    assert lib.tw_tree_accept(P, P, P, P, 65, 1, P, P, P, None) == tw.TW_ERR_UNSUPPORTED
+    assert lib.tw_tree_accept(P, P, P, P, 0, 1, P, P, P, None) == tw.TW_ERR_INVALID_ARG
+    assert lib.tw_tree_accept(P, None, P, P, 8, 1, P, P, P, None) == tw.TW_ERR_INVALID_ARG
+    assert lib.tw_tree_ancestor_masks(P, P, 65, 1, P, None) == tw.TW_ERR_UNSUPPORTED
+    assert lib.tw_tree_ancestor_masks(P, None, 8, 1, P, None) == tw.TW_ERR_INVALID_ARG
+
+    f = ctypes.c_float(0.1)
+    k, v = _view(), _view()
+    call = lambda **kw: lib.tw_tree_verify_attn(
+        kw.get("q", P), ctypes.byref(kw.get("k", k)), ctypes.byref(kw.get("v", v)), P,
+        kw.get("max_ctx", 256), P, P, kw.get("T", 26), kw.get("B", 1), f, P, kw.get("ws", None),
+        kw.get("ws_bytes", 0), None)
+    assert call(T=65) == tw.TW_ERR_UNSUPPORTED
+    assert call(T=0) == tw.TW_ERR_INVALID_ARG
+    assert call(q=None) == tw.TW_ERR_INVALID_ARG
+    assert call(k=_view(d_h=100)) == tw.TW_ERR_UNSUPPORTED
+    assert call(k=_view(d_h=256)) == tw.TW_ERR_UNSUPPORTED
+    assert call(k=_view(dtype=7)) == tw.TW_ERR_UNSUPPORTED
+    assert call(v=_view(H=16)) == tw.TW_ERR_UNSUPPORTED                 # views disagree
+    assert call(v=_view(dtype=tw.TW_F32)) == tw.TW_ERR_UNSUPPORTED
+    assert call(k=_view(row_off=None)) == tw.TW_ERR_INVALID_ARG         # neither offsets nor pages
+    assert call(k=_view(pt=P, max_pages=0, page_rows=16)) == tw.TW_ERR_INVALID_ARG
+    assert call() == tw.TW_ERR_WORKSPACE                                 # split launch, no workspace
+    assert call(ws=P, ws_bytes=16) == tw.TW_ERR_WORKSPACE
+    assert call(B=0) == tw.TW_OK
+
+    sc = lambda **kw: lib.tw_ttp_score(
+        kw.get("q", P), kw.get("n_q_max", 64), P, P, ctypes.byref(kw.get("k", k)), P,
+        kw.get("n_tot_max", 640), kw.get("B", 1), kw.get("v_start", 0), kw.get("M", 576), f, 1, P,
+        kw.get("ws", None), kw.get("ws_bytes", 0), None)
+    assert sc(M=700) == tw.TW_ERR_INVALID_ARG                           # span longer than the sequence
+    assert sc(v_start=100) == tw.TW_ERR_INVALID_ARG
+    assert sc(n_q_max=0) == tw.TW_ERR_INVALID_ARG
+    assert sc(q=None) == tw.TW_ERR_INVALID_ARG
+    assert sc(k=_view(pt=P, max_pages=4, page_rows=16)) == tw.TW_ERR_INVALID_ARG   # paged keys not taken
+    assert sc() == tw.TW_ERR_WORKSPACE
+    assert sc(M=0) == tw.TW_OK

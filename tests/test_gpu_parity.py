@@ -1,0 +1,363 @@
+"""Parity of the HIP path with the CPU oracle, element by element, on the same
+seeded inputs.  Every call goes through the C ABI (binding -> libtwigpath.so).
+
+Bars: indices, compaction and acceptance results bit-exact; attention outputs
+within 2e-3 max-abs (bf16 inputs, fp32 accumulation); pruning scores within
+1e-6 absolute (they are O(1/n_tot)).
+"""
+import math
+
+import pytest
+import torch
+
+import oracle
+from paper_2503_14075_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+ATTN_TOL = 2e-3
+SCORE_TOL = 1e-6
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module")
+def tw():
+    from paper_2503_14075_amd import binding
+    return binding
+
+
+@pytest.fixture(scope="module")
+def runner():
+    from paper_2503_14075_amd import runner
+    return runner
+
+
+def _i32(x):
+    return torch.tensor(x, dtype=torch.int32, device=DEV)
+
+
+# ----------------------------------------------------------------------------
+# helpers that run one call on the GPU from host tensors
+# ----------------------------------------------------------------------------
+def gpu_verify(tw, q, k, v, ctx_len, n_nodes, parents, scale, row_off=None, page_table=None,
+               page_rows=16):
+    B, T_max, H, d_h = q.shape
+    qd, kd, vd = q.to(DEV), k.to(DEV), v.to(DEV)
+    ro = None if row_off is None else _i32(row_off)
+    pt = None if page_table is None else _i32(page_table)
+    kv, vv = tw.kv_view(kd, ro, pt, page_rows), tw.kv_view(vd, ro, pt, page_rows)
+    max_ctx = max(ctx_len)
+    nbytes = tw.workspace_bytes(tw.TW_CALL_TREE_VERIFY_ATTN, B, T_max, H, d_h, max_ctx + T_max)
+    ws = torch.empty(max(nbytes, 4) // 4, dtype=torch.float32, device=DEV) if nbytes else None
+    out = torch.full((B, T_max, H, d_h), float("nan"), dtype=torch.float32, device=DEV)
+    tw.tree_verify_attn(qd, kv, vv, _i32(ctx_len), max_ctx, _i32(parents), _i32(n_nodes), scale, out, ws)
+    torch.cuda.synchronize()
+    return out.cpu()
+
+
+def check_verify(tw, q, k, v, ctx_len, n_nodes, parents, scale, tol=ATTN_TOL, **kw):
+    got = gpu_verify(tw, q, k, v, ctx_len, n_nodes, parents, scale, **kw)
+    want = oracle.tree_verify_attn(q, k, v, ctx_len, n_nodes, parents, scale, **kw)
+    worst = 0.0
+    for b, T in enumerate(n_nodes):
+        g, w_ = got[b, :T].double(), want[b, :T]
+        assert torch.isfinite(g).all(), f"non-finite output in instance {b}"
+        worst = max(worst, float((g - w_).abs().max()))
+        if T < got.shape[1]:
+            assert torch.isnan(got[b, T:]).all(), "rows past n_nodes must not be written"
+    assert worst <= tol, f"max-abs error {worst:.3e} > {tol}"
+    return worst
+
+
+def make_case(seed, B, H, d_h, ctx_len, T_max, dtype, trees, kv_std=0.5, q_std=None, gap=3):
+    q_std = 1.0 / math.sqrt(d_h) if q_std is None else q_std
+    rows = [c + T_max for c in ctx_len]
+    off, acc = [], gap
+    for r in rows:
+        off.append(acc)
+        acc += r + gap
+    q = W.normal(seed, 1, (B, T_max, H, d_h), q_std, dtype)
+    k = W.normal(seed, 2, (acc, H, d_h), kv_std, dtype)
+    v = W.normal(seed, 3, (acc, H, d_h), kv_std, dtype)
+    return q, k, v, off
+
+
+def padded(trees, T_max):
+    return [t + [0] * (T_max - len(t)) for t in trees]
+
+
+# ----------------------------------------------------------------------------
+# tree_verify_attn
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("T", [1, 2, 26, 31, 32, 33, 63, 64])
+def test_verify_tree_sizes_bf16(tw, T):
+    B, H, d_h = 3, 8, 128
+    ctx = [70, 1, 257]
+    trees = [W.random_parent_tree(W.HostRng(T, b), T, 6) for b in range(B)]
+    q, k, v, off = make_case(100 + T, B, H, d_h, ctx, T, torch.bfloat16, trees)
+    check_verify(tw, q, k, v, ctx, [T] * B, trees, 1 / math.sqrt(d_h), row_off=off)
+
+
+@pytest.mark.parametrize("shape", ["chain", "star", "root_only_ctx0"])
+def test_verify_degenerate_trees(tw, shape):
+    H, d_h, T = 4, 128, 17
+    if shape == "chain":
+        trees, ctx = [[-1] + list(range(T - 1))], [45]
+    elif shape == "star":
+        trees, ctx = [[-1] + [0] * (T - 1)], [45]
+    else:
+        trees, ctx = [W.random_parent_tree(W.HostRng(3, 3), T, 4)], [0]     # empty context
+    q, k, v, off = make_case(7, 1, H, d_h, ctx, T, torch.bfloat16, trees)
+    check_verify(tw, q, k, v, ctx, [T], trees, 1 / math.sqrt(d_h), row_off=off)
+
+
+def test_verify_ragged_nodes_and_odd_head_count(tw):
+    # n_nodes differs per sequence, H is not a multiple of the 4 heads a workgroup takes
+    B, H, d_h, T_max = 4, 6, 128, 40
+    n_nodes = [40, 1, 33, 7]
+    ctx = [100, 300, 0, 31]
+    trees = [W.random_parent_tree(W.HostRng(11, b), n, 5) for b, n in enumerate(n_nodes)]
+    q, k, v, off = make_case(12, B, H, d_h, ctx, T_max, torch.bfloat16, trees)
+    check_verify(tw, q, k, v, ctx, n_nodes, padded(trees, T_max), 1 / math.sqrt(d_h), row_off=off)
+
+
+def test_verify_split_cache_single_sequence(tw):
+    # one sequence, long context: the cache is split over workgroups and merged
+    H, d_h, T = 32, 128, 26
+    for ctx in ([256], [2050]):
+        trees = [W.fanout_tree(W.HostRng(1, 1), T, (4, 3, 2, 1, 1))]
+        q, k, v, off = make_case(13, 1, H, d_h, ctx, T, torch.bfloat16, trees)
+        assert tw.workspace_bytes(tw.TW_CALL_TREE_VERIFY_ATTN, 1, T, H, d_h, ctx[0] + T) > 0
+        check_verify(tw, q, k, v, ctx, [T], trees, 1 / math.sqrt(d_h), row_off=off)
+
+
+def test_verify_sharp_softmax(tw):
+    # logits with std ~4: the running maximum moves and a few keys dominate
+    H, d_h, T = 8, 128, 32
+    ctx = [500, 90]
+    trees = [W.random_parent_tree(W.HostRng(21, b), T, 5) for b in range(2)]
+    q, k, v, off = make_case(22, 2, H, d_h, ctx, T, torch.bfloat16, trees, kv_std=1.0, q_std=4.0)
+    check_verify(tw, q, k, v, ctx, [T] * 2, trees, 1 / math.sqrt(d_h), row_off=off)
+    # keys sorted by increasing logit force a rescale in every chunk
+    k[:, :, :] = 0
+    k[:, :, 0] = (torch.arange(k.shape[0]) % 600).to(torch.bfloat16)[:, None] * 0.0625
+    q[:, :, :, 0] = 8.0
+    check_verify(tw, q, k, v, ctx, [T] * 2, trees, 1 / math.sqrt(d_h), row_off=off)
+
+
+@pytest.mark.parametrize("d_h,dtype", [(64, torch.bfloat16), (64, torch.float32), (128, torch.float32),
+                                       (8, torch.float32), (40, torch.bfloat16)])
+def test_verify_other_head_sizes_and_fp32(tw, d_h, dtype):
+    B, H, T = 2, 4, 20
+    ctx = [97, 16]
+    trees = [W.random_parent_tree(W.HostRng(31, b), T, 4) for b in range(B)]
+    q, k, v, off = make_case(32, B, H, d_h, ctx, T, dtype, trees, kv_std=1.0, q_std=1.0)
+    tol = ATTN_TOL if dtype == torch.bfloat16 else 2e-5
+    check_verify(tw, q, k, v, ctx, [T] * B, trees, 1 / math.sqrt(d_h), tol=tol, row_off=off)
+
+
+def test_verify_paged_pool(tw):
+    B, H, d_h, T, pr = 5, 8, 128, 32, 16
+    cfg = W.replicate(W.CONFIGS["cfg3"], B)
+    cfg = W.Config(**{**cfg.__dict__, "H": H, "hidden": H * d_h})
+    w = W.make_workload(cfg, with_compact=False, with_score=False)
+    check_verify(tw, w.q_tree, w.k_pool, w.v_pool, w.ctx_len, w.n_nodes, w.parent, cfg.scale,
+                 page_table=w.page_table, page_rows=pr)
+
+
+def test_verify_is_deterministic(tw):
+    H, d_h, T = 32, 128, 26
+    trees = [W.fanout_tree(W.HostRng(1, 1), T, (4, 3, 2, 1, 1))]
+    q, k, v, off = make_case(14, 1, H, d_h, [700], T, torch.bfloat16, trees)
+    a = gpu_verify(tw, q, k, v, [700], [T], trees, 0.1, row_off=off)
+    b = gpu_verify(tw, q, k, v, [700], [T], trees, 0.1, row_off=off)
+    assert torch.equal(a, b)
+
+
+# ----------------------------------------------------------------------------
+# ancestor masks / tree_accept
+# ----------------------------------------------------------------------------
+def test_ancestor_masks_bit_exact(tw):
+    T_max = 64
+    trees, n_nodes = [], []
+    for s in range(40):
+        n = [1, 2, 63, 64][s % 4] if s < 8 else W.HostRng(s, 0).randint(1, 64)
+        trees.append(W.random_parent_tree(W.HostRng(s, 1), n, 1 + s % 9))
+        n_nodes.append(n)
+    trees.append([-1] + list(range(63)))
+    n_nodes.append(64)
+    masks = torch.zeros(len(trees), T_max, dtype=torch.int64, device=DEV)
+    tw.tree_ancestor_masks(_i32(padded(trees, T_max)), _i32(n_nodes), masks)
+    got = masks.cpu()
+    for b, t in enumerate(trees):
+        want = oracle.tree_ancestors(t) + [0] * (T_max - len(t))
+        assert [int(x) & ((1 << 64) - 1) for x in got[b].tolist()] == want
+
+
+def _check_accept(tw, draft, argmx, trees, n_nodes, T_max):
+    B = len(trees)
+    d, a, p, n = _i32(padded(draft, T_max)), _i32(padded(argmx, T_max)), _i32(padded(trees, T_max)), _i32(n_nodes)
+    n_acc = torch.full((B,), -7, dtype=torch.int32, device=DEV)
+    path = torch.full((B, T_max), -7, dtype=torch.int32, device=DEV)
+    bonus = torch.full((B,), -7, dtype=torch.int32, device=DEV)
+    tw.tree_accept(d, a, p, n, n_acc, path, bonus)
+    want = oracle.tree_accept(padded(draft, T_max), padded(argmx, T_max), padded(trees, T_max), n_nodes)
+    assert torch.equal(n_acc.cpu(), want[0])
+    assert torch.equal(path.cpu(), want[1])
+    assert torch.equal(bonus.cpu(), want[2])
+    return want[0]
+
+
+@pytest.mark.parametrize("alpha", [2, 3, 32000])
+def test_accept_random_trees(tw, alpha):
+    T_max, B = 64, 600
+    rng = W.HostRng(alpha, 0)
+    trees, draft, argmx, n_nodes = [], [], [], []
+    for b in range(B):
+        n = [1, 2, 63, 64][b % 4] if b < 16 else rng.randint(1, 64)
+        t = W.random_parent_tree(rng, n, 1 + b % 8)
+        if alpha > 3:
+            d, a = W.plant_tokens(rng, t)
+        else:
+            d = [rng.randint(0, alpha - 1) for _ in range(n)]
+            a = [rng.randint(0, alpha - 1) for _ in range(n)]
+        trees.append(t), draft.append(d), argmx.append(a), n_nodes.append(n)
+    n_acc = _check_accept(tw, draft, argmx, trees, n_nodes, T_max)
+    assert int(n_acc.max()) >= 2
+
+
+def test_accept_chain_star_and_duplicates(tw):
+    T = 8
+    chain = [-1] + list(range(T - 1))
+    star = [-1] + [0] * (T - 1)
+    cases = [
+        (chain, [0, 5, 6, 7, 8, 9, 1, 2], [5, 6, 7, 8, 0, 0, 0, 0]),      # prefix of four
+        (chain, [0] * T, [1] * T),                                        # nothing
+        (chain, [3] * T, [3] * T),                                        # everything
+        (star, [0, 4, 4, 4, 9, 9, 9, 9], [4, 1, 2, 3, 4, 5, 6, 7]),       # three equal siblings -> lowest
+        ([-1, 0, 0, 2], [0, 7, 7, 8], [7, 1, 8, 3]),                      # only the second twin continues
+    ]
+    trees = [c[0] for c in cases]
+    _check_accept(tw, [c[1] for c in cases], [c[2] for c in cases], trees, [len(t) for t in trees], T)
+
+
+# ----------------------------------------------------------------------------
+# ttp_select
+# ----------------------------------------------------------------------------
+def _check_select(tw, scores, R):
+    B, M = scores.shape
+    kept = torch.full((B, max(R, 1)), -7, dtype=torch.int32, device=DEV)[:, :R].contiguous()
+    tw.ttp_select(scores.to(DEV), R, kept)
+    torch.cuda.synchronize()
+    assert torch.equal(kept.cpu(), oracle.ttp_select(scores, R))
+
+
+@pytest.mark.parametrize("M", [1, 63, 576, 2880, 32000])
+def test_select_adversarial(tw, M):
+    g = torch.Generator().manual_seed(M)
+    vals = torch.tensor([-3.5, -0.0, 0.0, 1e-38, 1e-38, 0.25, 0.25, 7.0])
+    rows = [
+        vals[torch.randint(0, len(vals), (M,), generator=g)],                 # heavy ties, signed zeros
+        torch.zeros(M),                                                       # all equal
+        torch.arange(M).float(), -torch.arange(M).float(),                    # sorted both ways
+        torch.rand(M, generator=g) * 1e-3,                                    # score-like
+        -torch.rand(M, generator=g),                                          # all negative
+        torch.randn(M, generator=g) * 1e-41,                                  # denormals of both signs
+    ]
+    sc = torch.stack(rows).float()
+    for R in sorted({0, 1, min(2, M), M // 9, M // 2, max(M - 1, 0), M}):
+        _check_select(tw, sc, R)
+
+
+# ----------------------------------------------------------------------------
+# ttp_compact
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("row_elems,dtype", [(4096, torch.bfloat16), (256, torch.float32),
+                                             (1030, torch.bfloat16), (7, torch.uint8)])
+def test_compact_bit_exact(tw, row_elems, dtype):
+    v0, M, N = 5, 300, 40
+    n_tot = v0 + M + N
+    g = torch.Generator().manual_seed(row_elems)
+    for R in (0, 1, 77, M):
+        kept = torch.sort(torch.randperm(M, generator=g)[:R]).values.to(torch.int32)
+        n_t = 70 if row_elems == 256 else 3          # more tensors than one launch's table holds
+        src = [torch.randint(0, 256, (n_tot, row_elems), generator=g).to(dtype) for _ in range(n_t)]
+        dsrc = [s.to(DEV) for s in src]
+        ddst = [torch.zeros(n_tot - M + R, row_elems, dtype=dtype, device=DEV) for _ in src]
+        tw.ttp_compact(kept.to(DEV) if R else None, R, v0, M, n_tot, dsrc, ddst,
+                       row_elems * src[0].element_size())
+        torch.cuda.synchronize()
+        for s, d in zip(src, ddst):
+            want = oracle.ttp_compact(kept, v0, M, s)
+            assert torch.equal(d.cpu().view(torch.uint8), want.view(torch.uint8))
+
+
+# ----------------------------------------------------------------------------
+# the five configurations, whole path
+# ----------------------------------------------------------------------------
+def _path_parity(runner, cfg, verify_instances=None, check_compact_tensors=None):
+    w = W.make_workload(cfg)
+    dw = runner.DeviceWorkload(w, DEV)
+    dw.step()
+    torch.cuda.synchronize()
+    B, M, R = cfg.B, cfg.M, cfg.R
+    # S1 score
+    want_sc = oracle.ttp_score(w.q_sel, w.k_score, w.n_q, w.q_pos0, w.n_tot, w.score_row_off, 0, M,
+                               cfg.scale, True)
+    got_sc = dw.scores.cpu()
+    err = float((got_sc.double() - want_sc).abs().max())
+    assert err <= SCORE_TOL, f"score error {err:.3e}"
+    # S2 select: bit-exact on the scores the GPU produced
+    got_kept = dw.kept.cpu()
+    assert torch.equal(got_kept, oracle.ttp_select(got_sc, R))
+    # S1 -> S2 end to end: any disagreement with the fp64 scores sits within the score error of the threshold
+    ref_kept = oracle.ttp_select(want_sc.float(), R)
+    for b in range(B):
+        diff = set(got_kept[b].tolist()) ^ set(ref_kept[b].tolist())
+        if diff:
+            thr = torch.sort(want_sc[b], descending=True).values[R - 1]
+            assert all(abs(float(want_sc[b, m] - thr)) <= 2 * SCORE_TOL for m in diff)
+    # S3 compact: bit-exact given the kept indices the GPU selected
+    for b in range(B):
+        idx = range(len(w.compact_src[b])) if check_compact_tensors is None else check_compact_tensors
+        for t in idx:
+            want = oracle.ttp_compact(got_kept[b], 0, M, w.compact_src[b][t])
+            assert torch.equal(dw.compact_dst[b][t].cpu().view(torch.int16), want.view(torch.int16)), (b, t)
+    # S5 verify on all or on sampled instances
+    insts = list(range(dw.n_inst)) if verify_instances is None else verify_instances
+    sub = lambda xs: [xs[i] for i in insts]
+    want = oracle.tree_verify_attn(
+        w.q_tree[insts].contiguous(), w.k_pool, w.v_pool, sub(w.ctx_len), sub(w.n_nodes), sub(w.parent),
+        cfg.scale, row_off=None if w.row_off is None else sub(w.row_off),
+        page_table=None if w.page_table is None else sub(w.page_table), page_rows=cfg.page_rows)
+    got = dw.out.cpu()[insts].double()
+    assert torch.isfinite(got).all()
+    tol = ATTN_TOL if cfg.dtype == "bf16" else 2e-5
+    err = float((got - want).abs().max())
+    assert err <= tol, f"attention error {err:.3e}"
+    # S6 accept
+    wa = oracle.tree_accept(w.draft, w.argmax, w.tree_seq, [cfg.T] * B)
+    assert torch.equal(dw.n_acc.cpu(), wa[0]) and torch.equal(dw.path.cpu(), wa[1])
+    assert torch.equal(dw.bonus.cpu(), wa[2])
+
+
+def test_cfg0_tiny_fp32(runner):
+    _path_parity(runner, W.CONFIGS["cfg0"])
+
+
+def test_cfg1_llava_shape_single_layer(runner):
+    _path_parity(runner, W.CONFIGS["cfg1"])
+
+
+@pytest.mark.parametrize("name", ["cfg2_p0", "cfg2_p256", "cfg2_p1024"])
+def test_cfg2_all_layers(runner, name):
+    # 32 independent layer caches in one launch; the oracle checks first, middle and last layers
+    _path_parity(runner, W.CONFIGS[name], verify_instances=[0, 13, 31], check_compact_tensors=[0, 1, 30, 60])
+
+
+def test_cfg3_ragged_paged_batch(runner):
+    _path_parity(runner, W.CONFIGS["cfg3"])
+
+
+def test_cfg4_high_resolution(runner):
+    _path_parity(runner, W.CONFIGS["cfg4"], verify_instances=[0, 3])
