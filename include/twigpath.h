@@ -132,6 +132,20 @@ int32_t tw_ttp_compact(const int32_t* kept, int32_t R, int32_t v_start, int32_t 
                        size_t row_bytes, void* stream);
 
 /*
+ * The same compaction for a batch of B sequences whose rows live in shared
+ * pools (one launch for the whole batch).  Sequence b owns source rows
+ * src_row_off[b] .. +n_tot[b] and destination rows dst_row_off[b] ..
+ * +n_tot[b]-M+R of every (src[t], dst[t]) pair; kept is [dev] [B][R];
+ * n_tot, src_row_off, dst_row_off are [dev] [B]; n_tot_max is a host upper bound
+ * of n_tot.  Precondition on device contents: v_start + M <= n_tot[b] <= n_tot_max.
+ * Errors as tw_ttp_compact, plus UNSUPPORTED for B > 65535.
+ */
+int32_t tw_ttp_compact_batched(const int32_t* kept, int32_t R, int32_t v_start, int32_t M,
+                               const int32_t* n_tot, int32_t n_tot_max, const int32_t* src_row_off,
+                               const int32_t* dst_row_off, int32_t B, const void* const* src,
+                               void* const* dst, int32_t n_tensors, size_t row_bytes, void* stream);
+
+/*
  * Ancestor-or-self bit masks of draft trees (tree attention, Sec. 5.4 and
  * App. A).  Node 0 is the root (parent -1); parent[i] < i for i > 0.
  *   parent [dev] [B][T_max];  n_nodes [dev] [B];  masks [dev] [B][T_max] uint64 out

@@ -28,6 +28,7 @@ _STATUS = {0: "TW_OK", -1: "TW_ERR_INVALID_ARG", -2: "TW_ERR_UNSUPPORTED", -3: "
            -4: "TW_ERR_LAUNCH"}
 
 EXPORTS = ["tw_version", "tw_workspace_bytes", "tw_ttp_score", "tw_ttp_select", "tw_ttp_compact",
+           "tw_ttp_compact_batched",
            "tw_tree_ancestor_masks", "tw_tree_verify_attn", "tw_tree_accept", "tw_validate_tree",
            "tw_rbar"]
 
@@ -51,6 +52,9 @@ _lib.tw_ttp_select.argtypes = [_vp, _i32, _i32, _i32, _vp, _vp]
 _lib.tw_ttp_compact.restype = _i32
 _lib.tw_ttp_compact.argtypes = [_vp, _i32, _i32, _i32, _i32, ctypes.POINTER(_vp), ctypes.POINTER(_vp),
                                 _i32, _sz, _vp]
+_lib.tw_ttp_compact_batched.restype = _i32
+_lib.tw_ttp_compact_batched.argtypes = [_vp, _i32, _i32, _i32, _vp, _i32, _vp, _vp, _i32,
+                                        ctypes.POINTER(_vp), ctypes.POINTER(_vp), _i32, _sz, _vp]
 _lib.tw_tree_ancestor_masks.restype = _i32
 _lib.tw_tree_ancestor_masks.argtypes = [_vp, _vp, _i32, _i32, _vp, _vp]
 _lib.tw_tree_verify_attn.restype = _i32
@@ -133,6 +137,17 @@ def ttp_compact(kept: Optional[torch.Tensor], R: int, v_start: int, M: int, n_to
     d_arr = (_vp * max(n, 1))(*[_ptr(t) for t in dst])
     _check("tw_ttp_compact", _lib.tw_ttp_compact(_ptr(kept), R, v_start, M, n_tot, s_arr, d_arr, n,
                                                  row_bytes, _stream()))
+
+
+def ttp_compact_batched(kept: torch.Tensor, R: int, v_start: int, M: int, n_tot: torch.Tensor,
+                        n_tot_max: int, src_row_off: torch.Tensor, dst_row_off: torch.Tensor,
+                        src: Sequence[torch.Tensor], dst: Sequence[torch.Tensor], row_bytes: int) -> None:
+    n, B = len(src), n_tot.numel()
+    s_arr = (_vp * max(n, 1))(*[_ptr(t) for t in src])
+    d_arr = (_vp * max(n, 1))(*[_ptr(t) for t in dst])
+    _check("tw_ttp_compact_batched", _lib.tw_ttp_compact_batched(
+        _ptr(kept), R, v_start, M, _ptr(n_tot), n_tot_max, _ptr(src_row_off), _ptr(dst_row_off), B,
+        s_arr, d_arr, n, row_bytes, _stream()))
 
 
 def tree_ancestor_masks(parent: torch.Tensor, n_nodes: torch.Tensor, masks: torch.Tensor) -> None:

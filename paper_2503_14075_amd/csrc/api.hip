@@ -101,6 +101,20 @@ int32_t tw_ttp_select(const float* scores, int32_t B, int32_t M, int32_t R, int3
                                                                                    : TW_ERR_LAUNCH;
 }
 
+static int32_t compact_tables(const CompactBatch& cb, int B, int n_out_max, const void* const* src,
+                              void* const* dst, int n_tensors, size_t row_bytes, hipStream_t s) {
+    for (int t0 = 0; t0 < n_tensors; t0 += kCompactMaxTensors) {
+        const int n = n_tensors - t0 < kCompactMaxTensors ? n_tensors - t0 : kCompactMaxTensors;
+        CompactTable tab;
+        for (int t = 0; t < kCompactMaxTensors; ++t) {
+            tab.src[t] = t < n ? src[t0 + t] : nullptr;
+            tab.dst[t] = t < n ? dst[t0 + t] : nullptr;
+        }
+        if (launch_compact(cb, B, n_out_max, tab, n, row_bytes, s) != hipSuccess) return TW_ERR_LAUNCH;
+    }
+    return TW_OK;
+}
+
 int32_t tw_ttp_compact(const int32_t* kept, int32_t R, int32_t v_start, int32_t M, int32_t n_tot,
                        const void* const* src, void* const* dst, int32_t n_tensors,
                        size_t row_bytes, void* stream) {
@@ -110,18 +124,25 @@ int32_t tw_ttp_compact(const int32_t* kept, int32_t R, int32_t v_start, int32_t 
     if (!src || !dst || row_bytes == 0 || (R > 0 && !kept)) return TW_ERR_INVALID_ARG;
     for (int t = 0; t < n_tensors; ++t)
         if (!src[t] || !dst[t]) return TW_ERR_INVALID_ARG;
-    for (int t0 = 0; t0 < n_tensors; t0 += kCompactMaxTensors) {
-        const int n = n_tensors - t0 < kCompactMaxTensors ? n_tensors - t0 : kCompactMaxTensors;
-        CompactTable tab;
-        for (int t = 0; t < kCompactMaxTensors; ++t) {
-            tab.src[t] = t < n ? src[t0 + t] : nullptr;
-            tab.dst[t] = t < n ? dst[t0 + t] : nullptr;
-        }
-        if (launch_compact(kept, R, v_start, M, n_tot, tab, n, row_bytes, (hipStream_t)stream) !=
-            hipSuccess)
-            return TW_ERR_LAUNCH;
-    }
-    return TW_OK;
+    const CompactBatch cb = {kept, nullptr, nullptr, nullptr, n_tot, R, v_start, M};
+    return compact_tables(cb, 1, n_tot - M + R, src, dst, n_tensors, row_bytes, (hipStream_t)stream);
+}
+
+int32_t tw_ttp_compact_batched(const int32_t* kept, int32_t R, int32_t v_start, int32_t M,
+                               const int32_t* n_tot, int32_t n_tot_max, const int32_t* src_row_off,
+                               const int32_t* dst_row_off, int32_t B, const void* const* src,
+                               void* const* dst, int32_t n_tensors, size_t row_bytes, void* stream) {
+    if (R < 0 || M < 0 || R > M || v_start < 0 || n_tot_max < 0 || n_tensors < 0 || B < 0)
+        return TW_ERR_INVALID_ARG;
+    if ((int64_t)v_start + M > n_tot_max) return TW_ERR_INVALID_ARG;
+    if (B > 65535) return TW_ERR_UNSUPPORTED;
+    if (n_tensors == 0 || B == 0) return TW_OK;
+    if (!src || !dst || row_bytes == 0 || (R > 0 && !kept) || !n_tot || !src_row_off || !dst_row_off)
+        return TW_ERR_INVALID_ARG;
+    for (int t = 0; t < n_tensors; ++t)
+        if (!src[t] || !dst[t]) return TW_ERR_INVALID_ARG;
+    const CompactBatch cb = {kept, n_tot, src_row_off, dst_row_off, 0, R, v_start, M};
+    return compact_tables(cb, B, n_tot_max - M + R, src, dst, n_tensors, row_bytes, (hipStream_t)stream);
 }
 
 int32_t tw_tree_ancestor_masks(const int32_t* parent, const int32_t* n_nodes, int32_t T_max,

@@ -22,13 +22,10 @@
 //
 // MFMA operand layouts used (lane l, g = l/32, i = l%32):
 //   A[i][8g+e], B[8g+e][i] for e = 0..7;  D[8*(r/4) + 4g + r%4][i] for r = 0..15.
+#include "mfma_util.h"
 #include "twig_internal.h"
 
 namespace tw {
-
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(16))) float floatx16;
-typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 
 constexpr int kMfThreads = 256;
 constexpr int kChunk = 32;
@@ -45,11 +42,6 @@ struct MfCfg {
     static constexpr int kNQ = DH / 32;             // output column blocks of PV
     static constexpr int kWaveLds = kChunk * (kKStride + kVStride);
 };
-
-__device__ __forceinline__ bf16x8 as_bf16x8(const u32x4& v) { return __builtin_bit_cast(bf16x8, v); }
-
-// row within a chunk held by accumulator register r of lane group g
-__device__ __forceinline__ int acc_row(int r, int g) { return 8 * (r >> 2) + 4 * g + (r & 3); }
 
 // K and V share one row mapping (same row_off / page_table) on this path.
 template <int DH, int NB, bool PAGED>
@@ -110,7 +102,7 @@ __global__ __launch_bounds__(kMfThreads, (NB == 1 ? 2 : 1)) void verify_mfma_ker
 #pragma unroll
             for (int r = 0; r < 16; ++r) o[nb][q][r] = 0.f;
     }
-    const float sl2 = a.scale * 1.4426950408889634f;
+    const float sl2 = a.scale * kLog2e;
 
     // lane's share of a chunk load: row (lane / lanes_per_row) + rows_per_load * j,
     // 16-byte column lane % lanes_per_row of the head's segment
@@ -292,7 +284,7 @@ __global__ __launch_bounds__(kMfThreads, (NB == 1 ? 2 : 1)) void verify_mfma_ker
             dst = a.part_o + slot * DH;
             mul = 1.f;
             if (g == 0) {
-                a.part_ml[slot * 2] = run_m[nb] * 0.6931471805599453f;   // natural-log units for the combine
+                a.part_ml[slot * 2] = run_m[nb] * kLn2;   // natural-log units for the combine
                 a.part_ml[slot * 2 + 1] = l;
             }
         }

@@ -1,7 +1,8 @@
 // Stable compaction of hidden-state and KV rows after token pruning
 // (Sec. 3.1 Eq. 3, Sec. 4.2 Eq. 5; R = 0 is FinalWipe).  A pure row gather:
 // one workgroup moves one destination row of one tensor with 16-byte lanes,
-// one launch covers every tensor of the pointer table.
+// one launch covers every tensor of the pointer table and every sequence of a
+// batch.
 #include "twig_internal.h"
 
 namespace tw {
@@ -20,14 +21,16 @@ __device__ __forceinline__ int compact_src_row(const int32_t* kept, int R, int v
 }
 
 template <bool kVec16>
-__global__ __launch_bounds__(kCompactThreads) void compact_kernel(const int32_t* __restrict__ kept,
-                                                                  int R, int v_start, int M,
-                                                                  CompactTable tab,
+__global__ __launch_bounds__(kCompactThreads) void compact_kernel(CompactBatch cb, CompactTable tab,
                                                                   size_t row_bytes) {
-    const int r = blockIdx.x;
-    const int sr = compact_src_row(kept, R, v_start, M, r);
-    const char* src = (const char*)tab.src[blockIdx.y] + (size_t)sr * row_bytes;
-    char* dst = (char*)tab.dst[blockIdx.y] + (size_t)r * row_bytes;
+    const int r = blockIdx.x, b = blockIdx.z;
+    const int n_tot = cb.n_tot ? cb.n_tot[b] : cb.n_tot_all;
+    if (r >= n_tot - cb.M + cb.R) return;
+    const int64_t s0 = cb.src_off ? cb.src_off[b] : 0, d0 = cb.dst_off ? cb.dst_off[b] : 0;
+    int sr = compact_src_row(cb.kept + (int64_t)b * cb.R, cb.R, cb.v_start, cb.M, r);
+    sr = sr < n_tot ? sr : n_tot - 1;   // stays inside the sequence even if the span does not
+    const char* src = (const char*)tab.src[blockIdx.y] + (size_t)(s0 + sr) * row_bytes;
+    char* dst = (char*)tab.dst[blockIdx.y] + (size_t)(d0 + r) * row_bytes;
     if (kVec16) {
         const u32x4* s4 = (const u32x4*)src;
         u32x4* d4 = (u32x4*)dst;
@@ -46,20 +49,17 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(const int32_t*
     }
 }
 
-hipError_t launch_compact(const int32_t* kept, int R, int v_start, int M, int n_tot,
-                          const CompactTable& tab, int n_tensors, size_t row_bytes, hipStream_t s) {
-    const int n_out = n_tot - M + R;
-    if (n_out <= 0 || n_tensors <= 0) return hipSuccess;
+hipError_t launch_compact(const CompactBatch& cb, int B, int n_out_max, const CompactTable& tab,
+                          int n_tensors, size_t row_bytes, hipStream_t s) {
+    if (n_out_max <= 0 || n_tensors <= 0 || B <= 0) return hipSuccess;
     bool vec = (row_bytes % 16) == 0;
     for (int t = 0; t < n_tensors; ++t)
         vec = vec && ((uintptr_t)tab.src[t] % 16 == 0) && ((uintptr_t)tab.dst[t] % 16 == 0);
-    dim3 grid(n_out, n_tensors);
+    dim3 grid(n_out_max, n_tensors, B);
     if (vec)
-        hipLaunchKernelGGL(compact_kernel<true>, grid, dim3(kCompactThreads), 0, s, kept, R, v_start, M,
-                           tab, row_bytes);
+        hipLaunchKernelGGL(compact_kernel<true>, grid, dim3(kCompactThreads), 0, s, cb, tab, row_bytes);
     else
-        hipLaunchKernelGGL(compact_kernel<false>, grid, dim3(kCompactThreads), 0, s, kept, R, v_start,
-                           M, tab, row_bytes);
+        hipLaunchKernelGGL(compact_kernel<false>, grid, dim3(kCompactThreads), 0, s, cb, tab, row_bytes);
     return hipGetLastError();
 }
 

@@ -2,18 +2,221 @@
 // in Sec. 5.1 Eq. 7): attention rows of the last text queries, averaged over
 // heads and rows, restricted to the visual columns.
 //
-// Two kernels, both with a fixed summation order (bit-identical run to run):
-//   1. score_logits: one workgroup per (head, 16 scoring rows, sequence) walks
-//      the keys in tiles of 64 staged in LDS, writes the masked logits to the
-//      workspace and keeps an online (max, sum) per row.
-//   2. score_reduce: one lane per visual key sums exp(logit - max) / sum over
-//      heads and rows in a fixed order.
+// The attention map is never materialised.  A (sequence, head) is handled in
+// two passes over its keys:
+//   pass 1  logits of every scoring row against every visible key -> per-row
+//           running (max, sum) only;
+//   pass 2  logits against the visual keys again (re-read from cache, not
+//           stored), weights exp(logit - max)/sum, summed over the scoring rows
+//           per key -> partial[b][h][m] in the workspace.
+// score_reduce then adds the heads in a fixed order.  No floating-point
+// atomics: results are bit-identical from run to run.
+//
+// bf16 with d_h 64/128 and at most 128 scoring rows runs on the matrix cores:
+// one wavefront per head, 32-key chunks staged through LDS exactly as in the
+// verification kernel.  Pass 1 forms K.Q^T (a lane owns one scoring row, so
+// the row statistics need no cross-lane traffic inside the loop); pass 2 forms
+// Q.K^T with the same register fragments swapped (a lane owns one key, so the
+// sum over scoring rows is in-lane).  Everything else takes the generic fp32
+// vector path.
+#include "mfma_util.h"
 #include "twig_internal.h"
 
 namespace tw {
 
+// ============================================================================
+// matrix-core path
+// ============================================================================
+constexpr int kScMfThreads = 256;
+constexpr int kScChunk = 32;
+
+template <int DH>
+struct ScCfg {
+    static constexpr int kRowB = DH * 2;
+    static constexpr int kKStride = kRowB + 16;
+    static constexpr int kLanesPerRow = kRowB / 16;
+    static constexpr int kRowsPerLoad = 64 / kLanesPerRow;
+    static constexpr int kLoads = kScChunk / kRowsPerLoad;
+    static constexpr int kDC = DH / 16;
+    static constexpr int kWaveLds = kScChunk * kKStride + 128 * 4;   // K chunk + per-row statistics
+};
+
+template <int DH, int NB>
+__global__ __launch_bounds__(kScMfThreads, (NB <= 2 ? 2 : 1)) void score_mfma_kernel(ScoreArgs a) {
+    using Cf = ScCfg<DH>;
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int g = lane >> 5, li = lane & 31;
+    const int b = blockIdx.y, h = blockIdx.x * 4 + wave;
+    if (h >= a.H) return;
+    int n_q = a.n_q ? a.n_q[b] : a.n_q_max;
+    n_q = n_q < 1 ? 1 : (n_q > a.n_q_max ? a.n_q_max : n_q);
+    int n_tot = a.n_tot[b];
+    n_tot = n_tot < 0 ? 0 : (n_tot > a.n_tot_max ? a.n_tot_max : n_tot);
+    const int pos0 = a.q_pos0[b];
+    float* partial = a.ws + ((int64_t)b * a.H + h) * a.M;
+    if (n_tot == 0) {
+        for (int m = lane; m < a.M; m += 64) partial[m] = 0.f;
+        return;
+    }
+    unsigned char* ldsK = lds + wave * Cf::kWaveLds;
+    float* s_stat = (float*)(ldsK + kScChunk * Cf::kKStride);
+
+    // Q fragments: lane (i, g) holds Q[row 32nb+i][16c + 8g .. +7]; rows past n_q are zero
+    bf16x8 qf[NB][Cf::kDC];
+    const uint16_t* qb = (const uint16_t*)a.q_sel;
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+        const int i = 32 * nb + li;
+        const int ic = i < n_q ? i : n_q - 1;
+        const u32x4* src = (const u32x4*)(qb + (((int64_t)b * a.n_q_max + ic) * a.H + h) * DH + 8 * g);
+#pragma unroll
+        for (int c = 0; c < Cf::kDC; ++c) {
+            u32x4 v = src[2 * c];
+            if (i >= n_q) v = (u32x4){0u, 0u, 0u, 0u};
+            qf[nb][c] = as_bf16x8(v);
+        }
+    }
+    const float sl2 = a.scale * kLog2e;
+
+    const int ld_row = lane / Cf::kLanesPerRow, ld_col = lane % Cf::kLanesPerRow;
+    const unsigned char* kbase = (const unsigned char*)a.k.base + (int64_t)h * Cf::kRowB + ld_col * 16;
+    const int64_t pool_stride = (int64_t)a.H * Cf::kRowB;
+    const int64_t last_pool_row = a.k.pool_rows - 1;
+    const int64_t row0 = (int64_t)a.k.row_off[b];
+    u32x4 pk[Cf::kLoads];
+    auto issue_loads = [&](int base) {
+#pragma unroll
+        for (int j = 0; j < Cf::kLoads; ++j) {
+            int r = base + ld_row + Cf::kRowsPerLoad * j;
+            r = r < n_tot - 1 ? r : n_tot - 1;   // past the end: re-read the last key (cached), masked below
+            int64_t prow = row0 + r;
+            prow = prow < 0 ? 0 : (prow > last_pool_row ? last_pool_row : prow);
+            pk[j] = *(const u32x4*)(kbase + prow * pool_stride);
+        }
+    };
+    auto stage = [&]() {
+#pragma unroll
+        for (int j = 0; j < Cf::kLoads; ++j)
+            *(u32x4*)(ldsK + (ld_row + Cf::kRowsPerLoad * j) * Cf::kKStride + ld_col * 16) = pk[j];
+    };
+    auto lds_sync = [&]() {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    };
+    // keys visible to scoring row i: j < vis_end(i)
+    const int vis_all = a.causal ? min(pos0 + 1, n_tot) : n_tot;   // visible to every row
+
+    // ---- pass 1: per-row (max, sum) over all visible keys ----------------------
+    float run_m[NB], run_l[NB];
+    int vis_end[NB];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+        run_m[nb] = -INFINITY;
+        run_l[nb] = 0.f;
+        vis_end[nb] = a.causal ? min(pos0 + 32 * nb + li + 1, n_tot) : n_tot;
+    }
+    issue_loads(0);
+    for (int base = 0; base < n_tot; base += kScChunk) {
+        stage();
+        issue_loads(base + kScChunk);
+        lds_sync();
+        floatx16 s[NB];
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) s[nb][r] = 0.f;
+#pragma unroll
+        for (int c = 0; c < Cf::kDC; ++c) {
+            const bf16x8 kf = as_bf16x8(*(const u32x4*)(ldsK + li * Cf::kKStride + 32 * c + 16 * g));
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+                s[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[nb][c], s[nb], 0, 0, 0);
+        }
+        const bool need_mask = base + kScChunk > vis_all;
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+            float x[16], mx = -INFINITY;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                x[r] = s[nb][r] * sl2;
+                if (need_mask && base + acc_row(r, g) >= vis_end[nb]) x[r] = -INFINITY;
+                mx = fmaxf(mx, x[r]);
+            }
+            const float m_new = fmaxf(run_m[nb], mx);
+            const float m_safe = m_new == -INFINITY ? 0.f : m_new;
+            float psum = 0.f;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) psum += exp2f(x[r] - m_safe);
+            run_l[nb] = run_l[nb] * exp2f(run_m[nb] - m_safe) + psum;
+            run_m[nb] = m_new;
+        }
+    }
+    // merge the two lane groups of a row; publish max + log2(sum) per row
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+        const float om = __shfl_xor(run_m[nb], 32, 64), ol = __shfl_xor(run_l[nb], 32, 64);
+        const float m = fmaxf(run_m[nb], om);
+        const float m_safe = m == -INFINITY ? 0.f : m;
+        const float l = run_l[nb] * exp2f(run_m[nb] - m_safe) + ol * exp2f(om - m_safe);
+        const int i = 32 * nb + li;
+        if (g == 0) s_stat[i] = (i < n_q && l > 0.f) ? m + log2f(l) : INFINITY;   // +inf: row contributes nothing
+    }
+    lds_sync();
+    float mc[NB][16];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) mc[nb][r] = s_stat[32 * nb + acc_row(r, g)];
+
+    // ---- pass 2: weights on the visual keys, summed over scoring rows -----------
+    const int span_end = a.v_start + a.M;
+    const int base2 = a.v_start / kScChunk * kScChunk;
+    issue_loads(base2);
+    for (int base = base2; base < span_end; base += kScChunk) {
+        lds_sync();   // fragment reads of the previous chunk are complete before it is overwritten
+        stage();
+        issue_loads(base + kScChunk);
+        lds_sync();
+        floatx16 d[NB];
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) d[nb][r] = 0.f;
+#pragma unroll
+        for (int c = 0; c < Cf::kDC; ++c) {
+            const bf16x8 kf = as_bf16x8(*(const u32x4*)(ldsK + li * Cf::kKStride + 32 * c + 16 * g));
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+                d[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[nb][c], kf, d[nb], 0, 0, 0);
+        }
+        const int j = base + li;   // this lane's key
+        const bool need_mask = base + kScChunk > vis_all;
+        float acc = 0.f;
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                float x = fmaf(d[nb][r], sl2, -mc[nb][r]);
+                if (need_mask) {
+                    const int i = 32 * nb + acc_row(r, g);
+                    const int ve = a.causal ? min(pos0 + i + 1, n_tot) : n_tot;
+                    if (j >= ve) x = -INFINITY;
+                }
+                acc += exp2f(x);
+            }
+        }
+        acc += __shfl_xor(acc, 32, 64);
+        if (g == 0 && j >= a.v_start && j < span_end) partial[j - a.v_start] = acc;
+    }
+}
+
+// ============================================================================
+// generic path (fp32 inputs, other head sizes, more than 128 scoring rows)
+// ============================================================================
 constexpr int kScThreads = 256;
-constexpr int kScRows = 16;   // scoring rows per workgroup
+constexpr int kScRows = 16;   // scoring rows per block of the inner loop
 constexpr int kScKeys = 64;   // keys per tile
 
 template <typename TIn>
@@ -37,127 +240,166 @@ __device__ __forceinline__ void load8<uint16_t>(const uint16_t* p, float* dst) {
     }
 }
 
+// grid (H, B).  The workgroup walks the scoring rows of its (sequence, head) in
+// blocks of 16; lane (i, kg) = (tid / 16, tid % 16) owns row i and keys kg + 16*jj
+// of each 64-key tile.
 template <typename TIn>
-__global__ __launch_bounds__(kScThreads) void score_logits_kernel(ScoreArgs a) {
+__global__ __launch_bounds__(kScThreads) void score_generic_kernel(ScoreArgs a) {
     extern __shared__ float smem[];
     const int d_h = a.d_h, ld = d_h + 1;
-    float* sQ = smem;                 // [kScRows][ld], pre-multiplied by scale
-    float* sK = sQ + kScRows * ld;    // [kScKeys][ld]
-    const int h = blockIdx.x, b = blockIdx.z, row0 = blockIdx.y * kScRows;
-    const int tid = threadIdx.x;
+    float* sQ = smem;                    // [kScRows][ld], pre-multiplied by scale
+    float* sK = sQ + kScRows * ld;       // [kScKeys][ld]
+    float* sP = sK + kScKeys * ld;       // [kScRows][kScKeys + 1]
+    __shared__ float s_m[kScRows], s_l[kScRows];
+    const int h = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
     int n_q = a.n_q ? a.n_q[b] : a.n_q_max;
     n_q = n_q < 1 ? 1 : (n_q > a.n_q_max ? a.n_q_max : n_q);
-    if (row0 >= n_q) return;
     int n_tot = a.n_tot[b];
     n_tot = n_tot < 0 ? 0 : (n_tot > a.n_tot_max ? a.n_tot_max : n_tot);
     const int pos0 = a.q_pos0[b];
     const TIn* q = (const TIn*)a.q_sel;
     const TIn* kbase = (const TIn*)a.k.base;
     const int c8n = d_h / 8;
-
-    for (int idx = tid; idx < kScRows * c8n; idx += kScThreads) {
-        const int i = idx / c8n, c8 = idx % c8n;
-        float v[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-        if (row0 + i < n_q)
-            load8<TIn>(q + (((int64_t)b * a.n_q_max + row0 + i) * a.H + h) * d_h + c8 * 8, v);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) sQ[i * ld + c8 * 8 + e] = v[e] * a.scale;
-    }
-
+    float* partial = a.ws + ((int64_t)b * a.H + h) * a.M;
     const int i = tid / 16, kg = tid % 16;
-    const int i_abs = row0 + i;
-    const bool row_ok = i_abs < n_q;
-    const int n_vis = !row_ok ? 0 : (a.causal ? min(pos0 + i_abs + 1, n_tot) : n_tot);
-    float* logit_row = a.ws + (((int64_t)b * a.H + h) * a.n_q_max + i_abs) * (int64_t)a.n_tot_max;
-    float run_m = -INFINITY, run_l = 0.f;
+    const int span_end = a.v_start + a.M;
 
-    for (int base = 0; base < n_tot; base += kScKeys) {
-        __syncthreads();
+    auto load_keys = [&](int base) {
         for (int idx = tid; idx < kScKeys * c8n; idx += kScThreads) {
             const int r = idx / c8n, c8 = idx % c8n;
             float v[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-            if (base + r < n_tot) {
-                const int64_t prow = pool_row(a.k, b, base + r);
-                load8<TIn>(kbase + (prow * a.H + h) * d_h + c8 * 8, v);
-            }
+            if (base + r < n_tot)
+                load8<TIn>(kbase + (pool_row(a.k, b, base + r) * a.H + h) * d_h + c8 * 8, v);
 #pragma unroll
             for (int e = 0; e < 8; ++e) sK[r * ld + c8 * 8 + e] = v[e];
         }
+    };
+
+    for (int row0 = 0; row0 < n_q; row0 += kScRows) {
         __syncthreads();
-        float dot[4] = {0.f, 0.f, 0.f, 0.f};
-        for (int c = 0; c < d_h; ++c) {
-            const float qv = sQ[i * ld + c];
+        for (int idx = tid; idx < kScRows * c8n; idx += kScThreads) {
+            const int ii = idx / c8n, c8 = idx % c8n;
+            float v[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+            if (row0 + ii < n_q)
+                load8<TIn>(q + (((int64_t)b * a.n_q_max + row0 + ii) * a.H + h) * d_h + c8 * 8, v);
 #pragma unroll
-            for (int jj = 0; jj < 4; ++jj) dot[jj] = fmaf(qv, sK[(kg + 16 * jj) * ld + c], dot[jj]);
+            for (int e = 0; e < 8; ++e) sQ[ii * ld + c8 * 8 + e] = v[e] * a.scale;
         }
+        const int i_abs = row0 + i;
+        const bool row_ok = i_abs < n_q;
+        const int n_vis = !row_ok ? 0 : (a.causal ? min(pos0 + i_abs + 1, n_tot) : n_tot);
+        // ---- pass 1 ----
+        float run_m = -INFINITY, run_l = 0.f;
+        for (int base = 0; base < n_tot; base += kScKeys) {
+            __syncthreads();
+            load_keys(base);
+            __syncthreads();
+            float dot[4] = {0.f, 0.f, 0.f, 0.f};
+            for (int c = 0; c < d_h; ++c) {
+                const float qv = sQ[i * ld + c];
 #pragma unroll
-        for (int jj = 0; jj < 4; ++jj) {
-            const int j = base + kg + 16 * jj;
-            if (row_ok && j < n_tot) {
-                const bool vis = j < n_vis;
-                const float s = vis ? dot[jj] : -INFINITY;
-                logit_row[j] = s;
-                if (vis) {
-                    const float m_new = fmaxf(run_m, s);
-                    run_l = run_l * expf(run_m - m_new) + expf(s - m_new);
+                for (int jj = 0; jj < 4; ++jj) dot[jj] = fmaf(qv, sK[(kg + 16 * jj) * ld + c], dot[jj]);
+            }
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) {
+                if (base + kg + 16 * jj < n_vis) {
+                    const float m_new = fmaxf(run_m, dot[jj]);
+                    run_l = run_l * expf(run_m - m_new) + expf(dot[jj] - m_new);
                     run_m = m_new;
                 }
             }
         }
-    }
-    // merge the 16 lanes that share a scoring row
 #pragma unroll
-    for (int off = 1; off < 16; off <<= 1) {
-        const float om = __shfl_xor(run_m, off, 64), ol = __shfl_xor(run_l, off, 64);
-        const float m_new = fmaxf(run_m, om);
-        const float sa = run_m == -INFINITY ? 0.f : expf(run_m - m_new);
-        const float sb = om == -INFINITY ? 0.f : expf(om - m_new);
-        run_l = run_l * sa + ol * sb;
-        run_m = m_new;
-    }
-    if (row_ok && kg == 0) {
-        float* st = a.ws + (int64_t)a.B * a.H * a.n_q_max * a.n_tot_max +
-                    (((int64_t)b * a.H + h) * a.n_q_max + i_abs) * 2;
-        st[0] = run_m;
-        st[1] = run_l;
+        for (int off = 1; off < 16; off <<= 1) {
+            const float om = __shfl_xor(run_m, off, 64), ol = __shfl_xor(run_l, off, 64);
+            const float m_new = fmaxf(run_m, om);
+            const float sa = run_m == -INFINITY ? 0.f : expf(run_m - m_new);
+            const float sb = om == -INFINITY ? 0.f : expf(om - m_new);
+            run_l = run_l * sa + ol * sb;
+            run_m = m_new;
+        }
+        if (kg == 0) {
+            s_m[i] = run_m;
+            s_l[i] = run_l;
+        }
+        // ---- pass 2 over the tiles that touch the visual span ----
+        for (int base = a.v_start / kScKeys * kScKeys; base < span_end; base += kScKeys) {
+            __syncthreads();
+            load_keys(base);
+            __syncthreads();
+            float dot[4] = {0.f, 0.f, 0.f, 0.f};
+            for (int c = 0; c < d_h; ++c) {
+                const float qv = sQ[i * ld + c];
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj) dot[jj] = fmaf(qv, sK[(kg + 16 * jj) * ld + c], dot[jj]);
+            }
+            const float m = s_m[i], l = s_l[i];
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) {
+                const int j = base + kg + 16 * jj;
+                sP[i * (kScKeys + 1) + kg + 16 * jj] = j < n_vis ? expf(dot[jj] - m) / l : 0.f;
+            }
+            __syncthreads();
+            if (tid < kScKeys) {
+                const int j = base + tid;
+                if (j >= a.v_start && j < span_end) {
+                    float sum = 0.f;
+#pragma unroll
+                    for (int ii = 0; ii < kScRows; ++ii) sum += sP[ii * (kScKeys + 1) + tid];
+                    // this lane is the only writer of the slot for the whole kernel
+                    partial[j - a.v_start] = row0 == 0 ? sum : partial[j - a.v_start] + sum;
+                }
+            }
+        }
     }
 }
 
-__global__ __launch_bounds__(kScThreads) void score_reduce_kernel(ScoreArgs a) {
-    const int b = blockIdx.y, m = blockIdx.x * kScThreads + threadIdx.x;
+// scores[b][m] = mean over heads and scoring rows; heads are added in index order.
+__global__ __launch_bounds__(256) void score_reduce_kernel(ScoreArgs a) {
+    const int b = blockIdx.y, m = blockIdx.x * 256 + threadIdx.x;
     if (m >= a.M) return;
     int n_q = a.n_q ? a.n_q[b] : a.n_q_max;
     n_q = n_q < 1 ? 1 : (n_q > a.n_q_max ? a.n_q_max : n_q);
-    const int j = a.v_start + m;
-    const float* stats = a.ws + (int64_t)a.B * a.H * a.n_q_max * a.n_tot_max;
     float acc = 0.f;
-    for (int h = 0; h < a.H; ++h) {
-        for (int i = 0; i < n_q; ++i) {
-            const int64_t row = ((int64_t)b * a.H + h) * a.n_q_max + i;
-            const float s = a.ws[row * a.n_tot_max + j];
-            const float mx = stats[row * 2], l = stats[row * 2 + 1];
-            if (s != -INFINITY) acc += expf(s - mx) / l;
-        }
-    }
+    for (int h = 0; h < a.H; ++h) acc += a.ws[((int64_t)b * a.H + h) * a.M + m];
     a.scores[(int64_t)b * a.M + m] = acc / ((float)a.H * (float)n_q);
 }
 
 size_t score_workspace_bytes(int B, int H, int n_q_max, int n_tot_max) {
-    return ((size_t)B * H * n_q_max * n_tot_max + (size_t)B * H * n_q_max * 2) * sizeof(float);
+    (void)n_q_max;
+    return (size_t)B * H * n_tot_max * sizeof(float);   // per-head partial sums, at most n_tot_max visual keys
+}
+
+template <int DH, int NB>
+static hipError_t launch_score_mfma(const ScoreArgs& a, hipStream_t s) {
+    const size_t lds = 4 * (size_t)ScCfg<DH>::kWaveLds;
+    hipLaunchKernelGGL((score_mfma_kernel<DH, NB>), dim3((a.H + 3) / 4, a.B), dim3(kScMfThreads), lds, s, a);
+    return hipGetLastError();
+}
+
+template <int DH>
+static hipError_t launch_score_mfma_rows(const ScoreArgs& a, hipStream_t s) {
+    if (a.n_q_max <= 32) return launch_score_mfma<DH, 1>(a, s);
+    if (a.n_q_max <= 64) return launch_score_mfma<DH, 2>(a, s);
+    return launch_score_mfma<DH, 4>(a, s);
 }
 
 hipError_t launch_score(const ScoreArgs& a, int dtype, hipStream_t s) {
     if (a.B == 0 || a.M == 0) return hipSuccess;
-    const dim3 grid(a.H, (a.n_q_max + kScRows - 1) / kScRows, a.B);
-    const size_t lds = (size_t)(kScRows + kScKeys) * (a.d_h + 1) * sizeof(float);
-    if (dtype == TW_F32)
-        hipLaunchKernelGGL(score_logits_kernel<float>, grid, dim3(kScThreads), lds, s, a);
-    else
-        hipLaunchKernelGGL(score_logits_kernel<uint16_t>, grid, dim3(kScThreads), lds, s, a);
-    hipError_t e = hipGetLastError();
+    hipError_t e;
+    if (dtype == TW_BF16 && (a.d_h == 64 || a.d_h == 128) && a.n_q_max <= 128) {
+        e = a.d_h == 128 ? launch_score_mfma_rows<128>(a, s) : launch_score_mfma_rows<64>(a, s);
+    } else {
+        const size_t lds = ((size_t)(kScRows + kScKeys) * (a.d_h + 1) + (size_t)kScRows * (kScKeys + 1)) *
+                           sizeof(float);
+        if (dtype == TW_F32)
+            hipLaunchKernelGGL(score_generic_kernel<float>, dim3(a.H, a.B), dim3(kScThreads), lds, s, a);
+        else
+            hipLaunchKernelGGL(score_generic_kernel<uint16_t>, dim3(a.H, a.B), dim3(kScThreads), lds, s, a);
+        e = hipGetLastError();
+    }
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(score_reduce_kernel, dim3((a.M + kScThreads - 1) / kScThreads, a.B),
-                       dim3(kScThreads), 0, s, a);
+    hipLaunchKernelGGL(score_reduce_kernel, dim3((a.M + 255) / 256, a.B), dim3(256), 0, s, a);
     return hipGetLastError();
 }
 

@@ -106,8 +106,16 @@ struct CompactTable {
     const void* src[kCompactMaxTensors];
     void* dst[kCompactMaxTensors];
 };
-hipError_t launch_compact(const int32_t* kept, int R, int v_start, int M, int n_tot,
-                          const CompactTable& tab, int n_tensors, size_t row_bytes, hipStream_t s);
+// One sequence: n_tot/src_off/dst_off null and n_tot_all set.  Batch: device arrays [B].
+struct CompactBatch {
+    const int32_t* kept;     // [B][R]
+    const int32_t* n_tot;    // [B] or null
+    const int32_t* src_off;  // [B] first source row of sequence b, or null
+    const int32_t* dst_off;  // [B] first destination row, or null
+    int32_t n_tot_all, R, v_start, M;
+};
+hipError_t launch_compact(const CompactBatch& cb, int B, int n_out_max, const CompactTable& tab,
+                          int n_tensors, size_t row_bytes, hipStream_t s);
 
 hipError_t launch_ancestor_masks(const int32_t* parent, const int32_t* n_nodes, int T_max, int B,
                                  uint64_t* masks, hipStream_t s);

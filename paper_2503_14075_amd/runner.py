@@ -40,10 +40,11 @@ class DeviceWorkload:
             self.k_score_view = tw.kv_view(self.k_score, row_off=self.score_row_off)
             nbytes = tw.workspace_bytes(tw.TW_CALL_TTP_SCORE, B, w.n_q_max, H, d_h, self.n_tot_max)
             self.score_ws = torch.empty(max(nbytes, 4) // 4, dtype=torch.float32, device=dev)
-        self.compact_src = [[t.to(dev) for t in ts] for ts in w.compact_src]
-        self.compact_dst = [[torch.empty((cfg.R + w.n_text[b],) + tuple(t.shape[1:]), dtype=t.dtype,
-                                         device=dev) for t in ts]
-                            for b, ts in enumerate(self.compact_src)]
+        self.compact_src = [t.to(dev) for t in w.compact_src]
+        n_keep_total = sum(cfg.R + n for n in w.n_text)
+        self.compact_dst = [torch.empty((n_keep_total,) + tuple(t.shape[1:]), dtype=t.dtype, device=dev)
+                            for t in self.compact_src]
+        self.compact_dst_off = _i32(w.compact_dst_off, dev)
         # ---- verification side --------------------------------------------------
         self.q_tree = w.q_tree.to(dev)
         self.k_pool = w.k_pool.to(dev)
@@ -80,14 +81,14 @@ class DeviceWorkload:
 
     def run_compact(self) -> None:
         cfg = self.cfg
-        for b, (src, dst) in enumerate(zip(self.compact_src, self.compact_dst)):
-            # hidden rows and KV rows may differ in width: one call per row width
-            groups = {}
-            for s, d in zip(src, dst):
-                groups.setdefault(s[0].numel() * s.element_size(), []).append((s, d))
-            for row_bytes, pairs in groups.items():
-                tw.ttp_compact(self.kept[b], cfg.R, 0, cfg.M, self.w.n_tot[b], [p[0] for p in pairs],
-                               [p[1] for p in pairs], row_bytes)
+        # hidden rows and KV rows may differ in width: one batched call per row width
+        groups = {}
+        for s, d in zip(self.compact_src, self.compact_dst):
+            groups.setdefault(s[0].numel() * s.element_size(), []).append((s, d))
+        for row_bytes, pairs in groups.items():
+            tw.ttp_compact_batched(self.kept, cfg.R, 0, cfg.M, self.n_tot, self.n_tot_max,
+                                   self.score_row_off, self.compact_dst_off, [p[0] for p in pairs],
+                                   [p[1] for p in pairs], row_bytes)
 
     def run_verify(self) -> None:
         tw.tree_verify_attn(self.q_tree, self.k_view, self.v_view, self.ctx_len, self.max_ctx_len,

@@ -264,7 +264,8 @@ class Workload:
     score_row_off: List[int]           # first row of sequence b in k_score
     q_sel: torch.Tensor                # [B][n_q_max][H][d_h]
     k_score: torch.Tensor              # [sum n_tot][H][d_h]
-    compact_src: List[List[torch.Tensor]]   # [B][n_tensors] each [n_tot_b][row_elems]
+    compact_src: List[torch.Tensor]    # [n_tensors] pools [sum n_tot][row_elems]; sequence b at score_row_off[b]
+    compact_dst_off: List[int]         # first destination row of sequence b (sum of kept rows before it)
     # ---- per verified instance (B*L, sequence-major: inst = b*L + layer) ----
     ctx_len: List[int]
     n_nodes: List[int]
@@ -324,16 +325,19 @@ def make_workload(cfg: Config, device="cpu", with_compact: bool = True,
         q_sel = torch.empty(0, dtype=dt, device=device)
         k_score = torch.empty(0, dtype=dt, device=device)
 
-    # compaction sources: hidden, then K and V of each compacted layer
-    compact_src: List[List[torch.Tensor]] = []
+    # compaction sources: hidden, then K and V of each compacted layer; every tensor is
+    # one pool holding all sequences back to back (same row offsets as k_score)
+    compact_src: List[torch.Tensor] = []
+    compact_dst_off, dacc = [], 0
+    for b in range(B):
+        compact_dst_off.append(dacc)
+        dacc += cfg.R + n_text[b]
     if with_compact:
-        for b in range(B):
-            ts = [normal(cfg.seed, _ST_COMPACT + 4096 * b, (n_tot[b], cfg.hidden), 1.0, dt, device)]
-            for l in range(cfg.compact_layers):
-                for kv in range(2):
-                    ts.append(normal(cfg.seed, _ST_COMPACT + 4096 * b + 1 + 2 * l + kv,
-                                     (n_tot[b], H * d_h), cfg.kv_std, dt, device))
-            compact_src.append(ts)
+        compact_src.append(normal(cfg.seed, _ST_COMPACT, (acc, cfg.hidden), 1.0, dt, device))
+        for l in range(cfg.compact_layers):
+            for kv in range(2):
+                compact_src.append(normal(cfg.seed, _ST_COMPACT + 1 + 2 * l + kv, (acc, H * d_h),
+                                          cfg.kv_std, dt, device))
 
     # verification caches: instance = (sequence, layer)
     n_keep = [cfg.R + n for n in n_text]
@@ -371,7 +375,7 @@ def make_workload(cfg: Config, device="cpu", with_compact: bool = True,
 
     return Workload(cfg=cfg, n_text=n_text, n_tot=n_tot, n_q=n_q, n_q_max=n_q_max, q_pos0=q_pos0,
                     score_row_off=score_row_off, q_sel=q_sel, k_score=k_score,
-                    compact_src=compact_src, ctx_len=ctx_len, n_nodes=n_nodes, parent=parent,
+                    compact_src=compact_src, compact_dst_off=compact_dst_off, ctx_len=ctx_len, n_nodes=n_nodes, parent=parent,
                     q_tree=q_tree, k_pool=k_pool, v_pool=v_pool, row_off=row_off,
                     page_table=page_table, max_pages=max_pages, draft=draft, argmax=argmx,
                     tree_seq=trees)

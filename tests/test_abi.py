@@ -46,7 +46,7 @@ def test_workspace_sizes():
     assert n > 0 and n % (32 * 26 * 130 * 4) == 0
     # 128 sequences fill the chip without splitting
     assert tw.workspace_bytes(tw.TW_CALL_TREE_VERIFY_ATTN, 128, 26, 32, 128, 282) == 0
-    assert tw.workspace_bytes(tw.TW_CALL_TTP_SCORE, 1, 64, 32, 128, 640) >= 32 * 64 * 640 * 4
+    assert tw.workspace_bytes(tw.TW_CALL_TTP_SCORE, 1, 64, 32, 128, 640) >= 32 * 576 * 4   # per-head partial sums
     assert tw.workspace_bytes(99, 1, 1, 1, 8, 1) == 0
     assert tw.workspace_bytes(tw.TW_CALL_TTP_SCORE, 0, 64, 32, 128, 640) == 0
 
@@ -74,6 +74,13 @@ def test_argument_validation_without_launch():
     bad = (ctypes.c_void_p * 2)(P, None)
     assert lib.tw_ttp_compact(P, 2, 0, 4, 10, bad, vp2, 2, 64, None) == tw.TW_ERR_INVALID_ARG
     assert lib.tw_ttp_compact(P, 2, 0, 4, 10, vp2, vp2, 0, 64, None) == tw.TW_OK
+    cb = lambda **kw: lib.tw_ttp_compact_batched(P, kw.get('R', 2), 0, 4, kw.get('n_tot', P), kw.get('nmax', 10), P, P,
+                                                 kw.get('B', 3), vp2, vp2, 2, 64, None)
+    assert cb(R=5) == tw.TW_ERR_INVALID_ARG
+    assert cb(nmax=3) == tw.TW_ERR_INVALID_ARG
+    assert cb(n_tot=None) == tw.TW_ERR_INVALID_ARG
+    assert cb(B=70000) == tw.TW_ERR_UNSUPPORTED
+    assert cb(B=0) == tw.TW_OK
 
     assert lib.tw_tree_accept(P, P, P, P, 65, 1, P, P, P, None) == tw.TW_ERR_UNSUPPORTED
     assert lib.tw_tree_accept(P, P, P, P, 0, 1, P, P, P, None) == tw.TW_ERR_INVALID_ARG

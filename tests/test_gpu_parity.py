@@ -292,6 +292,88 @@ def test_compact_bit_exact(tw, row_elems, dtype):
             assert torch.equal(d.cpu().view(torch.uint8), want.view(torch.uint8))
 
 
+def test_compact_batched_ragged_pools(tw):
+    # four sequences of different lengths in shared pools, span not at row 0
+    v0, M, R, row = 3, 50, 9, 96
+    n_text = [7, 30, 1, 12]
+    n_tot = [v0 + M + n for n in n_text]
+    src_off = [0]
+    for n in n_tot[:-1]:
+        src_off.append(src_off[-1] + n)
+    n_keep = [n - M + R for n in n_tot]
+    dst_off = [0]
+    for n in n_keep[:-1]:
+        dst_off.append(dst_off[-1] + n)
+    g = torch.Generator().manual_seed(5)
+    kept = torch.stack([torch.sort(torch.randperm(M, generator=g)[:R]).values for _ in n_tot]).to(torch.int32)
+    src = [torch.randint(0, 60000, (sum(n_tot), row), generator=g).to(torch.int32).view(torch.float32)
+           for _ in range(3)]
+    dsrc = [s_.to(DEV) for s_ in src]
+    ddst = [torch.zeros(sum(n_keep), row, dtype=torch.float32, device=DEV) for _ in src]
+    tw.ttp_compact_batched(kept.to(DEV), R, v0, M, _i32(n_tot), max(n_tot), _i32(src_off), _i32(dst_off),
+                           dsrc, ddst, row * 4)
+    torch.cuda.synchronize()
+    for s_, d in zip(src, ddst):
+        for b in range(4):
+            want = oracle.ttp_compact(kept[b], v0, M, s_[src_off[b]:src_off[b] + n_tot[b]])
+            got = d.cpu()[dst_off[b]:dst_off[b] + n_keep[b]]
+            assert torch.equal(got.view(torch.int32), want.view(torch.int32))
+
+
+# ----------------------------------------------------------------------------
+# ttp_score
+# ----------------------------------------------------------------------------
+def _check_score(tw, dtype, H, d_h, M, v0, n_text, n_q, causal, q_std=1.0, seed=1):
+    B = len(n_text)
+    n_tot = [v0 + M + n for n in n_text]
+    off, acc = [], 2
+    for n in n_tot:
+        off.append(acc)
+        acc += n + 1
+    n_q_max = max(n_q)
+    q = W.normal(seed, 1, (B, n_q_max, H, d_h), q_std, dtype)
+    k = W.normal(seed, 2, (acc, H, d_h), 1.0, dtype)
+    pos0 = [nt - nq for nt, nq in zip(n_tot, n_q)]
+    scale = 1 / math.sqrt(d_h)
+    want = oracle.ttp_score(q, k, n_q, pos0, n_tot, off, v0, M, scale, causal)
+    kd, ro = k.to(DEV), _i32(off)          # the view only holds pointers: keep the tensors alive
+    view = tw.kv_view(kd, row_off=ro)
+    nbytes = tw.workspace_bytes(tw.TW_CALL_TTP_SCORE, B, n_q_max, H, d_h, max(n_tot))
+    ws = torch.empty(nbytes // 4, dtype=torch.float32, device=DEV)
+    scores = torch.full((B, M), float("nan"), dtype=torch.float32, device=DEV)
+    tw.ttp_score(q.to(DEV), view, _i32(n_q), _i32(pos0), _i32(n_tot), max(n_tot), v0, M, scale, causal,
+                 scores, ws)
+    torch.cuda.synchronize()
+    got = scores.cpu().double()
+    assert torch.isfinite(got).all()
+    err = float((got - want).abs().max())
+    assert err <= SCORE_TOL, f"score error {err:.3e}"
+    again = torch.empty_like(scores)
+    tw.ttp_score(q.to(DEV), view, _i32(n_q), _i32(pos0), _i32(n_tot), max(n_tot), v0, M, scale, causal,
+                 again, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(again, scores)          # fixed summation order
+
+
+@pytest.mark.parametrize("n_q", [[1, 1, 1], [8, 5, 8], [33, 64, 40], [128, 100, 65]])
+@pytest.mark.parametrize("causal", [True, False])
+def test_score_bf16_matrix_core_path(tw, n_q, causal):
+    _check_score(tw, torch.bfloat16, 8, 128, 200, 0, [130, 128, 150], n_q, causal)
+
+
+def test_score_span_not_at_zero_sharp_and_small_heads(tw):
+    _check_score(tw, torch.bfloat16, 6, 128, 77, 37, [40, 33], [16, 33], True, q_std=6.0)
+    _check_score(tw, torch.bfloat16, 4, 64, 576, 0, [64], [64], True)
+    _check_score(tw, torch.bfloat16, 4, 128, 100, 5, [20], [20], False, q_std=6.0)
+
+
+def test_score_generic_path(tw):
+    _check_score(tw, torch.float32, 4, 64, 90, 3, [20, 9], [8, 9], True)
+    _check_score(tw, torch.float32, 2, 128, 70, 0, [33], [33], False, q_std=4.0)
+    _check_score(tw, torch.bfloat16, 2, 40, 70, 0, [17], [17], True)
+    _check_score(tw, torch.bfloat16, 2, 128, 70, 0, [140], [130], True)      # more than 128 scoring rows
+
+
 # ----------------------------------------------------------------------------
 # the five configurations, whole path
 # ----------------------------------------------------------------------------
@@ -318,11 +400,13 @@ def _path_parity(runner, cfg, verify_instances=None, check_compact_tensors=None)
             thr = torch.sort(want_sc[b], descending=True).values[R - 1]
             assert all(abs(float(want_sc[b, m] - thr)) <= 2 * SCORE_TOL for m in diff)
     # S3 compact: bit-exact given the kept indices the GPU selected
-    for b in range(B):
-        idx = range(len(w.compact_src[b])) if check_compact_tensors is None else check_compact_tensors
-        for t in idx:
-            want = oracle.ttp_compact(got_kept[b], 0, M, w.compact_src[b][t])
-            assert torch.equal(dw.compact_dst[b][t].cpu().view(torch.int16), want.view(torch.int16)), (b, t)
+    idx = range(len(w.compact_src)) if check_compact_tensors is None else check_compact_tensors
+    for t in idx:
+        got_dst = dw.compact_dst[t].cpu()
+        for b in range(B):
+            s0, d0, n_keep = w.score_row_off[b], w.compact_dst_off[b], R + w.n_text[b]
+            want = oracle.ttp_compact(got_kept[b], 0, M, w.compact_src[t][s0:s0 + w.n_tot[b]])
+            assert torch.equal(got_dst[d0:d0 + n_keep].view(torch.int16), want.view(torch.int16)), (b, t)
     # S5 verify on all or on sampled instances
     insts = list(range(dw.n_inst)) if verify_instances is None else verify_instances
     sub = lambda xs: [xs[i] for i in insts]

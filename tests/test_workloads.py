@@ -35,7 +35,7 @@ def test_config_shapes():
     w = W.make_workload(W.CONFIGS["cfg0"])
     assert w.k_score.shape == (608, 4, 64) and w.q_sel.shape == (1, 8, 4, 64)
     assert w.ctx_len == [96] and w.k_pool.shape == (104, 4, 64) and w.k_pool.dtype == torch.float32
-    assert len(w.compact_src[0]) == 3 and w.compact_src[0][0].shape == (608, 256)
+    assert len(w.compact_src) == 3 and w.compact_src[0].shape == (608, 256)
     w = W.make_workload(W.CONFIGS["cfg1"], with_compact=False)
     assert w.ctx_len == [256] and w.n_q == [64] and w.k_pool.shape == (282, 32, 128)
     assert w.k_pool.dtype == torch.bfloat16
