@@ -42,6 +42,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--batch", type=int, default=128, help="independent sequences per step")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the CPU oracle leg (0 = skip)")
+    ap.add_argument("--single-iters", type=int, default=200,
+                    help="launches of the single-sequence latency leg (0 = skip)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is single-GPU; run with --gpus 1 (no multi-GPU path exists)",
@@ -83,16 +85,18 @@ def main():
     achieved = vbytes / (ker_avg * 1e-3) / 1e9
 
     # single-instance latency of the graded kernel (one sequence, split + combine launches)
-    w1 = W.make_workload(W.CONFIGS["cfg1"], device=dev, with_compact=False, with_score=False)
-    d1 = runner.DeviceWorkload(w1, dev)
-    for _ in range(10):
-        d1.run_verify()
-    torch.cuda.synchronize()
-    t2 = time.perf_counter()
-    for _ in range(200):
-        d1.run_verify()
-    torch.cuda.synchronize()
-    single_us = (time.perf_counter() - t2) / 200 * 1e6
+    single_us = None
+    if args.single_iters > 0:
+        w1 = W.make_workload(W.CONFIGS["cfg1"], device=dev, with_compact=False, with_score=False)
+        d1 = runner.DeviceWorkload(w1, dev)
+        for _ in range(10):
+            d1.run_verify()
+        torch.cuda.synchronize()
+        t2 = time.perf_counter()
+        for _ in range(args.single_iters):
+            d1.run_verify()
+        torch.cuda.synchronize()
+        single_us = (time.perf_counter() - t2) / args.single_iters * 1e6
 
     cpu = None
     if args.cpu_seconds > 0:
@@ -123,12 +127,14 @@ def main():
                "sample": f"whole path on the first {n_done} of {cfg.B} sequences of the same batch "
                          f"({t_cpu:.1f} s of fp64 C, OpenMP over heads/rows)"}
 
+    # HBM bytes per launch from the committed rocprofv3 counter summary (same workload only)
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", "verify_traffic.json")
+    tpath = os.path.join(ROOT, "profiles", "verify_mfma_cfg1x128_hbm_traffic.md")
     if os.path.exists(tpath):
-        rec = json.load(open(tpath))
-        if rec.get("batch") == args.batch:
-            traffic = rec.get("hbm_bytes_per_launch")
+        rec = dict(ln.split("=", 1) for ln in open(tpath) if ln.count("=") == 1 and ln[0].isalpha())
+        rec = {k.strip(): v.strip() for k, v in rec.items()}
+        if rec.get("batch") == str(args.batch) and "hbm_bytes_per_launch" in rec:
+            traffic = int(rec["hbm_bytes_per_launch"])
 
     out = {
         "metric": "tree-verify attention tokens/s (whole hot-path step), LLaVA-7B shape",
