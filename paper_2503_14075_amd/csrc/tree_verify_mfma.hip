@@ -140,8 +140,8 @@ __global__ __launch_bounds__(kMfThreads, (NB == 1 ? 2 : 1)) void verify_mfma_ker
             else
                 prow = row0 + r;
             prow = prow < 0 ? 0 : (prow > last_pool_row ? last_pool_row : prow);
-            pk[j] = *(const u32x4*)(kbase + prow * pool_stride);
-            pv[j] = *(const u32x4*)(vbase + prow * pool_stride);
+            pk[j] = __builtin_nontemporal_load((const u32x4*)(kbase + prow * pool_stride));   // streamed once
+            pv[j] = __builtin_nontemporal_load((const u32x4*)(vbase + prow * pool_stride));
         }
     };
 

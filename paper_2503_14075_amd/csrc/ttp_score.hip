@@ -360,8 +360,17 @@ __global__ __launch_bounds__(256) void score_reduce_kernel(ScoreArgs a) {
     if (m >= a.M) return;
     int n_q = a.n_q ? a.n_q[b] : a.n_q_max;
     n_q = n_q < 1 ? 1 : (n_q > a.n_q_max ? a.n_q_max : n_q);
+    const float* p = a.ws + (int64_t)b * a.H * a.M + m;
     float acc = 0.f;
-    for (int h = 0; h < a.H; ++h) acc += a.ws[((int64_t)b * a.H + h) * a.M + m];
+    int h = 0;
+    for (; h + 8 <= a.H; h += 8) {   // eight independent loads in flight, added in head order
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = p[(int64_t)(h + u) * a.M];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc += v[u];
+    }
+    for (; h < a.H; ++h) acc += p[(int64_t)h * a.M];
     a.scores[(int64_t)b * a.M + m] = acc / ((float)a.H * (float)n_q);
 }
 
