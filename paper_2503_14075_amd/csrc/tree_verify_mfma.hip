@@ -212,14 +212,14 @@ __global__ __launch_bounds__(kMfThreads, (NB == 1 ? 2 : 1)) void verify_mfma_ker
             mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
             const float m_new = fmaxf(run_m[nb], mx);
             const float m_safe = m_new == -INFINITY ? 0.f : m_new;
-            alpha[nb] = exp2f(run_m[nb] - m_safe);   // 0 on the first visible chunk, 1 when the maximum holds
+            alpha[nb] = fast_exp2(run_m[nb] - m_safe);   // 0 on the first visible chunk, 1 when the maximum holds
             any_rescale = any_rescale || (alpha[nb] != 1.f);
             float psum = 0.f;
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 // the row sum is taken over the bf16-rounded weights that enter the PV
                 // product, so the normalised weights still sum to one
-                const __bf16 pb = (__bf16)exp2f(x[r] - m_safe);
+                const __bf16 pb = (__bf16)fast_exp2(x[r] - m_safe);
                 psum += (float)pb;
                 pf[nb][r >> 3][r & 7] = pb;
             }

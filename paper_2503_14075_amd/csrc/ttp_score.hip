@@ -148,8 +148,8 @@ __global__ __launch_bounds__(kScMfThreads, (NB <= 2 ? 2 : 1)) void score_mfma_ke
             const float m_safe = m_new == -INFINITY ? 0.f : m_new;
             float psum = 0.f;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) psum += exp2f(x[r] - m_safe);
-            run_l[nb] = run_l[nb] * exp2f(run_m[nb] - m_safe) + psum;
+            for (int r = 0; r < 16; ++r) psum += fast_exp2(x[r] - m_safe);
+            run_l[nb] = run_l[nb] * fast_exp2(run_m[nb] - m_safe) + psum;
             run_m[nb] = m_new;
         }
     }
@@ -159,7 +159,7 @@ __global__ __launch_bounds__(kScMfThreads, (NB <= 2 ? 2 : 1)) void score_mfma_ke
         const float om = __shfl_xor(run_m[nb], 32, 64), ol = __shfl_xor(run_l[nb], 32, 64);
         const float m = fmaxf(run_m[nb], om);
         const float m_safe = m == -INFINITY ? 0.f : m;
-        const float l = run_l[nb] * exp2f(run_m[nb] - m_safe) + ol * exp2f(om - m_safe);
+        const float l = run_l[nb] * fast_exp2(run_m[nb] - m_safe) + ol * fast_exp2(om - m_safe);
         const int i = 32 * nb + li;
         if (g == 0) s_stat[i] = (i < n_q && l > 0.f) ? m + log2f(l) : INFINITY;   // +inf: row contributes nothing
     }
@@ -204,7 +204,7 @@ __global__ __launch_bounds__(kScMfThreads, (NB <= 2 ? 2 : 1)) void score_mfma_ke
                     const int ve = a.causal ? min(pos0 + i + 1, n_tot) : n_tot;
                     if (j >= ve) x = -INFINITY;
                 }
-                acc += exp2f(x);
+                acc += fast_exp2(x);
             }
         }
         acc += __shfl_xor(acc, 32, 64);
@@ -396,7 +396,9 @@ static hipError_t launch_score_mfma_rows(const ScoreArgs& a, hipStream_t s) {
 hipError_t launch_score(const ScoreArgs& a, int dtype, hipStream_t s) {
     if (a.B == 0 || a.M == 0) return hipSuccess;
     hipError_t e;
-    if (dtype == TW_BF16 && (a.d_h == 64 || a.d_h == 128) && a.n_q_max <= 128) {
+    if (score_resident_supported(a, dtype)) {
+        e = launch_score_resident(a, s);
+    } else if (dtype == TW_BF16 && (a.d_h == 64 || a.d_h == 128) && a.n_q_max <= 128) {
         e = a.d_h == 128 ? launch_score_mfma_rows<128>(a, s) : launch_score_mfma_rows<64>(a, s);
     } else {
         const size_t lds = ((size_t)(kScRows + kScKeys) * (a.d_h + 1) + (size_t)kScRows * (kScKeys + 1)) *

@@ -97,6 +97,8 @@ struct ScoreArgs {
 };
 size_t score_workspace_bytes(int B, int H, int n_q_max, int n_tot_max);
 hipError_t launch_score(const ScoreArgs& a, int dtype, hipStream_t s);
+bool score_resident_supported(const ScoreArgs& a, int dtype);
+hipError_t launch_score_resident(const ScoreArgs& a, hipStream_t s);
 
 // --- select / compact / tree -------------------------------------------------
 hipError_t launch_select(const float* scores, int B, int M, int R, int32_t* kept, hipStream_t s);

@@ -367,6 +367,16 @@ def test_score_span_not_at_zero_sharp_and_small_heads(tw):
     _check_score(tw, torch.bfloat16, 4, 128, 100, 5, [20], [20], False, q_std=6.0)
 
 
+def test_score_register_resident_boundary(tw):
+    # 768 keys is the longest prompt whose logits stay in registers; 769 takes the two-pass kernel
+    _check_score(tw, torch.bfloat16, 4, 128, 576, 0, [192, 100], [64, 33], True)
+    _check_score(tw, torch.bfloat16, 4, 128, 576, 0, [193, 100], [64, 33], True)
+    _check_score(tw, torch.bfloat16, 5, 128, 700, 20, [48], [17], False, q_std=5.0)
+    # many (sequence, head) pairs per workgroup: 40 sequences x 32 heads on 256 compute units
+    _check_score(tw, torch.bfloat16, 32, 128, 100, 0, [9 + (b % 7) for b in range(40)],
+                 [1 + (b % 9) for b in range(40)], True)
+
+
 def test_score_generic_path(tw):
     _check_score(tw, torch.float32, 4, 64, 90, 3, [20, 9], [8, 9], True)
     _check_score(tw, torch.float32, 2, 128, 70, 0, [33], [33], False, q_std=4.0)
