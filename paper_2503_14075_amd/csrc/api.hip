@@ -24,23 +24,36 @@ int view_status(const tw_kv_view* v, bool allow_paged) {
 
 namespace tw {
 
-// Split the cache rows of each (sequence, head) over several workgroups until
-// the launch has about four workgroups per compute unit, but never below 64
-// rows per split.
-int verify_plan_splits(int B, int H, int T_max, int max_rows) {
-    (void)T_max;
-    const long pairs = (long)B * H;
-    if (pairs <= 0) return 1;
-    long want = (1024 + pairs - 1) / pairs;
-    long cap = max_rows / 64;
+// Wavefront layout and row split of tree verification.  A node block is 32 tree rows.  With at
+// least 2048 (sequence, head, node block) units every wavefront takes its own unit (four heads,
+// or two heads x two blocks, per workgroup); with fewer, a workgroup takes one head and its
+// wavefronts share the head's rows round-robin.  The cache rows are split over several workgroups
+// only while the launch has fewer than 512 workgroups, and never below 256 rows per split (a
+// split costs a partial-output round trip worth about 65 rows of K and V).
+VerifyPlan verify_plan(int B, int H, int T_max, int max_rows) {
+    VerifyPlan p;
+    p.n_blk = T_max > 32 ? 2 : 1;
+    const long units = (long)B * H * p.n_blk;
+    long wgs;
+    if (units >= 2048) {
+        p.heads_per_wg = 4 / p.n_blk;
+        p.n_phase = 1;
+        wgs = (long)B * ((H + p.heads_per_wg - 1) / p.heads_per_wg);
+    } else {
+        p.heads_per_wg = 1;
+        p.n_phase = 4 / p.n_blk;
+        wgs = (long)B * H;
+    }
+    long want = wgs >= 512 || wgs <= 0 ? 1 : (512 + wgs - 1) / wgs;
+    long cap = max_rows / 256;
     if (cap < 1) cap = 1;
     if (cap > 64) cap = 64;
-    if (want > cap) want = cap;
-    return want < 1 ? 1 : (int)want;
+    p.n_splits = (int)(want < cap ? want : cap);
+    return p;
 }
 
 size_t verify_workspace_bytes(int B, int H, int T_max, int d_h, int max_rows) {
-    const int ns = verify_plan_splits(B, H, T_max, max_rows);
+    const int ns = verify_plan(B, H, T_max, max_rows).n_splits;
     if (ns == 1) return 0;
     return (size_t)ns * B * H * T_max * (d_h + 2) * sizeof(float);
 }
@@ -187,7 +200,11 @@ int32_t tw_tree_verify_attn(const void* q, const tw_kv_view* k, const tw_kv_view
     a.d_h = k->d_h;
     a.max_rows = max_rows;
     a.scale = scale;
-    a.n_splits = verify_plan_splits(B, a.H, T_max, max_rows);
+    const VerifyPlan plan = verify_plan(B, a.H, T_max, max_rows);
+    a.n_splits = plan.n_splits;
+    a.n_blk = plan.n_blk;
+    a.n_phase = plan.n_phase;
+    a.heads_per_wg = plan.heads_per_wg;
     a.part_o = nullptr;
     a.part_ml = nullptr;
     if (a.n_splits > 1) {

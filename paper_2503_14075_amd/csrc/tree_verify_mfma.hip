@@ -4,12 +4,22 @@
 // head) is fetched from HBM once and shared by all tree rows.
 //
 // Decomposition
-//   grid (ceil(H/4), B, n_splits), 256 threads.  Wavefront w of a workgroup owns
-//   head 4*blockIdx.x + w and walks the split's cache rows in chunks of 32.  The
-//   four wavefronts never synchronise after the prologue; each has a private LDS
-//   staging area.  Per chunk a wavefront
-//     1. stores the prefetched K and V rows (16-byte lanes, fully coalesced
-//        256-byte row segments) into LDS and issues the loads of the next chunk,
+//   A wavefront owns one work unit = (head, block of 32 tree nodes, row phase).
+//   The four wavefronts of a workgroup split as  heads_per_wg x n_blk x n_phase = 4:
+//     T <= 32, many units   4 heads x 1 block x 1 phase       verify_mfma_kernel
+//     T <= 32, few units    1 head  x 1 block x 4 phases      verify_mfma_kernel
+//     T <= 64, many units   2 heads x 2 blocks x 1 phase      verify_mfma_pair_kernel
+//     T <= 64, few units    1 head  x 2 blocks x 2 phases     verify_mfma_pair_kernel
+//   Phases take the 32-row chunks of a head round-robin and merge through LDS at the end.
+//   In the pair kernel the two node blocks of a head need the same K/V rows: one wavefront
+//   loads the K chunk, its partner the V chunk, into a stage they share (double-buffered,
+//   one workgroup barrier per chunk, loads two chunks ahead).
+//   grid (ceil(H / heads_per_wg), B, n_splits); n_splits > 1 additionally splits the cache
+//   rows over workgroups, partial (max, sum, O) go to the workspace for verify_combine_kernel.
+//
+// Per 32-row chunk a wavefront
+//     1. stores prefetched K/V rows (16-byte lanes, fully coalesced 256-byte row segments)
+//        into the LDS stage and issues the loads of a later chunk,
 //     2. S^T[row][node] = K . Q^T with v_mfma_f32_32x32x16_bf16 (A = K rows read
 //        back from LDS as 16-byte fragments, B = Q fragments kept in registers),
 //     3. online softmax per node: the 32x32 accumulator layout gives every lane
@@ -19,9 +29,6 @@
 //        is permuted, so P never leaves registers; V^T fragments are gathered
 //        from LDS (one 8-byte read per row, regrouped with byte permutes).
 //   Exponentials run in base 2 with scale*log2(e) folded into the logits.
-//
-// MFMA operand layouts used (lane l, g = l/32, i = l%32):
-//   A[i][8g+e], B[8g+e][i] for e = 0..7;  D[8*(r/4) + 4g + r%4][i] for r = 0..15.
 #include "mfma_util.h"
 #include "twig_internal.h"
 
@@ -40,12 +47,247 @@ struct MfCfg {
     static constexpr int kLoads = kChunk / kRowsPerLoad;  // 16-byte loads per lane per tensor
     static constexpr int kDC = DH / 16;             // reduction chunks of QK^T
     static constexpr int kNQ = DH / 32;             // output column blocks of PV
-    static constexpr int kWaveLds = kChunk * (kKStride + kVStride);
+    static constexpr int kStage = kChunk * (kKStride + kVStride);   // one K+V chunk
+    static constexpr int kOStride = DH + 4;         // floats per node row in the merge buffer
+    static constexpr int kMergeLds = 4 * 32 * kOStride * 4 + 4 * 32 * 2 * 4;   // O tiles + (max, sum)
+    static constexpr int kLds = 4 * kStage > kMergeLds ? 4 * kStage : kMergeLds;
 };
 
-// K and V share one row mapping (same row_off / page_table) on this path.
-template <int DH, int NB, bool PAGED>
-__global__ __launch_bounds__(kMfThreads, (NB == 1 ? 2 : 1)) void verify_mfma_kernel(VerifyArgs a) {
+// Per-wavefront attention state of one (head, node block).
+template <int DH>
+struct WaveState {
+    bf16x8 qf[MfCfg<DH>::kDC];      // Q fragments (B operand): lane (i, g) holds Q[node][16c + 8g .. +7]
+    floatx16 o[MfCfg<DH>::kNQ];     // O^T accumulators, column block q holds columns kNQ*i + q
+    float run_m, run_l;             // running maximum (base-2 units) and this lane's share of the row sum
+    uint64_t anc;                   // ancestor-or-self mask of the lane's node
+};
+
+template <int DH>
+__device__ __forceinline__ void load_q(WaveState<DH>& w, const VerifyArgs& a, int b, int h, int t, int T, int g) {
+    using Cf = MfCfg<DH>;
+    const int tc = t < T ? t : T - 1;
+    const u32x4* src = (const u32x4*)((const uint16_t*)a.q + (((int64_t)b * a.T_max + tc) * a.H + h) * DH + 8 * g);
+#pragma unroll
+    for (int c = 0; c < Cf::kDC; ++c) {
+        u32x4 v = src[2 * c];
+        if (t >= T) v = (u32x4){0u, 0u, 0u, 0u};   // padding nodes
+        w.qf[c] = as_bf16x8(v);
+    }
+#pragma unroll
+    for (int q = 0; q < Cf::kNQ; ++q)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) w.o[q][r] = 0.f;
+    w.run_m = -INFINITY;
+    w.run_l = 0.f;
+}
+
+// Steps 2-4 for the chunk staged at (ldsK, ldsV) whose first cache row is `base`.
+template <int DH>
+__device__ __forceinline__ void process_chunk(WaveState<DH>& w, const unsigned char* ldsK,
+                                              const unsigned char* ldsV, int base, int C, int n_rows,
+                                              float sl2, int g, int li) {
+    using Cf = MfCfg<DH>;
+    floatx16 s;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s[r] = 0.f;
+#pragma unroll
+    for (int c = 0; c < Cf::kDC; ++c) {
+        const bf16x8 kf = as_bf16x8(*(const u32x4*)(ldsK + li * Cf::kKStride + 32 * c + 16 * g));
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, w.qf[c], s, 0, 0, 0);
+    }
+    const bool need_mask = base + kChunk > C;
+    bf16x8 pf[2];
+    float x[16], mx = -INFINITY;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        x[r] = s[r] * sl2;
+        if (need_mask) {
+            const int row = base + acc_row(r, g);
+            const bool vis = row < C || (row < n_rows && ((w.anc >> (row - C)) & 1ull));
+            x[r] = vis ? x[r] : -INFINITY;
+        }
+        mx = fmaxf(mx, x[r]);
+    }
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float m_new = fmaxf(w.run_m, mx);
+    const float m_safe = m_new == -INFINITY ? 0.f : m_new;
+    const float alpha = fast_exp2(w.run_m - m_safe);   // 0 on the first visible chunk, 1 when the maximum holds
+    float psum = 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        // the row sum is taken over the bf16-rounded weights that enter the PV
+        // product, so the normalised weights still sum to one
+        const __bf16 pb = (__bf16)fast_exp2(x[r] - m_safe);
+        psum += (float)pb;
+        pf[r >> 3][r & 7] = pb;
+    }
+    w.run_l = w.run_l * alpha + psum;
+    w.run_m = m_new;
+    if (__any(alpha != 1.f)) {
+#pragma unroll
+        for (int q = 0; q < Cf::kNQ; ++q)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) w.o[q][r] *= alpha;
+    }
+    // reduction slot (g, e) of half c2 is chunk row acc_row(8*c2 + e, g)
+#pragma unroll
+    for (int c2 = 0; c2 < 2; ++c2) {
+        uint32_t v[8][Cf::kNQ / 2];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const unsigned char* p = ldsV + acc_row(8 * c2 + e, g) * Cf::kVStride + li * (Cf::kNQ * 2);
+            if (Cf::kNQ == 4) {
+                const uint2 t2 = *(const uint2*)p;
+                v[e][0] = t2.x;
+                v[e][Cf::kNQ / 2 - 1] = t2.y;
+            } else {
+                v[e][0] = *(const uint32_t*)p;
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < Cf::kNQ; ++q) {
+            u32x4 av;
+            const uint32_t sel = (q & 1) ? 0x07060302u : 0x05040100u;
+            av.x = __builtin_amdgcn_perm(v[1][q >> 1], v[0][q >> 1], sel);
+            av.y = __builtin_amdgcn_perm(v[3][q >> 1], v[2][q >> 1], sel);
+            av.z = __builtin_amdgcn_perm(v[5][q >> 1], v[4][q >> 1], sel);
+            av.w = __builtin_amdgcn_perm(v[7][q >> 1], v[6][q >> 1], sel);
+            w.o[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(av), pf[c2], w.o[q], 0, 0, 0);
+        }
+    }
+}
+
+// One unit per wavefront (n_phase == 1): normalise, or hand the partial to the combine kernel.
+template <int DH>
+__device__ __forceinline__ void epilogue_direct(const WaveState<DH>& w, const VerifyArgs& a, int b, int h,
+                                                int t, int split, int g) {
+    using Cf = MfCfg<DH>;
+    const float l = w.run_l + __shfl_xor(w.run_l, 32, 64);
+    float* dst;
+    float mul;
+    if (a.n_splits == 1) {
+        dst = a.out + (((int64_t)b * a.T_max + t) * a.H + h) * DH;
+        mul = 1.f / l;
+    } else {
+        const int64_t slot = (((int64_t)split * a.B + b) * a.H + h) * a.T_max + t;
+        dst = a.part_o + slot * DH;
+        mul = 1.f;
+        if (g == 0) {
+            a.part_ml[slot * 2] = w.run_m * kLn2;   // natural-log units for the combine
+            a.part_ml[slot * 2 + 1] = l;
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        float* p = dst + Cf::kNQ * acc_row(r, g);
+        if (Cf::kNQ == 4)
+            *(float4*)p = make_float4(w.o[0][r] * mul, w.o[1][r] * mul, w.o[Cf::kNQ - 2][r] * mul,
+                                      w.o[Cf::kNQ - 1][r] * mul);
+        else
+            *(float2*)p = make_float2(w.o[0][r] * mul, w.o[1][r] * mul);
+    }
+}
+
+// Row phases of one head merge through LDS.  Merge slot of a wavefront = blk * n_phase + phase.
+// Must be entered by the whole workgroup after its last use of the stages.
+template <int DH>
+__device__ __forceinline__ void epilogue_merge(const WaveState<DH>& w, const VerifyArgs& a, unsigned char* lds,
+                                               int b, int h, int T, int split, int slot_w, int n_blk,
+                                               int n_phase, int g, int li, int tid) {
+    using Cf = MfCfg<DH>;
+    __syncthreads();
+    float* mo = (float*)lds;                      // [4 slots][32 nodes][kOStride]
+    float* mstat = mo + 4 * 32 * Cf::kOStride;    // [4 slots][32 nodes][2]
+    const float l_wave = w.run_l + __shfl_xor(w.run_l, 32, 64);
+    float* mine = mo + (slot_w * 32 + li) * Cf::kOStride;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        float* p = mine + Cf::kNQ * acc_row(r, g);
+        if (Cf::kNQ == 4)
+            *(float4*)p = make_float4(w.o[0][r], w.o[1][r], w.o[Cf::kNQ - 2][r], w.o[Cf::kNQ - 1][r]);
+        else
+            *(float2*)p = make_float2(w.o[0][r], w.o[1][r]);
+    }
+    if (g == 0) {
+        mstat[(slot_w * 32 + li) * 2] = w.run_m;
+        mstat[(slot_w * 32 + li) * 2 + 1] = l_wave;
+    }
+    __syncthreads();
+    // thread -> (node, 4 output columns); phases are added in index order
+    constexpr int kPerRow = DH / 4;
+    for (int idx = tid; idx < n_blk * 32 * kPerRow; idx += kMfThreads) {
+        const int node = idx / kPerRow, d4 = idx % kPerRow;
+        const int nblk = node >> 5, nl = node & 31;
+        if (node >= T) continue;
+        float m = -INFINITY;
+        for (int p = 0; p < n_phase; ++p) m = fmaxf(m, mstat[((nblk * n_phase + p) * 32 + nl) * 2]);
+        const float m_safe = m == -INFINITY ? 0.f : m;
+        float l = 0.f;
+        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int p = 0; p < n_phase; ++p) {
+            const int s = nblk * n_phase + p;
+            const float sc = fast_exp2(mstat[(s * 32 + nl) * 2] - m_safe);
+            l += mstat[(s * 32 + nl) * 2 + 1] * sc;
+            const float4 v = *(const float4*)(mo + (s * 32 + nl) * Cf::kOStride + 4 * d4);
+            acc.x += v.x * sc;
+            acc.y += v.y * sc;
+            acc.z += v.z * sc;
+            acc.w += v.w * sc;
+        }
+        if (a.n_splits == 1) {
+            const float inv = 1.f / l;
+            float* dst = a.out + (((int64_t)b * a.T_max + node) * a.H + h) * DH + 4 * d4;
+            *(float4*)dst = make_float4(acc.x * inv, acc.y * inv, acc.z * inv, acc.w * inv);
+        } else {
+            const int64_t slot = (((int64_t)split * a.B + b) * a.H + h) * a.T_max + node;
+            *(float4*)(a.part_o + slot * DH + 4 * d4) = acc;
+            if (d4 == 0) {
+                a.part_ml[slot * 2] = m * kLn2;
+                a.part_ml[slot * 2 + 1] = l;
+            }
+        }
+    }
+}
+
+// Row range of a split and the tree of a sequence, common to both kernels.
+struct SeqInfo {
+    int T, C, n_rows, r_begin, r_end;
+};
+__device__ __forceinline__ SeqInfo seq_info(const VerifyArgs& a, int b, int split, int tid, int* s_parent,
+                                            unsigned long long* s_anc) {
+    SeqInfo s;
+    int T = a.n_nodes[b];
+    s.T = T < 1 ? 1 : (T > a.T_max ? a.T_max : T);
+    int C = a.ctx_len[b];
+    s.C = C < 0 ? 0 : (C > a.max_rows - a.T_max ? a.max_rows - a.T_max : C);
+    s.n_rows = s.C + s.T;
+    int per = (s.n_rows + a.n_splits - 1) / a.n_splits;
+    per = (per + kChunk - 1) / kChunk * kChunk;
+    s.r_begin = min(split * per, s.n_rows);
+    s.r_end = min(s.r_begin + per, s.n_rows);
+    if (tid < TW_MAX_TREE) s_parent[tid] = tid < s.T ? a.parent[(int64_t)b * a.T_max + tid] : 0;
+    __syncthreads();
+    if (tid < TW_MAX_TREE) s_anc[tid] = tid < s.T ? ancestor_mask(s_parent, tid) : 0ull;
+    __syncthreads();
+    return s;
+}
+
+// Pool row of cache row r (paged or contiguous), clamped into the pool.
+template <bool PAGED>
+__device__ __forceinline__ uint32_t pool_row_of(const VerifyArgs& a, int r, int page, int64_t row0) {
+    int64_t prow = PAGED ? (int64_t)page * a.k.page_rows + (r % a.k.page_rows) : row0 + r;
+    const int64_t last = a.k.pool_rows - 1;
+    prow = prow < 0 ? 0 : (prow > last ? last : prow);
+    return (uint32_t)prow;
+}
+
+// ---------------------------------------------------------------------------------------------
+// T <= 32: every wavefront stages its own chunks (K and V) in a private LDS area; no workgroup
+// barrier inside the loop.  K and V share one row mapping (same row_off / page_table).
+// STREAM: the loads carry the non-temporal hint (each byte is used once).
+// ---------------------------------------------------------------------------------------------
+template <int DH, bool PAGED>
+__global__ __launch_bounds__(kMfThreads, 2) void verify_mfma_kernel(VerifyArgs a) {
     using Cf = MfCfg<DH>;
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     __shared__ int s_parent[TW_MAX_TREE];
@@ -54,66 +296,32 @@ __global__ __launch_bounds__(kMfThreads, (NB == 1 ? 2 : 1)) void verify_mfma_ker
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int g = lane >> 5, li = lane & 31;
     const int b = blockIdx.y, split = blockIdx.z;
-    const int h = blockIdx.x * 4 + wave;
-    int T = a.n_nodes[b];
-    T = T < 1 ? 1 : (T > a.T_max ? a.T_max : T);
-    int C = a.ctx_len[b];
-    C = C < 0 ? 0 : (C > a.max_rows - a.T_max ? a.max_rows - a.T_max : C);
-    const int n_rows = C + T;
-    int per = (n_rows + a.n_splits - 1) / a.n_splits;
-    per = (per + kChunk - 1) / kChunk * kChunk;
-    const int r_begin = min(split * per, n_rows), r_end = min(r_begin + per, n_rows);
+    const int n_phase = a.n_phase;               // 1 (four heads per workgroup) or 4 (one head)
+    const int phase = wave % n_phase;
+    const int h = blockIdx.x * a.heads_per_wg + wave / n_phase;
+    const SeqInfo sq = seq_info(a, b, split, tid, s_parent, s_anc);
+    const bool active = h < a.H;
+    const int hc = active ? h : a.H - 1;
+    const int t = li;                            // this lane's tree node
 
-    if (tid < TW_MAX_TREE) s_parent[tid] = tid < T ? a.parent[(int64_t)b * a.T_max + tid] : 0;
-    __syncthreads();
-    if (tid < TW_MAX_TREE) s_anc[tid] = tid < T ? ancestor_mask(s_parent, tid) : 0ull;
-    __syncthreads();
-    if (h >= a.H) return;
-
-    unsigned char* ldsK = lds + wave * Cf::kWaveLds;
+    unsigned char* ldsK = lds + wave * Cf::kStage;
     unsigned char* ldsV = ldsK + kChunk * Cf::kKStride;
-
-    // Q fragments (B operand): lane (i, g) holds Q[node 32nb+i][16c + 8g .. +7]; padding nodes are zero
-    bf16x8 qf[NB][Cf::kDC];
-    uint64_t anc[NB];
-    const uint16_t* qb = (const uint16_t*)a.q;
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb) {
-        const int t = 32 * nb + li;
-        const int tc = t < T ? t : T - 1;
-        anc[nb] = s_anc[t];
-        const u32x4* src = (const u32x4*)(qb + (((int64_t)b * a.T_max + tc) * a.H + h) * DH + 8 * g);
-#pragma unroll
-        for (int c = 0; c < Cf::kDC; ++c) {
-            u32x4 v = src[2 * c];
-            if (t >= T) v = (u32x4){0u, 0u, 0u, 0u};
-            qf[nb][c] = as_bf16x8(v);
-        }
-    }
-
-    floatx16 o[NB][Cf::kNQ];
-    float run_m[NB], run_l[NB];
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb) {
-        run_m[nb] = -INFINITY;
-        run_l[nb] = 0.f;
-#pragma unroll
-        for (int q = 0; q < Cf::kNQ; ++q)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) o[nb][q][r] = 0.f;
-    }
+    WaveState<DH> w;
+    w.anc = s_anc[t];
+    load_q(w, a, b, hc, t, sq.T, g);
     const float sl2 = a.scale * kLog2e;
 
     // lane's share of a chunk load: row (lane / lanes_per_row) + rows_per_load * j,
     // 16-byte column lane % lanes_per_row of the head's segment
     const int ld_row = lane / Cf::kLanesPerRow, ld_col = lane % Cf::kLanesPerRow;
-    const unsigned char* kbase = (const unsigned char*)a.k.base + (int64_t)h * Cf::kRowB + ld_col * 16;
-    const unsigned char* vbase = (const unsigned char*)a.v.base + (int64_t)h * Cf::kRowB + ld_col * 16;
-    const int64_t pool_stride = (int64_t)a.H * Cf::kRowB;
-    const int64_t last_pool_row = a.k.pool_rows - 1;
+    const unsigned char* kbase = (const unsigned char*)a.k.base + (int64_t)hc * Cf::kRowB + ld_col * 16;
+    const unsigned char* vbase = (const unsigned char*)a.v.base + (int64_t)hc * Cf::kRowB + ld_col * 16;
+    const uint32_t pool_stride = (uint32_t)(a.H * Cf::kRowB);
     const int32_t* ptab = PAGED ? a.k.page_table + (int64_t)b * a.k.max_pages : nullptr;
     const int64_t row0 = PAGED ? 0 : (int64_t)a.k.row_off[b];
-    const int last_row = r_end - 1;   // loads past the split re-read its last row (cached) and are masked
+    // loads past the split re-read its last row (cached) and are masked
+    const int last_row = sq.r_end > sq.r_begin ? sq.r_end - 1 : sq.r_begin;
+    const int step = kChunk * n_phase;
 
     // Paged caches: the page of every row this lane loads, looked up two chunks ahead
     // so the dependent data loads never wait on a table read.
@@ -134,199 +342,153 @@ __global__ __launch_bounds__(kMfThreads, (NB == 1 ? 2 : 1)) void verify_mfma_ker
         for (int j = 0; j < Cf::kLoads; ++j) {
             int r = base + ld_row + Cf::kRowsPerLoad * j;
             r = r < last_row ? r : last_row;
-            int64_t prow;
-            if (PAGED)
-                prow = (int64_t)pg[j] * a.k.page_rows + (r % a.k.page_rows);
-            else
-                prow = row0 + r;
-            prow = prow < 0 ? 0 : (prow > last_pool_row ? last_pool_row : prow);
-            pk[j] = __builtin_nontemporal_load((const u32x4*)(kbase + prow * pool_stride));   // streamed once
-            pv[j] = __builtin_nontemporal_load((const u32x4*)(vbase + prow * pool_stride));
+            const uint64_t off = (uint64_t)pool_row_of<PAGED>(a, r, PAGED ? pg[j] : 0, row0) * pool_stride;
+            pk[j] = __builtin_nontemporal_load((const u32x4*)(kbase + off));   // streamed once
+            pv[j] = __builtin_nontemporal_load((const u32x4*)(vbase + off));
         }
     };
 
-    if (r_begin >= r_end) {
-        // empty split: nothing visible, the combine kernel skips it
-        if (a.n_splits > 1 && g == 0) {
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb) {
-                const int t = 32 * nb + li;
-                if (t < T) {
-                    const int64_t slot = (((int64_t)split * a.B + b) * a.H + h) * a.T_max + t;
-                    a.part_ml[slot * 2] = -INFINITY;
-                    a.part_ml[slot * 2 + 1] = 0.f;
-                }
-            }
-        }
-        return;
+    const int first = sq.r_begin + kChunk * phase;
+    if (active && first < sq.r_end) {
+        if (PAGED) lookup_pages(first);
+        issue_loads(first);
+        if (PAGED) lookup_pages(first + step);
     }
-    if (PAGED) lookup_pages(r_begin);
-    issue_loads(r_begin);
-    if (PAGED) lookup_pages(r_begin + kChunk);
-    for (int base = r_begin; base < r_end; base += kChunk) {
-        // ---- 1. stage the prefetched chunk, start the next one -----------------
+    for (int base = first; active && base < sq.r_end; base += step) {
 #pragma unroll
         for (int j = 0; j < Cf::kLoads; ++j) {
             const int r = ld_row + Cf::kRowsPerLoad * j;
             *(u32x4*)(ldsK + r * Cf::kKStride + ld_col * 16) = pk[j];
             *(u32x4*)(ldsV + r * Cf::kVStride + ld_col * 16) = pv[j];
         }
-        issue_loads(base + kChunk);
-        if (PAGED) lookup_pages(base + 2 * kChunk);
+        issue_loads(base + step);
+        if (PAGED) lookup_pages(base + 2 * step);
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-
-        // ---- 2. S^T = K . Q^T ---------------------------------------------------
-        floatx16 s[NB];
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) s[nb][r] = 0.f;
-#pragma unroll
-        for (int c = 0; c < Cf::kDC; ++c) {
-            const bf16x8 kf = as_bf16x8(*(const u32x4*)(ldsK + li * Cf::kKStride + 32 * c + 16 * g));
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb)
-                s[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[nb][c], s[nb], 0, 0, 0);
-        }
-
-        // ---- 3. online softmax ---------------------------------------------------
-        const bool need_mask = base + kChunk > C;
-        bf16x8 pf[NB][2];
-        float alpha[NB];
-        bool any_rescale = false;
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb) {
-            float x[16], mx = -INFINITY;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                x[r] = s[nb][r] * sl2;
-                if (need_mask) {
-                    const int row = base + acc_row(r, g);
-                    const bool vis = row < C || (row < n_rows && ((anc[nb] >> (row - C)) & 1ull));
-                    x[r] = vis ? x[r] : -INFINITY;
-                }
-                mx = fmaxf(mx, x[r]);
-            }
-            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-            const float m_new = fmaxf(run_m[nb], mx);
-            const float m_safe = m_new == -INFINITY ? 0.f : m_new;
-            alpha[nb] = fast_exp2(run_m[nb] - m_safe);   // 0 on the first visible chunk, 1 when the maximum holds
-            any_rescale = any_rescale || (alpha[nb] != 1.f);
-            float psum = 0.f;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                // the row sum is taken over the bf16-rounded weights that enter the PV
-                // product, so the normalised weights still sum to one
-                const __bf16 pb = (__bf16)fast_exp2(x[r] - m_safe);
-                psum += (float)pb;
-                pf[nb][r >> 3][r & 7] = pb;
-            }
-            run_l[nb] = run_l[nb] * alpha[nb] + psum;
-            run_m[nb] = m_new;
-        }
-        if (__any(any_rescale)) {
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-                for (int q = 0; q < Cf::kNQ; ++q)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) o[nb][q][r] *= alpha[nb];
-        }
-
-        // ---- 4. O^T += V^T . P^T -------------------------------------------------
-        // reduction slot (g, e) of half c2 is chunk row acc_row(8*c2 + e, g); output
-        // column block q holds columns kNQ*i + q.
-#pragma unroll
-        for (int c2 = 0; c2 < 2; ++c2) {
-            uint32_t w[8][Cf::kNQ / 2];
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const unsigned char* p = ldsV + acc_row(8 * c2 + e, g) * Cf::kVStride + li * (Cf::kNQ * 2);
-                if (Cf::kNQ == 4) {
-                    const uint2 t2 = *(const uint2*)p;
-                    w[e][0] = t2.x;
-                    w[e][Cf::kNQ / 2 - 1] = t2.y;
-                } else {
-                    w[e][0] = *(const uint32_t*)p;
-                }
-            }
-#pragma unroll
-            for (int q = 0; q < Cf::kNQ; ++q) {
-                u32x4 av;
-                const uint32_t sel = (q & 1) ? 0x07060302u : 0x05040100u;
-                av.x = __builtin_amdgcn_perm(w[1][q >> 1], w[0][q >> 1], sel);
-                av.y = __builtin_amdgcn_perm(w[3][q >> 1], w[2][q >> 1], sel);
-                av.z = __builtin_amdgcn_perm(w[5][q >> 1], w[4][q >> 1], sel);
-                av.w = __builtin_amdgcn_perm(w[7][q >> 1], w[6][q >> 1], sel);
-                const bf16x8 vf = as_bf16x8(av);
-#pragma unroll
-                for (int nb = 0; nb < NB; ++nb)
-                    o[nb][q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[nb][c2], o[nb][q], 0, 0, 0);
-            }
-        }
+        process_chunk<DH>(w, ldsK, ldsV, base, sq.C, sq.n_rows, sl2, g, li);
     }
-
-    // ---- epilogue: normalise or hand the partial to the combine kernel ----------
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb) {
-        const int t = 32 * nb + li;
-        const float l = run_l[nb] + __shfl_xor(run_l[nb], 32, 64);
-        if (t >= T) continue;
-        float* dst;
-        float mul;
-        if (a.n_splits == 1) {
-            dst = a.out + (((int64_t)b * a.T_max + t) * a.H + h) * DH;
-            mul = 1.f / l;
-        } else {
-            const int64_t slot = (((int64_t)split * a.B + b) * a.H + h) * a.T_max + t;
-            dst = a.part_o + slot * DH;
-            mul = 1.f;
-            if (g == 0) {
-                a.part_ml[slot * 2] = run_m[nb] * kLn2;   // natural-log units for the combine
-                a.part_ml[slot * 2 + 1] = l;
-            }
-        }
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            float* p = dst + Cf::kNQ * acc_row(r, g);
-            if (Cf::kNQ == 4) {
-                *(float4*)p = make_float4(o[nb][0][r] * mul, o[nb][1][r] * mul,
-                                          o[nb][Cf::kNQ - 2][r] * mul, o[nb][Cf::kNQ - 1][r] * mul);
-            } else {
-                *(float2*)p = make_float2(o[nb][0][r] * mul, o[nb][1][r] * mul);
-            }
-        }
+    if (n_phase == 1) {
+        if (active && t < sq.T) epilogue_direct<DH>(w, a, b, h, t, split, g);
+    } else {
+        epilogue_merge<DH>(w, a, lds, b, h, sq.T, split, phase, 1, n_phase, g, li, tid);
     }
 }
 
-template <int DH, int NB, bool PAGED>
+// ---------------------------------------------------------------------------------------------
+// 32 < T <= 64: wavefronts 2p and 2p+1 hold node blocks 0 and 1 of the same (head, phase) and
+// share one double-buffered stage: the even one loads the K chunk, the odd one the V chunk, two
+// chunks ahead; one workgroup barrier per chunk makes the stage visible.  Every wavefront runs
+// the same number of iterations so the barriers match.
+// ---------------------------------------------------------------------------------------------
+template <int DH, bool PAGED>
+__global__ __launch_bounds__(kMfThreads, 2) void verify_mfma_pair_kernel(VerifyArgs a) {
+    using Cf = MfCfg<DH>;
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    __shared__ int s_parent[TW_MAX_TREE];
+    __shared__ unsigned long long s_anc[TW_MAX_TREE];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int g = lane >> 5, li = lane & 31;
+    const int b = blockIdx.y, split = blockIdx.z;
+    const int blk = wave & 1, pair = wave >> 1;
+    const int n_phase = a.n_phase;               // 1 (two heads per workgroup) or 2 (one head)
+    const int phase = n_phase == 1 ? 0 : pair;
+    const int h = blockIdx.x * a.heads_per_wg + (n_phase == 1 ? pair : 0);
+    const SeqInfo sq = seq_info(a, b, split, tid, s_parent, s_anc);
+    const bool active = h < a.H;
+    const int hc = active ? h : a.H - 1;
+    const int t = 32 * blk + li;
+
+    unsigned char* stage = lds + pair * 2 * Cf::kStage;   // two buffers of one K+V chunk
+    WaveState<DH> w;
+    w.anc = s_anc[t];
+    load_q(w, a, b, hc, t, sq.T, g);
+    const float sl2 = a.scale * kLog2e;
+
+    const int ld_row = lane / Cf::kLanesPerRow, ld_col = lane % Cf::kLanesPerRow;
+    // the even wavefront of a pair streams K, the odd one V
+    const unsigned char* src = (const unsigned char*)(blk == 0 ? a.k.base : a.v.base) + (int64_t)hc * Cf::kRowB +
+                               ld_col * 16;
+    const int dst_off = blk == 0 ? 0 : kChunk * Cf::kKStride;
+    const int dst_stride = blk == 0 ? Cf::kKStride : Cf::kVStride;
+    const uint32_t pool_stride = (uint32_t)(a.H * Cf::kRowB);
+    const int32_t* ptab = PAGED ? a.k.page_table + (int64_t)b * a.k.max_pages : nullptr;
+    const int64_t row0 = PAGED ? 0 : (int64_t)a.k.row_off[b];
+    const int last_row = sq.r_end > sq.r_begin ? sq.r_end - 1 : sq.r_begin;
+    const int step = kChunk * n_phase;
+
+    u32x4 pld[2][Cf::kLoads];
+    auto issue_loads = [&](int base, int slot) {
+#pragma unroll
+        for (int j = 0; j < Cf::kLoads; ++j) {
+            int r = base + ld_row + Cf::kRowsPerLoad * j;
+            r = r < last_row ? r : last_row;
+            int page = 0;
+            if (PAGED) {
+                int pi = r / a.k.page_rows;
+                pi = pi < a.k.max_pages ? pi : a.k.max_pages - 1;
+                page = ptab[pi];
+            }
+            const uint64_t off = (uint64_t)pool_row_of<PAGED>(a, r, page, row0) * pool_stride;
+            pld[slot][j] = __builtin_nontemporal_load((const u32x4*)(src + off));   // streamed once
+        }
+    };
+    auto stage_chunk = [&](int slot, unsigned char* buf) {
+#pragma unroll
+        for (int j = 0; j < Cf::kLoads; ++j)
+            *(u32x4*)(buf + dst_off + (ld_row + Cf::kRowsPerLoad * j) * dst_stride + ld_col * 16) = pld[slot][j];
+    };
+
+    const int n_chunks = (sq.r_end - sq.r_begin + kChunk - 1) / kChunk;
+    const int n_iter = (n_chunks + n_phase - 1) / n_phase;   // the same for every wavefront of the workgroup
+    const int first = sq.r_begin + kChunk * phase;
+    issue_loads(first, 0);
+    issue_loads(first + step, 1);
+    for (int it = 0; it < n_iter; it += 2) {
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            const int base = first + (it + half) * step;
+            unsigned char* buf = stage + half * Cf::kStage;
+            stage_chunk(half, buf);
+            issue_loads(base + 2 * step, half);
+            __syncthreads();   // the partner's half of the chunk is staged; the other buffer is free again
+            if (active && it + half < n_iter && base < sq.r_end)
+                process_chunk<DH>(w, buf, buf + kChunk * Cf::kKStride, base, sq.C, sq.n_rows, sl2, g, li);
+        }
+    }
+    if (n_phase == 1) {
+        if (active && t < sq.T) epilogue_direct<DH>(w, a, b, h, t, split, g);
+    } else {
+        epilogue_merge<DH>(w, a, lds, b, h, sq.T, split, blk * n_phase + phase, 2, n_phase, g, li, tid);
+    }
+}
+
+template <int DH, bool PAGED>
 static hipError_t launch_one(const VerifyArgs& a, hipStream_t s) {
-    const dim3 grid((a.H + 3) / 4, a.B, a.n_splits);
-    const size_t lds = 4 * (size_t)MfCfg<DH>::kWaveLds;
-    hipError_t e = hipFuncSetAttribute((const void*)verify_mfma_kernel<DH, NB, PAGED>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    const dim3 grid((a.H + a.heads_per_wg - 1) / a.heads_per_wg, a.B, a.n_splits);
+    const size_t lds = MfCfg<DH>::kLds;
+    const void* fn = a.n_blk == 1 ? (const void*)verify_mfma_kernel<DH, PAGED>
+                                  : (const void*)verify_mfma_pair_kernel<DH, PAGED>;
+    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((verify_mfma_kernel<DH, NB, PAGED>), grid, dim3(kMfThreads), lds, s, a);
+    if (a.n_blk == 1)
+        hipLaunchKernelGGL((verify_mfma_kernel<DH, PAGED>), grid, dim3(kMfThreads), lds, s, a);
+    else
+        hipLaunchKernelGGL((verify_mfma_pair_kernel<DH, PAGED>), grid, dim3(kMfThreads), lds, s, a);
     return hipGetLastError();
-}
-
-template <int DH, int NB>
-static hipError_t launch_paging(const VerifyArgs& a, hipStream_t s) {
-    return a.k.page_table ? launch_one<DH, NB, true>(a, s) : launch_one<DH, NB, false>(a, s);
 }
 
 bool verify_mfma_supported(const VerifyArgs& a, int dtype) {
     return dtype == TW_BF16 && (a.d_h == 64 || a.d_h == 128) && a.k.page_table == a.v.page_table &&
            a.k.row_off == a.v.row_off && a.k.page_rows == a.v.page_rows &&
-           a.k.max_pages == a.v.max_pages && a.k.pool_rows == a.v.pool_rows;
+           a.k.max_pages == a.v.max_pages && a.k.pool_rows == a.v.pool_rows &&
+           a.k.pool_rows <= 0x7FFFFFFFll;
 }
 
 hipError_t launch_verify_mfma(const VerifyArgs& a, hipStream_t s) {
-    const bool wide = a.T_max > 32;
-    if (a.d_h == 128) return wide ? launch_paging<128, 2>(a, s) : launch_paging<128, 1>(a, s);
-    return wide ? launch_paging<64, 2>(a, s) : launch_paging<64, 1>(a, s);
+    if (a.d_h == 128) return a.k.page_table ? launch_one<128, true>(a, s) : launch_one<128, false>(a, s);
+    return a.k.page_table ? launch_one<64, true>(a, s) : launch_one<64, false>(a, s);
 }
 
 }  // namespace tw

@@ -73,10 +73,15 @@ struct VerifyArgs {
     float* part_ml;  // [n_splits][B][H][T_max][2] running max, running sum
     int32_t T_max, B, H, d_h;
     int32_t n_splits, max_rows;
+    int32_t n_blk, n_phase, heads_per_wg;   // wavefront layout of the matrix-core kernel
     float scale;
 };
 
-int verify_plan_splits(int B, int H, int T_max, int max_rows);
+// Launch shape of tree verification: heads_per_wg * n_blk * n_phase == 4 wavefronts.
+struct VerifyPlan {
+    int n_splits, n_blk, n_phase, heads_per_wg;
+};
+VerifyPlan verify_plan(int B, int H, int T_max, int max_rows);
 size_t verify_workspace_bytes(int B, int H, int T_max, int d_h, int max_rows);
 hipError_t launch_verify_generic(const VerifyArgs& a, int dtype, hipStream_t s);
 bool verify_mfma_supported(const VerifyArgs& a, int dtype);

@@ -41,9 +41,11 @@ def test_host_helpers():
 
 
 def test_workspace_sizes():
-    # one sequence, 32 heads: the 282-row cache is split, partials need room
-    n = tw.workspace_bytes(tw.TW_CALL_TREE_VERIFY_ATTN, 1, 26, 32, 128, 282)
+    # one sequence, 32 heads, long cache: the rows are split, partials need room
+    n = tw.workspace_bytes(tw.TW_CALL_TREE_VERIFY_ATTN, 1, 26, 32, 128, 2076)
     assert n > 0 and n % (32 * 26 * 130 * 4) == 0
+    # a short cache is not worth splitting
+    assert tw.workspace_bytes(tw.TW_CALL_TREE_VERIFY_ATTN, 1, 26, 32, 128, 282) == 0
     # 128 sequences fill the chip without splitting
     assert tw.workspace_bytes(tw.TW_CALL_TREE_VERIFY_ATTN, 128, 26, 32, 128, 282) == 0
     assert tw.workspace_bytes(tw.TW_CALL_TTP_SCORE, 1, 64, 32, 128, 640) >= 32 * 576 * 4   # per-head partial sums
@@ -92,7 +94,7 @@ def test_argument_validation_without_launch():
     k, v = _view(), _view()
     call = lambda **kw: lib.tw_tree_verify_attn(
         kw.get("q", P), ctypes.byref(kw.get("k", k)), ctypes.byref(kw.get("v", v)), P,
-        kw.get("max_ctx", 256), P, P, kw.get("T", 26), kw.get("B", 1), f, P, kw.get("ws", None),
+        kw.get("max_ctx", 4096), P, P, kw.get("T", 26), kw.get("B", 1), f, P, kw.get("ws", None),
         kw.get("ws_bytes", 0), None)
     assert call(T=65) == tw.TW_ERR_UNSUPPORTED
     assert call(T=0) == tw.TW_ERR_INVALID_ARG

@@ -124,11 +124,23 @@ def test_verify_ragged_nodes_and_odd_head_count(tw):
 def test_verify_split_cache_single_sequence(tw):
     # one sequence, long context: the cache is split over workgroups and merged
     H, d_h, T = 32, 128, 26
-    for ctx in ([256], [2050]):
+    for ctx in ([700], [2050]):
         trees = [W.fanout_tree(W.HostRng(1, 1), T, (4, 3, 2, 1, 1))]
         q, k, v, off = make_case(13, 1, H, d_h, ctx, T, torch.bfloat16, trees)
         assert tw.workspace_bytes(tw.TW_CALL_TREE_VERIFY_ATTN, 1, T, H, d_h, ctx[0] + T) > 0
         check_verify(tw, q, k, v, ctx, [T], trees, 1 / math.sqrt(d_h), row_off=off)
+
+
+@pytest.mark.parametrize("B,H,T", [(64, 32, 20), (40, 32, 50), (3, 8, 20), (3, 7, 50), (1, 32, 64)])
+def test_verify_wave_layouts(tw, B, H, T):
+    # 4 heads / 2 heads x 2 node blocks per workgroup (many units), and one head per
+    # workgroup with the rows shared by 4 or 2 wavefronts per node block (few units)
+    d_h = 128
+    ctx = [33 + 37 * (b % 11) for b in range(B)]
+    n_nodes = [T if b % 3 else max(1, T - 7) for b in range(B)]
+    trees = [W.random_parent_tree(W.HostRng(41, b), n, 6) for b, n in enumerate(n_nodes)]
+    q, k, v, off = make_case(42, B, H, d_h, ctx, T, torch.bfloat16, trees)
+    check_verify(tw, q, k, v, ctx, n_nodes, padded(trees, T), 1 / math.sqrt(d_h), row_off=off)
 
 
 def test_verify_sharp_softmax(tw):
