@@ -189,6 +189,24 @@ int32_t tw_tree_accept(const int32_t* draft, const int32_t* argmax, const int32_
                        const int32_t* n_nodes, int32_t T_max, int32_t B, int32_t* n_acc,
                        int32_t* path, int32_t* bonus, void* stream);
 
+/*
+ * Commit of the accepted path into the KV cache (the step after the acceptance
+ * walk in Alg. 2; KV append of Sec. 3.1), so that the next draft-verify
+ * iteration can run on the same cache.  For every sequence b and every view
+ * (one layer's K or V, each with its own row mapping): the tree root stays at
+ * cache row C = ctx_len[b]; accepted node path[b][i] (cache row C + path[b][i])
+ * is moved to cache row C + 1 + i for i < n_acc[b]; other rows are untouched;
+ * new_ctx_len[b] = C + 1 + n_acc[b] (may be NULL; must not alias ctx_len).
+ * In place.  path/n_acc are the outputs of tw_tree_accept.
+ *   path [dev] [B][T_max], n_acc [dev] [B], ctx_len [dev] [B], views [host] n_views
+ *   structs, new_ctx_len [dev] [B] out.
+ * Precondition on device contents: path strictly increasing, 1 <= path[b][i] < T_max.
+ * Errors: INVALID_ARG (null pointers, malformed views), UNSUPPORTED (T_max > 64, B > 65535).
+ */
+int32_t tw_kv_commit(const int32_t* path, const int32_t* n_acc, int32_t T_max, const tw_kv_view* views,
+                     int32_t n_views, const int32_t* ctx_len, int32_t B, int32_t* new_ctx_len,
+                     void* stream);
+
 /* Host helper: TW_OK when parent[0] == -1 and 0 <= parent[i] < i for 0 < i < T <= 64. */
 int32_t tw_validate_tree(const int32_t* parent_host, int32_t T);
 

@@ -174,3 +174,23 @@ def tree_accept(draft, argmax, parent, n_nodes: Sequence[int]):
 
 def rbar(M: int, K: int, R: int, K_f: int, L: int) -> int:
     return int(lib().orc_rbar(int(M), int(K), int(R), int(K_f), int(L)))
+
+
+def kv_commit(pool: torch.Tensor, ctx_len: Sequence[int], n_nodes: Sequence[int], path, n_acc,
+              row_off: Optional[Sequence[int]] = None, page_table=None, page_rows: int = 16):
+    """Moves the accepted rows of every sequence in place inside `pool` ([rows][...]) and
+    returns the new context lengths."""
+    assert pool.device.type == "cpu" and pool.is_contiguous()
+    row_bytes = pool[0].numel() * pool.element_size()
+    p = _i32(path)
+    new_len = []
+    for b, (c, t) in enumerate(zip(ctx_len, n_nodes)):
+        rows, _ = cache_rows([c], [t], None if row_off is None else [row_off[b]],
+                             None if page_table is None else [page_table[b]], page_rows)
+        pb = p[b].contiguous()
+        rc = lib().orc_kv_commit(_p(pool), ctypes.c_size_t(row_bytes), _p(rows), int(rows.numel()), int(c),
+                                 _p(pb), int(n_acc[b]), int(t))
+        if rc < 0:
+            raise ValueError(f"oracle kv_commit: invalid argument (code {rc})")
+        new_len.append(rc)
+    return new_len

@@ -309,3 +309,28 @@ int orc_rbar(int M, int K, int R, int K_f, int L) {
     double x = ((double)M * K + (double)R * (K_f - K)) / (double)L;
     return (int)floor(x + 0.5);
 }
+
+/*
+ * Commit of the accepted path into one cache tensor (the step that follows the
+ * acceptance walk in Alg. 2; KV append of Sec. 3.1).  The tree root already
+ * sits at cache row C; accepted node path[i] (cache row C + path[i]) becomes
+ * cache row C + 1 + i.  Stated as a gather from a snapshot of the old rows, so
+ * the order of the moves cannot matter.  rows[r] is the pool row of cache row r
+ * of this sequence (n_rows_known entries).  Returns the new context length
+ * C + 1 + n_acc, or -1 for invalid arguments.
+ */
+int orc_kv_commit(void* pool, size_t row_bytes, const int64_t* rows, int n_rows_known, int C,
+                  const int32_t* path, int n_acc, int T) {
+    if (!pool || !rows || C < 0 || n_acc < 0 || n_acc > T - 1 || C + T > n_rows_known) return -1;
+    for (int i = 0; i < n_acc; ++i) {
+        if (path[i] < 1 || path[i] >= T) return -1;
+        if (i > 0 && path[i] <= path[i - 1]) return -1;
+    }
+    char* p = (char*)pool;
+    char* snap = (char*)malloc((size_t)(n_acc > 0 ? n_acc : 1) * row_bytes);
+    if (!snap) return -3;
+    for (int i = 0; i < n_acc; ++i) memcpy(snap + (size_t)i * row_bytes, p + (size_t)rows[C + path[i]] * row_bytes, row_bytes);
+    for (int i = 0; i < n_acc; ++i) memcpy(p + (size_t)rows[C + 1 + i] * row_bytes, snap + (size_t)i * row_bytes, row_bytes);
+    free(snap);
+    return C + 1 + n_acc;
+}

@@ -29,7 +29,7 @@ _STATUS = {0: "TW_OK", -1: "TW_ERR_INVALID_ARG", -2: "TW_ERR_UNSUPPORTED", -3: "
 
 EXPORTS = ["tw_version", "tw_workspace_bytes", "tw_ttp_score", "tw_ttp_select", "tw_ttp_compact",
            "tw_ttp_compact_batched",
-           "tw_tree_ancestor_masks", "tw_tree_verify_attn", "tw_tree_accept", "tw_validate_tree",
+           "tw_tree_ancestor_masks", "tw_tree_verify_attn", "tw_tree_accept", "tw_kv_commit", "tw_validate_tree",
            "tw_rbar"]
 
 
@@ -62,6 +62,8 @@ _lib.tw_tree_verify_attn.argtypes = [_vp, ctypes.POINTER(KvView), ctypes.POINTER
                                      _vp, _i32, _i32, _f32, _vp, _vp, _sz, _vp]
 _lib.tw_tree_accept.restype = _i32
 _lib.tw_tree_accept.argtypes = [_vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp, _vp, _vp]
+_lib.tw_kv_commit.restype = _i32
+_lib.tw_kv_commit.argtypes = [_vp, _vp, _i32, ctypes.POINTER(KvView), _i32, _vp, _i32, _vp, _vp]
 _lib.tw_validate_tree.restype = _i32
 _lib.tw_validate_tree.argtypes = [ctypes.POINTER(_i32), _i32]
 _lib.tw_rbar.restype = _i32
@@ -172,6 +174,14 @@ def tree_accept(draft: torch.Tensor, argmax: torch.Tensor, parent: torch.Tensor,
     _check("tw_tree_accept", _lib.tw_tree_accept(_ptr(draft), _ptr(argmax), _ptr(parent), _ptr(n_nodes),
                                                  T_max, B, _ptr(n_acc), _ptr(path), _ptr(bonus),
                                                  _stream()))
+
+
+def kv_commit(path: torch.Tensor, n_acc: torch.Tensor, views: Sequence[KvView], ctx_len: torch.Tensor,
+              new_ctx_len: Optional[torch.Tensor]) -> None:
+    B, T_max = path.shape
+    arr = (KvView * max(len(views), 1))(*views)
+    _check("tw_kv_commit", _lib.tw_kv_commit(_ptr(path), _ptr(n_acc), T_max, arr, len(views), _ptr(ctx_len),
+                                             B, _ptr(new_ctx_len), _stream()))
 
 
 def validate_tree(parent: Sequence[int]) -> int:

@@ -237,6 +237,49 @@ int32_t tw_tree_accept(const int32_t* draft, const int32_t* argmax, const int32_
                : TW_ERR_LAUNCH;
 }
 
+int32_t tw_kv_commit(const int32_t* path, const int32_t* n_acc, int32_t T_max, const tw_kv_view* views,
+                     int32_t n_views, const int32_t* ctx_len, int32_t B, int32_t* new_ctx_len,
+                     void* stream) {
+    if (B < 0 || n_views < 0 || T_max < 1) return TW_ERR_INVALID_ARG;
+    if (T_max > TW_MAX_TREE) return TW_ERR_UNSUPPORTED;
+    if (B == 0) return TW_OK;
+    if (B > 65535) return TW_ERR_UNSUPPORTED;
+    if (!path || !n_acc || !ctx_len || (n_views > 0 && !views)) return TW_ERR_INVALID_ARG;
+    for (int v = 0; v < n_views; ++v) {
+        if (!views[v].base || views[v].pool_rows <= 0 || views[v].H <= 0 || views[v].d_h <= 0)
+            return TW_ERR_INVALID_ARG;
+        if (views[v].dtype != TW_F32 && views[v].dtype != TW_BF16) return TW_ERR_UNSUPPORTED;
+        if (views[v].page_table ? (views[v].max_pages <= 0 || views[v].page_rows <= 0) : !views[v].row_off)
+            return TW_ERR_INVALID_ARG;
+    }
+    hipStream_t s = (hipStream_t)stream;
+    // 32 views per launch; the first launch also writes the new lengths.  With no views at all a
+    // launch over one empty view still writes them.
+    const int n_launch_views = n_views > 0 ? n_views : (new_ctx_len ? 1 : 0);
+    for (int v0 = 0; v0 < n_launch_views; v0 += kCommitMaxViews) {
+        CommitArgs a;
+        const int n = n_launch_views - v0 < kCommitMaxViews ? n_launch_views - v0 : kCommitMaxViews;
+        size_t max_row = 16;
+        for (int v = 0; v < kCommitMaxViews; ++v) {
+            a.views[v] = KvDev{};
+            a.elem_bytes[v] = 0;
+            if (v < n && v0 + v < n_views) {
+                a.views[v] = to_dev(views[v0 + v]);
+                a.elem_bytes[v] = views[v0 + v].dtype == TW_F32 ? 4 : 2;
+                const size_t rb = (size_t)views[v0 + v].H * views[v0 + v].d_h * a.elem_bytes[v];
+                if (rb > max_row) max_row = rb;
+            }
+        }
+        a.path = path;
+        a.n_acc = n_acc;
+        a.ctx_len = ctx_len;
+        a.new_ctx_len = v0 == 0 ? new_ctx_len : nullptr;
+        a.T_max = T_max;
+        if (launch_kv_commit(a, n, B, max_row, s) != hipSuccess) return TW_ERR_LAUNCH;
+    }
+    return TW_OK;
+}
+
 int32_t tw_validate_tree(const int32_t* parent_host, int32_t T) {
     if (!parent_host || T < 1) return TW_ERR_INVALID_ARG;
     if (T > TW_MAX_TREE) return TW_ERR_UNSUPPORTED;

@@ -124,6 +124,19 @@ struct CompactBatch {
 hipError_t launch_compact(const CompactBatch& cb, int B, int n_out_max, const CompactTable& tab,
                           int n_tensors, size_t row_bytes, hipStream_t s);
 
+// --- commit of the accepted path ------------------------------------------------
+constexpr int kCommitMaxViews = 32;
+struct CommitArgs {
+    KvDev views[kCommitMaxViews];
+    int32_t elem_bytes[kCommitMaxViews];
+    const int32_t* path;      // [B][T_max]
+    const int32_t* n_acc;     // [B]
+    const int32_t* ctx_len;   // [B]
+    int32_t* new_ctx_len;     // [B] or null
+    int32_t T_max;
+};
+hipError_t launch_kv_commit(const CommitArgs& a, int n_views, int B, size_t max_row_bytes, hipStream_t s);
+
 hipError_t launch_ancestor_masks(const int32_t* parent, const int32_t* n_nodes, int T_max, int B,
                                  uint64_t* masks, hipStream_t s);
 hipError_t launch_accept(const int32_t* draft, const int32_t* argmax, const int32_t* parent,

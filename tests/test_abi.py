@@ -90,6 +90,17 @@ def test_argument_validation_without_launch():
     assert lib.tw_tree_ancestor_masks(P, P, 65, 1, P, None) == tw.TW_ERR_UNSUPPORTED
     assert lib.tw_tree_ancestor_masks(P, None, 8, 1, P, None) == tw.TW_ERR_INVALID_ARG
 
+    two = (tw.KvView * 2)(_view(), _view())
+    kc = lambda **kw: lib.tw_kv_commit(kw.get("path", P), P, kw.get("T", 26), kw.get("views", two), 2, P,
+                                       kw.get("B", 1), P, None)
+    assert kc(T=65) == tw.TW_ERR_UNSUPPORTED
+    assert kc(T=0) == tw.TW_ERR_INVALID_ARG
+    assert kc(path=None) == tw.TW_ERR_INVALID_ARG
+    assert kc(views=None) == tw.TW_ERR_INVALID_ARG
+    assert kc(views=(tw.KvView * 2)(_view(), _view(row_off=None))) == tw.TW_ERR_INVALID_ARG
+    assert kc(B=70000) == tw.TW_ERR_UNSUPPORTED
+    assert kc(B=0) == tw.TW_OK
+
     f = ctypes.c_float(0.1)
     k, v = _view(), _view()
     call = lambda **kw: lib.tw_tree_verify_attn(

@@ -254,6 +254,101 @@ def test_accept_chain_star_and_duplicates(tw):
 
 
 # ----------------------------------------------------------------------------
+# kv_commit (the step after the walk) and two chained draft-verify iterations
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("paged", [False, True])
+def test_kv_commit_bit_exact(tw, paged):
+    B, H, d_h, T, pr = 6, 4, 64, 24, 16
+    rng = W.HostRng(77, int(paged))
+    ctx = [rng.randint(0, 90) for _ in range(B)]
+    trees = [W.random_parent_tree(rng, T, 6) for _ in range(B)]
+    toks = [W.plant_tokens(rng, t, vocab=3, p_match=0.9) for t in trees]
+    n_acc, path, _ = oracle.tree_accept([x[0] for x in toks], [x[1] for x in toks], trees, [T] * B)
+    assert int(n_acc.max()) >= 2
+    rows = [c + T for c in ctx]
+    if paged:
+        n_pages = [(r + pr - 1) // pr for r in rows]
+        ids = list(range(sum(n_pages)))
+        rng.shuffle(ids)
+        pt, k0 = [], 0
+        for n in n_pages:
+            pt.append(ids[k0:k0 + n] + [0] * (max(n_pages) - n))
+            k0 += n
+        pool_rows, off = sum(n_pages) * pr, None
+    else:
+        pt, off, acc = None, [], 1
+        for r in rows:
+            off.append(acc)
+            acc += r + 2
+        pool_rows = acc
+    pools = [W.normal(5, s, (pool_rows, H, d_h), 1.0, torch.bfloat16 if s % 2 else torch.float32) for s in range(5)]
+    dev = [p.to(DEV) for p in pools]
+    ro = None if off is None else _i32(off)
+    ptd = None if pt is None else _i32(pt)
+    views = [tw.kv_view(p, ro, ptd, pr) for p in dev]
+    new_len = torch.zeros(B, dtype=torch.int32, device=DEV)
+    tw.kv_commit(path.to(DEV), n_acc.to(DEV), views, _i32(ctx), new_len)
+    torch.cuda.synchronize()
+    for p_host, p_dev in zip(pools, dev):
+        want_len = oracle.kv_commit(p_host, ctx, [T] * B, path, n_acc.tolist(), row_off=off, page_table=pt,
+                                    page_rows=pr)
+        assert new_len.cpu().tolist() == want_len
+        assert torch.equal(p_dev.cpu().view(torch.uint8), p_host.view(torch.uint8))
+
+
+def test_two_chained_draft_verify_iterations(tw):
+    # verify -> accept -> commit -> verify again on the committed cache, GPU against the oracle doing the same
+    B, H, d_h, T = 3, 8, 128, 20
+    rng = W.HostRng(88, 0)
+    ctx = [50, 7, 131]
+    room = 2 * T + 2
+    off, acc = [], 0
+    for c in ctx:
+        off.append(acc)
+        acc += c + room
+    k = W.normal(9, 1, (acc, H, d_h), 0.5, torch.bfloat16)
+    v = W.normal(9, 2, (acc, H, d_h), 0.5, torch.bfloat16)
+    kd, vd, ro = k.to(DEV), v.to(DEV), _i32(off)
+    kv, vv = tw.kv_view(kd, ro), tw.kv_view(vd, ro)
+    ctx_d = _i32(ctx)
+    scale = 1 / math.sqrt(d_h)
+    cur_ctx = list(ctx)
+    for it in range(2):
+        trees = [W.random_parent_tree(rng, T, 5) for _ in range(B)]
+        toks = [W.plant_tokens(rng, t, vocab=4, p_match=0.9) for t in trees]
+        draft, argmx = [x[0] for x in toks], [x[1] for x in toks]
+        q = W.normal(9, 10 + it, (B, T, H, d_h), 1 / math.sqrt(d_h), torch.bfloat16)
+        out = torch.zeros(B, T, H, d_h, dtype=torch.float32, device=DEV)
+        nb = tw.workspace_bytes(tw.TW_CALL_TREE_VERIFY_ATTN, B, T, H, d_h, max(cur_ctx) + T)
+        ws = torch.empty(max(nb, 4) // 4, dtype=torch.float32, device=DEV) if nb else None
+        par_d, nn_d = _i32(trees), _i32([T] * B)
+        tw.tree_verify_attn(q.to(DEV), kv, vv, ctx_d, max(cur_ctx), par_d, nn_d, scale, out, ws)
+        n_acc = torch.zeros(B, dtype=torch.int32, device=DEV)
+        path = torch.zeros(B, T, dtype=torch.int32, device=DEV)
+        bonus = torch.zeros(B, dtype=torch.int32, device=DEV)
+        tw.tree_accept(_i32(draft), _i32(argmx), par_d, nn_d, n_acc, path, bonus)
+        new_ctx = torch.zeros(B, dtype=torch.int32, device=DEV)
+        tw.kv_commit(path, n_acc, [kv, vv], ctx_d, new_ctx)
+        torch.cuda.synchronize()
+        want = oracle.tree_verify_attn(q, k, v, cur_ctx, [T] * B, trees, scale, row_off=off)
+        assert float((out.cpu().double() - want).abs().max()) <= ATTN_TOL
+        wa = oracle.tree_accept(draft, argmx, trees, [T] * B)
+        assert torch.equal(n_acc.cpu(), wa[0]) and torch.equal(path.cpu(), wa[1]) and torch.equal(bonus.cpu(), wa[2])
+        want_ctx = oracle.kv_commit(k, cur_ctx, [T] * B, wa[1], wa[0].tolist(), row_off=off)
+        oracle.kv_commit(v, cur_ctx, [T] * B, wa[1], wa[0].tolist(), row_off=off)
+        assert new_ctx.cpu().tolist() == want_ctx
+        assert torch.equal(kd.cpu().view(torch.int16), k.view(torch.int16))
+        cur_ctx, ctx_d = want_ctx, new_ctx
+        # the next tree's K/V (root = the bonus token) are written by the caller at the new rows
+        for b in range(B):
+            r0 = off[b] + cur_ctx[b]
+            k[r0:r0 + T] = W.normal(9, 100 + 10 * it + b, (T, H, d_h), 0.5, torch.bfloat16)
+            v[r0:r0 + T] = W.normal(9, 200 + 10 * it + b, (T, H, d_h), 0.5, torch.bfloat16)
+        kd.copy_(k)
+        vd.copy_(v)
+
+
+# ----------------------------------------------------------------------------
 # ttp_select
 # ----------------------------------------------------------------------------
 def _check_select(tw, scores, R):

@@ -451,3 +451,58 @@ def test_rbar_matches_printed_settings():
     for M, K, R, K_f, L, want in (map(int, r) for r in rows):
         assert oracle.rbar(M, K, R, K_f, L) == want
     assert oracle.rbar(576, 2, 64, 32, 32) == round((576 * 2 + 64 * 30) / 32)   # Eq. 4 form
+
+
+# ----------------------------------------------------------------------------
+# kv_commit (the step after the acceptance walk; KV append of Sec. 3.1)
+# ----------------------------------------------------------------------------
+def test_kv_commit_gather_identity_and_untouched_rows():
+    C, T, width = 5, 8, 6
+    pool = torch.arange((C + T + 3) * width, dtype=torch.float32).view(-1, width)
+    off = 2
+    # accepted nodes 2, 5, 6 -> rows C+1, C+2, C+3 (library gather on a snapshot)
+    before = pool.clone()
+    new_len = oracle.kv_commit(pool, [C], [T], [[2, 5, 6, -1, -1, -1, -1, -1]], [3], row_off=[off])
+    assert new_len == [C + 1 + 3]
+    want = before.clone()
+    want[off + C + 1:off + C + 4] = before.index_select(0, torch.tensor([off + C + 2, off + C + 5, off + C + 6]))
+    assert torch.equal(pool, want)
+    assert torch.equal(pool[:off + C + 1], before[:off + C + 1])            # context and root untouched
+    assert torch.equal(pool[off + C + 4:], before[off + C + 4:])            # rejected tail left behind
+    # a chain prefix is already in place
+    pool2 = before.clone()
+    assert oracle.kv_commit(pool2, [C], [T], [[1, 2, 3, 4, -1, -1, -1, -1]], [4], row_off=[off]) == [C + 5]
+    assert torch.equal(pool2, before)
+    # overlapping moves (source of one is the destination of the next) still read the old rows
+    pool3 = before.clone()
+    oracle.kv_commit(pool3, [C], [T], [[2, 3, 4, 5, 6, 7, -1, -1]], [6], row_off=[off])
+    assert torch.equal(pool3[off + C + 1:off + C + 7], before[off + C + 2:off + C + 8])
+    # nothing accepted: only the root is committed
+    pool4 = before.clone()
+    assert oracle.kv_commit(pool4, [C], [T], [[-1] * 8], [0], row_off=[off]) == [C + 1]
+    assert torch.equal(pool4, before)
+    for bad in ([[0, 1, -1, -1, -1, -1, -1, -1]], [[3, 2, -1, -1, -1, -1, -1, -1]], [[2, 8, -1, -1, -1, -1, -1, -1]]):
+        with pytest.raises(ValueError):
+            oracle.kv_commit(before.clone(), [C], [T], bad, [2], row_off=[off])
+
+
+def test_kv_commit_then_decode_equals_attention_over_the_accepted_path():
+    # after the commit, one-token decode attention over the committed cache equals attention
+    # over [context, root, accepted path] taken from the uncommitted cache
+    H, d, C, T = 2, 8, 7, 9
+    par = [-1, 0, 0, 1, 1, 2, 4, 4, 6]
+    path, n_acc = [1, 4, 6, 8, -1, -1, -1, -1, -1], 4
+    k = _rand(51, 1, (C + T, H, d))
+    v = _rand(51, 2, (C + T, H, d))
+    q = _rand(51, 3, (1, 1, H, d))
+    kc, vc = k.clone(), v.clone()
+    n1 = oracle.kv_commit(kc, [C], [T], [path], [n_acc], row_off=[0])
+    n2 = oracle.kv_commit(vc, [C], [T], [path], [n_acc], row_off=[0])
+    assert n1 == n2 == [C + 1 + n_acc]
+    # the new token sits at row new_len: give it the K/V of old row C+8's successor slot (any values)
+    new_len = n1[0]
+    got = oracle.tree_verify_attn(q, kc, vc, [new_len - 1], [1], [[-1]], 0.3, row_off=[0])[0, 0]
+    rows = list(range(C + 1)) + [C + p for p in path[:n_acc - 1]] + [C + path[n_acc - 1]]
+    want = _causal_library(q[0], k[rows], v[rows], 0.3)[0]
+    assert torch.allclose(got, want, atol=1e-12)
+    assert W.tree_depths(par)[8] == 4          # the path really is a root-to-node chain of that depth
