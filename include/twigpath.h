@@ -102,6 +102,24 @@ int32_t tw_ttp_score(const void* q_sel, int32_t n_q_max, const int32_t* n_q, con
                      void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * Pruning score in the P-Head form (Sec. 5.1 Eq. 7).  One query per sequence
+ * (the last text token).  For head h and visual key m the logit is
+ *   scale * sum_c (gq[b][h][c] * q[b][h][c]) * (gk[key][h][c] * K[key][h][c]),   key = v_start + m,
+ * the softmax runs over the M visual keys only, and scores[b][m] is the mean
+ * over heads (so every scores[b] sums to one).  gq / gk are the outputs of the
+ * gating projections G_q, G_k, laid out like q and K.
+ *   q, gq   [dev] [B][H][d_h], dtype of the views
+ *   k, gk   [host structs] contiguous views with the same dtype/H/d_h
+ *   scores  [dev] [B][M] fp32 out
+ *   ws      at least B*H*M*4 bytes (tw_workspace_bytes(TW_CALL_TTP_SCORE, B, 1, H, d_h, M))
+ * Errors: INVALID_ARG (null pointers, paged views, span outside the pools),
+ * UNSUPPORTED (d_h, view mismatch, M > 32768), WORKSPACE.
+ */
+int32_t tw_ttp_score_phead(const void* q, const void* gq, const tw_kv_view* k, const tw_kv_view* gk,
+                           int32_t B, int32_t v_start, int32_t M, float scale, float* scores, void* ws,
+                           size_t ws_bytes, void* stream);
+
+/*
  * Top-R keep (TopR of Sec. 3.1 Eq. 3).  kept[b] receives the indices of the R
  * largest scores[b][.], ties toward the lower index, in ascending index order.
  * -0.0 and +0.0 compare equal; scores must be finite.

@@ -194,3 +194,18 @@ def kv_commit(pool: torch.Tensor, ctx_len: Sequence[int], n_nodes: Sequence[int]
             raise ValueError(f"oracle kv_commit: invalid argument (code {rc})")
         new_len.append(rc)
     return new_len
+
+
+def ttp_score_phead(q: torch.Tensor, gq: torch.Tensor, k: torch.Tensor, gk: torch.Tensor,
+                    k_row_off: Sequence[int], gk_row_off: Sequence[int], v_start: int, M: int,
+                    scale: float) -> torch.Tensor:
+    """scores [B][M] fp64; q, gq [B][H][d_h]; k, gk [rows][H][d_h]."""
+    B, H, d_h = q.shape
+    assert gq.shape == q.shape and k.shape[1:] == (H, d_h) and gk.shape[1:] == (H, d_h)
+    assert q.dtype == gq.dtype == k.dtype == gk.dtype
+    out = torch.zeros(B, M, dtype=torch.float64)
+    a, b_ = _i64(k_row_off), _i64(gk_row_off)
+    rc = lib().orc_ttp_score_phead(_p(q), _p(gq), _p(k), _p(gk), _dtype_code(q), B, H, d_h, _p(a), _p(b_),
+                                   int(v_start), int(M), ctypes.c_double(scale), _p(out))
+    _check(rc, "ttp_score_phead")
+    return out

@@ -334,3 +334,45 @@ int orc_kv_commit(void* pool, size_t row_bytes, const int64_t* rows, int n_rows_
     free(snap);
     return C + 1 + n_acc;
 }
+
+/*
+ * Pruning score in the P-Head form (Sec. 5.1 Eq. 7): for each head the single
+ * query (last text token) and every visual key are first multiplied
+ * element-wise by their gate vectors, the scaled dot products are normalised by
+ * a softmax over the M visual keys only, and the heads are averaged.
+ *
+ *   q, gq   [B][H][d_h]      k, gk  token-major rows; visual key m of sequence b is row
+ *   k_row_off[b] + v_start + m (gk_row_off for the gates).   scores [B][M] fp64
+ */
+int orc_ttp_score_phead(const void* q, const void* gq, const void* k, const void* gk, int dtype, int B,
+                        int H, int d_h, const int64_t* k_row_off, const int64_t* gk_row_off, int v_start,
+                        int M, double scale, double* scores) {
+    if (!q || !gq || !k || !gk || !scores || B < 0 || M < 1 || v_start < 0) return -1;
+    double* s = (double*)malloc((size_t)M * sizeof(double));
+    if (!s) return -3;
+    for (int b = 0; b < B; ++b) {
+        for (int m = 0; m < M; ++m) scores[(size_t)b * M + m] = 0.0;
+        for (int h = 0; h < H; ++h) {
+            int64_t qo = ((int64_t)b * H + h) * d_h;
+            double mx = -INFINITY;
+            for (int m = 0; m < M; ++m) {
+                int64_t ko = ((k_row_off[b] + v_start + m) * H + h) * (int64_t)d_h;
+                int64_t go = ((gk_row_off[b] + v_start + m) * H + h) * (int64_t)d_h;
+                double dot = 0.0;
+                for (int c = 0; c < d_h; ++c)
+                    dot += (widen(gq, dtype, qo + c) * widen(q, dtype, qo + c)) *
+                           (widen(gk, dtype, go + c) * widen(k, dtype, ko + c));
+                s[m] = scale * dot;
+                if (s[m] > mx) mx = s[m];
+            }
+            double l = 0.0;
+            for (int m = 0; m < M; ++m) {
+                s[m] = exp(s[m] - mx);
+                l += s[m];
+            }
+            for (int m = 0; m < M; ++m) scores[(size_t)b * M + m] += s[m] / l / (double)H;
+        }
+    }
+    free(s);
+    return 0;
+}

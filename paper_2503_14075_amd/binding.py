@@ -27,7 +27,7 @@ TW_CALL_TTP_SCORE, TW_CALL_TREE_VERIFY_ATTN = 1, 2
 _STATUS = {0: "TW_OK", -1: "TW_ERR_INVALID_ARG", -2: "TW_ERR_UNSUPPORTED", -3: "TW_ERR_WORKSPACE",
            -4: "TW_ERR_LAUNCH"}
 
-EXPORTS = ["tw_version", "tw_workspace_bytes", "tw_ttp_score", "tw_ttp_select", "tw_ttp_compact",
+EXPORTS = ["tw_version", "tw_workspace_bytes", "tw_ttp_score", "tw_ttp_score_phead", "tw_ttp_select", "tw_ttp_compact",
            "tw_ttp_compact_batched",
            "tw_tree_ancestor_masks", "tw_tree_verify_attn", "tw_tree_accept", "tw_kv_commit", "tw_validate_tree",
            "tw_rbar"]
@@ -47,6 +47,9 @@ _lib.tw_workspace_bytes.argtypes = [_i32] * 6
 _lib.tw_ttp_score.restype = _i32
 _lib.tw_ttp_score.argtypes = [_vp, _i32, _vp, _vp, ctypes.POINTER(KvView), _vp, _i32, _i32, _i32, _i32,
                               _f32, _i32, _vp, _vp, _sz, _vp]
+_lib.tw_ttp_score_phead.restype = _i32
+_lib.tw_ttp_score_phead.argtypes = [_vp, _vp, ctypes.POINTER(KvView), ctypes.POINTER(KvView), _i32, _i32, _i32,
+                                    _f32, _vp, _vp, _sz, _vp]
 _lib.tw_ttp_select.restype = _i32
 _lib.tw_ttp_select.argtypes = [_vp, _i32, _i32, _i32, _vp, _vp]
 _lib.tw_ttp_compact.restype = _i32
@@ -125,6 +128,13 @@ def ttp_score(q_sel: torch.Tensor, k: KvView, n_q: Optional[torch.Tensor], q_pos
         _ptr(q_sel), n_q_max, _ptr(n_q), _ptr(q_pos0), ctypes.byref(k), _ptr(n_tot), n_tot_max, B,
         v_start, M, scale, int(causal), _ptr(scores), _ptr(ws),
         0 if ws is None else ws.numel() * ws.element_size(), _stream()))
+
+
+def ttp_score_phead(q: torch.Tensor, gq: torch.Tensor, k: KvView, gk: KvView, v_start: int, M: int,
+                    scale: float, scores: torch.Tensor, ws: torch.Tensor) -> None:
+    _check("tw_ttp_score_phead", _lib.tw_ttp_score_phead(
+        _ptr(q), _ptr(gq), ctypes.byref(k), ctypes.byref(gk), q.shape[0], v_start, M, scale, _ptr(scores),
+        _ptr(ws), ws.numel() * ws.element_size(), _stream()))
 
 
 def ttp_select(scores: torch.Tensor, R: int, kept: torch.Tensor) -> None:

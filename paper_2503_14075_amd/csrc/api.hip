@@ -104,6 +104,37 @@ int32_t tw_ttp_score(const void* q_sel, int32_t n_q_max, const int32_t* n_q, con
     return launch_score(a, k->dtype, (hipStream_t)stream) == hipSuccess ? TW_OK : TW_ERR_LAUNCH;
 }
 
+int32_t tw_ttp_score_phead(const void* q, const void* gq, const tw_kv_view* k, const tw_kv_view* gk,
+                           int32_t B, int32_t v_start, int32_t M, float scale, float* scores, void* ws,
+                           size_t ws_bytes, void* stream) {
+    if (B < 0 || M < 0 || v_start < 0) return TW_ERR_INVALID_ARG;
+    if (B == 0 || M == 0) return TW_OK;
+    if (!q || !gq || !scores) return TW_ERR_INVALID_ARG;
+    int vs = view_status(k, false);
+    if (vs != TW_OK) return vs;
+    vs = view_status(gk, false);
+    if (vs != TW_OK) return vs;
+    if (k->dtype != gk->dtype || k->H != gk->H || k->d_h != gk->d_h) return TW_ERR_UNSUPPORTED;
+    if (M > 32768) return TW_ERR_UNSUPPORTED;   // logits of one head are kept in LDS
+    if ((int64_t)v_start + M > k->pool_rows || (int64_t)v_start + M > gk->pool_rows) return TW_ERR_INVALID_ARG;
+    const size_t need = (size_t)B * k->H * M * sizeof(float);
+    if (!ws || ws_bytes < need) return TW_ERR_WORKSPACE;
+    PheadArgs a;
+    a.q = q;
+    a.gq = gq;
+    a.k = to_dev(*k);
+    a.gk = to_dev(*gk);
+    a.scores = scores;
+    a.ws = (float*)ws;
+    a.B = B;
+    a.H = k->H;
+    a.d_h = k->d_h;
+    a.v_start = v_start;
+    a.M = M;
+    a.scale = scale;
+    return launch_phead(a, k->dtype, (hipStream_t)stream) == hipSuccess ? TW_OK : TW_ERR_LAUNCH;
+}
+
 int32_t tw_ttp_select(const float* scores, int32_t B, int32_t M, int32_t R, int32_t* kept,
                       void* stream) {
     if (B < 0 || M < 0 || R < 0 || R > M) return TW_ERR_INVALID_ARG;

@@ -393,6 +393,11 @@ static hipError_t launch_score_mfma_rows(const ScoreArgs& a, hipStream_t s) {
     return launch_score_mfma<DH, 4>(a, s);
 }
 
+hipError_t launch_score_reduce(const ScoreArgs& a, hipStream_t s) {
+    hipLaunchKernelGGL(score_reduce_kernel, dim3((a.M + 255) / 256, a.B), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
 hipError_t launch_score(const ScoreArgs& a, int dtype, hipStream_t s) {
     if (a.B == 0 || a.M == 0) return hipSuccess;
     hipError_t e;
@@ -410,8 +415,7 @@ hipError_t launch_score(const ScoreArgs& a, int dtype, hipStream_t s) {
         e = hipGetLastError();
     }
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(score_reduce_kernel, dim3((a.M + 255) / 256, a.B), dim3(256), 0, s, a);
-    return hipGetLastError();
+    return launch_score_reduce(a, s);
 }
 
 }  // namespace tw

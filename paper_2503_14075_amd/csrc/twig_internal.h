@@ -102,8 +102,21 @@ struct ScoreArgs {
 };
 size_t score_workspace_bytes(int B, int H, int n_q_max, int n_tot_max);
 hipError_t launch_score(const ScoreArgs& a, int dtype, hipStream_t s);
+hipError_t launch_score_reduce(const ScoreArgs& a, hipStream_t s);
 bool score_resident_supported(const ScoreArgs& a, int dtype);
 hipError_t launch_score_resident(const ScoreArgs& a, hipStream_t s);
+
+// --- pruning score, P-Head form ------------------------------------------------
+struct PheadArgs {
+    const void* q;    // [B][H][d_h]
+    const void* gq;   // [B][H][d_h]
+    KvDev k, gk;      // keys and their gates, same layout
+    float* scores;    // [B][M]
+    float* ws;        // [B][H][M]
+    int32_t B, H, d_h, v_start, M;
+    float scale;
+};
+hipError_t launch_phead(const PheadArgs& a, int dtype, hipStream_t s);
 
 // --- select / compact / tree -------------------------------------------------
 hipError_t launch_select(const float* scores, int B, int M, int R, int32_t* kept, hipStream_t s);

@@ -132,3 +132,14 @@ def test_argument_validation_without_launch():
     assert sc(k=_view(pt=P, max_pages=4, page_rows=16)) == tw.TW_ERR_INVALID_ARG   # paged keys not taken
     assert sc() == tw.TW_ERR_WORKSPACE
     assert sc(M=0) == tw.TW_OK
+
+    ph = lambda **kw: lib.tw_ttp_score_phead(
+        kw.get("q", P), P, ctypes.byref(kw.get("k", k)), ctypes.byref(kw.get("gk", k)), 1, kw.get("v_start", 0),
+        kw.get("M", 576), f, P, kw.get("ws", None), kw.get("ws_bytes", 0), None)
+    assert ph(q=None) == tw.TW_ERR_INVALID_ARG
+    assert ph(gk=_view(H=8)) == tw.TW_ERR_UNSUPPORTED
+    assert ph(k=_view(pt=P, max_pages=4, page_rows=16)) == tw.TW_ERR_INVALID_ARG
+    assert ph(M=2000) == tw.TW_ERR_INVALID_ARG                           # span outside the 1000-row pool
+    assert ph(M=40000, k=_view(rows=50000), gk=_view(rows=50000)) == tw.TW_ERR_UNSUPPORTED
+    assert ph() == tw.TW_ERR_WORKSPACE
+    assert ph(M=0) == tw.TW_OK

@@ -484,6 +484,31 @@ def test_score_register_resident_boundary(tw):
                  [1 + (b % 9) for b in range(40)], True)
 
 
+@pytest.mark.parametrize("dtype,H,d_h,M,v0,B", [(torch.bfloat16, 32, 128, 576, 0, 3), (torch.bfloat16, 5, 64, 77, 9, 2),
+                                               (torch.float32, 4, 40, 130, 2, 2), (torch.bfloat16, 2, 128, 2880, 0, 1)])
+def test_score_phead_form(tw, dtype, H, d_h, M, v0, B):
+    n = v0 + M + 11
+    q = W.normal(71, 1, (B, H, d_h), 1.0, dtype)
+    gq = W.normal(71, 2, (B, H, d_h), 1.0, dtype)
+    k = W.normal(71, 3, (B * n + 2, H, d_h), 1.0, dtype)
+    gk = W.normal(71, 4, (B * n + 2, H, d_h), 1.0, dtype)
+    off = [1 + b * n for b in range(B)]
+    scale = 1 / math.sqrt(d_h)
+    want = oracle.ttp_score_phead(q, gq, k, gk, off, off, v0, M, scale)
+    kd, gd, ro = k.to(DEV), gk.to(DEV), _i32(off)
+    ws = torch.empty(tw.workspace_bytes(tw.TW_CALL_TTP_SCORE, B, 1, H, d_h, M) // 4, dtype=torch.float32, device=DEV)
+    scores = torch.full((B, M), float("nan"), dtype=torch.float32, device=DEV)
+    tw.ttp_score_phead(q.to(DEV), gq.to(DEV), tw.kv_view(kd, row_off=ro), tw.kv_view(gd, row_off=ro), v0, M,
+                       scale, scores, ws)
+    torch.cuda.synchronize()
+    got = scores.cpu().double()
+    assert torch.isfinite(got).all()
+    # logits of gated products grow like d_h; fp32 rounding of the 4-factor products gives ~1e-6 relative
+    err = float(((got - want).abs() / (1e-6 + 2e-5 * want)).max())
+    assert err <= 1.0, f"P-Head score error ratio {err:.3f}"
+    assert float((got.sum(1) - 1).abs().max()) < 1e-5
+
+
 def test_score_generic_path(tw):
     _check_score(tw, torch.float32, 4, 64, 90, 3, [20, 9], [8, 9], True)
     _check_score(tw, torch.float32, 2, 128, 70, 0, [33], [33], False, q_std=4.0)

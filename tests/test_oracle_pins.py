@@ -506,3 +506,39 @@ def test_kv_commit_then_decode_equals_attention_over_the_accepted_path():
     want = _causal_library(q[0], k[rows], v[rows], 0.3)[0]
     assert torch.allclose(got, want, atol=1e-12)
     assert W.tree_depths(par)[8] == 4          # the path really is a root-to-node chain of that depth
+
+
+# ----------------------------------------------------------------------------
+# ttp_score_phead  (Sec. 5.1 Eq. 7)
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_phead_score_matches_library_softmax_and_sums_to_one(dtype):
+    B, H, d, M, v0 = 2, 3, 16, 29, 4
+    q = _rand(61, 1, (B, H, d), 1.0, dtype)
+    gq = _rand(61, 2, (B, H, d), 1.0, dtype)
+    k = _rand(61, 3, (B * (v0 + M) + 3, H, d), 1.0, dtype)
+    gk = _rand(61, 4, (B * (v0 + M) + 5, H, d), 1.0, dtype)
+    koff = [1 + b * (v0 + M) for b in range(B)]
+    goff = [2 + b * (v0 + M) for b in range(B)]
+    got = oracle.ttp_score_phead(q, gq, k, gk, koff, goff, v0, M, 0.3)
+    for b in range(B):
+        kk = (k[koff[b] + v0:koff[b] + v0 + M].double() * gk[goff[b] + v0:goff[b] + v0 + M].double())
+        qq = q[b].double() * gq[b].double()
+        logits = 0.3 * torch.einsum("mhc,hc->hm", kk, qq)
+        want = torch.softmax(logits, dim=1).mean(0)
+        assert torch.allclose(got[b], want, atol=1e-13)
+        assert abs(float(got[b].sum()) - 1.0) < 1e-13
+
+
+def test_phead_score_with_unit_gates_is_the_attention_map_form():
+    # gates of one, no text keys, a single non-causal query: Eq. 7 reduces to the Eq. 3 form
+    H, d, M = 4, 8, 21
+    q = _rand(62, 1, (1, H, d))
+    k = _rand(62, 2, (M, H, d))
+    ones_q, ones_k = torch.ones_like(q), torch.ones_like(k)
+    a = oracle.ttp_score_phead(q, ones_q, k, ones_k, [0], [0], 0, M, 0.4)
+    b = oracle.ttp_score(q[:, None].contiguous(), k, [1], [M - 1], [M], [0], 0, M, 0.4, False)
+    assert torch.allclose(a, b, atol=1e-14)
+    # a zero query gate makes every head uniform
+    u = oracle.ttp_score_phead(q, torch.zeros_like(q), k, ones_k, [0], [0], 0, M, 0.4)
+    assert torch.allclose(u, torch.full((1, M), 1.0 / M, dtype=torch.float64), atol=1e-15)
