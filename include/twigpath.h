@@ -225,6 +225,41 @@ int32_t tw_kv_commit(const int32_t* path, const int32_t* n_acc, int32_t T_max, c
                      int32_t n_views, const int32_t* ctx_len, int32_t B, int32_t* new_ctx_len,
                      void* stream);
 
+/*
+ * Rank-ordered top-E of each row (the per-node expansion of the draft tree,
+ * Sec. 5.4 / App. A: "its top-E predicted tokens").  ids[r] / vals[r] receive the
+ * E largest entries of probs[r][0..V), larger value first, equal values lower
+ * index first.  probs [dev] [n][V] fp32 finite; ids [dev] [n][E] int32; vals [dev]
+ * [n][E] fp32.  Errors: INVALID_ARG (E > V, null pointers), UNSUPPORTED (E > 256,
+ * V > 2^20).
+ */
+int32_t tw_draft_topk(const float* probs, int32_t n, int32_t V, int32_t E, int32_t* ids, float* vals,
+                      void* stream);
+
+/*
+ * Pruning of a drafted token tree to its most confident candidates (App. A:
+ * the completed tree keeps at most N_max candidate nodes, highest confidence
+ * first, together with their ancestors).  Candidates 0..n_cand[b)-1 of sequence
+ * b are the drafted nodes in generation order: cand_parent < own index, or -1
+ * for a child of the root; cand_prob in [0, 1] is the draft probability of the
+ * token given its parent.  The confidence of a candidate is the product of
+ * cand_prob along its path; the T_max-1 most confident candidates are kept
+ * (ties toward the lower index; the kept set is closed under taking parents
+ * because confidence never grows along a path).  Output, in the format the
+ * verification calls take: node 0 = root (parent -1, token root_token[b]); kept
+ * candidates follow in ascending candidate index (a topological order);
+ * parent_out / token_out / src_out (the candidate index, -1 for the root) are
+ * [dev] [B][T_max], unused slots hold parent 0, token 0, src -1;
+ * n_nodes_out[b] = 1 + min(T_max - 1, n_cand[b]).
+ * ws: tw_tree_build_workspace_bytes(B, N, T_max).  Errors: INVALID_ARG,
+ * UNSUPPORTED (T_max > 64, N > 8192, B > 65535), WORKSPACE.
+ */
+size_t tw_tree_build_workspace_bytes(int32_t B, int32_t N, int32_t T_max);
+int32_t tw_tree_build(const int32_t* cand_parent, const int32_t* cand_token, const float* cand_prob,
+                      const int32_t* n_cand, const int32_t* root_token, int32_t N, int32_t B, int32_t T_max,
+                      int32_t* parent_out, int32_t* token_out, int32_t* src_out, int32_t* n_nodes_out,
+                      void* ws, size_t ws_bytes, void* stream);
+
 /* Host helper: TW_OK when parent[0] == -1 and 0 <= parent[i] < i for 0 < i < T <= 64. */
 int32_t tw_validate_tree(const int32_t* parent_host, int32_t T);
 

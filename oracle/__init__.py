@@ -209,3 +209,28 @@ def ttp_score_phead(q: torch.Tensor, gq: torch.Tensor, k: torch.Tensor, gk: torc
                                    int(v_start), int(M), ctypes.c_double(scale), _p(out))
     _check(rc, "ttp_score_phead")
     return out
+
+
+def draft_topk(probs: torch.Tensor, E: int):
+    """(ids [n][E] int32, vals [n][E] fp32), larger first, ties lower index first."""
+    assert probs.dtype == torch.float32 and probs.dim() == 2
+    n, V = probs.shape
+    ids = torch.empty(n, E, dtype=torch.int32)
+    vals = torch.empty(n, E, dtype=torch.float32)
+    _check(lib().orc_draft_topk(_p(probs.contiguous()), n, V, int(E), _p(ids), _p(vals)), "draft_topk")
+    return ids, vals
+
+
+def tree_build(cand_parent: Sequence[int], cand_token: Sequence[int], cand_prob: Sequence[float],
+               root_token: int, T_max: int):
+    """(n_nodes, parent [T_max], token [T_max], src [T_max]) for one sequence."""
+    cp, ct = _i32(cand_parent), _i32(cand_token)
+    pb = torch.as_tensor(cand_prob, dtype=torch.float32).contiguous()
+    par = torch.empty(T_max, dtype=torch.int32)
+    tok = torch.empty(T_max, dtype=torch.int32)
+    src = torch.empty(T_max, dtype=torch.int32)
+    n = lib().orc_tree_build(_p(cp), _p(ct), _p(pb), int(cp.numel()), int(root_token), int(T_max), _p(par),
+                             _p(tok), _p(src))
+    if n < 0:
+        raise ValueError(f"oracle tree_build: invalid argument (code {n})")
+    return int(n), par, tok, src

@@ -376,3 +376,76 @@ int orc_ttp_score_phead(const void* q, const void* gq, const void* k, const void
     free(s);
     return 0;
 }
+
+/*
+ * Rank-ordered top-E of a row (per-node expansion of the draft tree, Sec. 5.4 /
+ * App. A): the E largest values, larger first, equal values lower index first.
+ */
+int orc_draft_topk(const float* probs, int n, int V, int E, int32_t* ids, float* vals) {
+    if (n < 0 || V < 0 || E < 0 || E > V) return -1;
+    if (n > 0 && E > 0 && (!probs || !ids || !vals)) return -1;
+    orc_pair* pr = (orc_pair*)malloc(sizeof(orc_pair) * (size_t)(V > 0 ? V : 1));
+    if (!pr) return -3;
+    for (int r = 0; r < n; ++r) {
+        for (int m = 0; m < V; ++m) {
+            pr[m].s = probs[(size_t)r * V + m];
+            pr[m].m = m;
+        }
+        qsort(pr, (size_t)V, sizeof(orc_pair), pair_cmp);
+        for (int e = 0; e < E; ++e) {
+            ids[(size_t)r * E + e] = pr[e].m;
+            vals[(size_t)r * E + e] = pr[e].s;
+        }
+    }
+    free(pr);
+    return 0;
+}
+
+/*
+ * Pruning of a drafted tree to its most confident candidates (App. A).  The
+ * confidence of candidate i is the product of cand_prob along its path from the
+ * root (computed in fp32 from the node upwards, the order the GPU uses, so that
+ * ties and the order of near-equal confidences are decided identically); the
+ * T_max - 1 most confident candidates are kept, ties toward the lower index;
+ * node 0 is the root, kept candidates follow in ascending candidate index.
+ * One sequence per call.  Returns the number of nodes (root included), -1 on
+ * invalid arguments.
+ */
+int orc_tree_build(const int32_t* cand_parent, const int32_t* cand_token, const float* cand_prob, int n_cand,
+                   int32_t root_token, int T_max, int32_t* parent_out, int32_t* token_out, int32_t* src_out) {
+    if (n_cand < 0 || T_max < 1 || T_max > 64 || !parent_out || !token_out || !src_out) return -1;
+    for (int i = 0; i < n_cand; ++i)
+        if (cand_parent[i] < -1 || cand_parent[i] >= i) return -1;
+    int n_keep = n_cand < T_max - 1 ? n_cand : T_max - 1;
+    orc_pair* pr = (orc_pair*)malloc(sizeof(orc_pair) * (size_t)(n_cand > 0 ? n_cand : 1));
+    int32_t* node_of = (int32_t*)malloc(sizeof(int32_t) * (size_t)(n_cand > 0 ? n_cand : 1));
+    if (!pr || !node_of) return -3;
+    for (int i = 0; i < n_cand; ++i) {
+        float c = 1.0f;
+        for (int u = i; u >= 0; u = cand_parent[u]) c *= cand_prob[u];
+        pr[i].s = c;
+        pr[i].m = i;
+        node_of[i] = 0;
+    }
+    qsort(pr, (size_t)n_cand, sizeof(orc_pair), pair_cmp);
+    int32_t keep[64];
+    for (int r = 0; r < n_keep; ++r) keep[r] = pr[r].m;
+    qsort(keep, (size_t)n_keep, sizeof(int32_t), int_cmp);
+    for (int t = 0; t < T_max; ++t) {
+        parent_out[t] = 0;
+        token_out[t] = 0;
+        src_out[t] = -1;
+    }
+    parent_out[0] = -1;
+    token_out[0] = root_token;
+    for (int r = 0; r < n_keep; ++r) node_of[keep[r]] = 1 + r;
+    for (int r = 0; r < n_keep; ++r) {
+        int c = keep[r];
+        parent_out[1 + r] = cand_parent[c] < 0 ? 0 : node_of[cand_parent[c]];
+        token_out[1 + r] = cand_token[c];
+        src_out[1 + r] = c;
+    }
+    free(pr);
+    free(node_of);
+    return 1 + n_keep;
+}

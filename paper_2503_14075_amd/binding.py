@@ -29,7 +29,8 @@ _STATUS = {0: "TW_OK", -1: "TW_ERR_INVALID_ARG", -2: "TW_ERR_UNSUPPORTED", -3: "
 
 EXPORTS = ["tw_version", "tw_workspace_bytes", "tw_ttp_score", "tw_ttp_score_phead", "tw_ttp_select", "tw_ttp_compact",
            "tw_ttp_compact_batched",
-           "tw_tree_ancestor_masks", "tw_tree_verify_attn", "tw_tree_accept", "tw_kv_commit", "tw_validate_tree",
+           "tw_tree_ancestor_masks", "tw_tree_verify_attn", "tw_tree_accept", "tw_kv_commit", "tw_draft_topk",
+           "tw_tree_build_workspace_bytes", "tw_tree_build", "tw_validate_tree",
            "tw_rbar"]
 
 
@@ -67,6 +68,12 @@ _lib.tw_tree_accept.restype = _i32
 _lib.tw_tree_accept.argtypes = [_vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp, _vp, _vp]
 _lib.tw_kv_commit.restype = _i32
 _lib.tw_kv_commit.argtypes = [_vp, _vp, _i32, ctypes.POINTER(KvView), _i32, _vp, _i32, _vp, _vp]
+_lib.tw_draft_topk.restype = _i32
+_lib.tw_draft_topk.argtypes = [_vp, _i32, _i32, _i32, _vp, _vp, _vp]
+_lib.tw_tree_build_workspace_bytes.restype = _sz
+_lib.tw_tree_build_workspace_bytes.argtypes = [_i32, _i32, _i32]
+_lib.tw_tree_build.restype = _i32
+_lib.tw_tree_build.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.tw_validate_tree.restype = _i32
 _lib.tw_validate_tree.argtypes = [ctypes.POINTER(_i32), _i32]
 _lib.tw_rbar.restype = _i32
@@ -192,6 +199,26 @@ def kv_commit(path: torch.Tensor, n_acc: torch.Tensor, views: Sequence[KvView], 
     arr = (KvView * max(len(views), 1))(*views)
     _check("tw_kv_commit", _lib.tw_kv_commit(_ptr(path), _ptr(n_acc), T_max, arr, len(views), _ptr(ctx_len),
                                              B, _ptr(new_ctx_len), _stream()))
+
+
+def draft_topk(probs: torch.Tensor, E: int, ids: torch.Tensor, vals: torch.Tensor) -> None:
+    n, V = probs.shape
+    _check("tw_draft_topk", _lib.tw_draft_topk(_ptr(probs), n, V, E, _ptr(ids), _ptr(vals), _stream()))
+
+
+def tree_build_workspace_bytes(B: int, N: int, T_max: int) -> int:
+    return int(_lib.tw_tree_build_workspace_bytes(B, N, T_max))
+
+
+def tree_build(cand_parent: torch.Tensor, cand_token: torch.Tensor, cand_prob: torch.Tensor,
+               n_cand: torch.Tensor, root_token: torch.Tensor, T_max: int, parent_out: torch.Tensor,
+               token_out: torch.Tensor, src_out: torch.Tensor, n_nodes_out: torch.Tensor,
+               ws: Optional[torch.Tensor]) -> None:
+    B, N = cand_parent.shape
+    _check("tw_tree_build", _lib.tw_tree_build(
+        _ptr(cand_parent), _ptr(cand_token), _ptr(cand_prob), _ptr(n_cand), _ptr(root_token), N, B, T_max,
+        _ptr(parent_out), _ptr(token_out), _ptr(src_out), _ptr(n_nodes_out), _ptr(ws),
+        0 if ws is None else ws.numel() * ws.element_size(), _stream()))
 
 
 def validate_tree(parent: Sequence[int]) -> int:

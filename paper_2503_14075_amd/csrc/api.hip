@@ -311,6 +311,59 @@ int32_t tw_kv_commit(const int32_t* path, const int32_t* n_acc, int32_t T_max, c
     return TW_OK;
 }
 
+int32_t tw_draft_topk(const float* probs, int32_t n, int32_t V, int32_t E, int32_t* ids, float* vals,
+                      void* stream) {
+    if (n < 0 || V < 0 || E < 0 || E > V) return TW_ERR_INVALID_ARG;
+    if (E > 256 || V > (1 << 20)) return TW_ERR_UNSUPPORTED;
+    if (n == 0 || E == 0) return TW_OK;
+    if (!probs || !ids || !vals) return TW_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    if (launch_select(probs, n, V, E, ids, s) != hipSuccess) return TW_ERR_LAUNCH;   // survivors, ascending index
+    return launch_rank_sort(probs, n, V, E, ids, vals, s) == hipSuccess ? TW_OK : TW_ERR_LAUNCH;
+}
+
+size_t tw_tree_build_workspace_bytes(int32_t B, int32_t N, int32_t T_max) {
+    if (B <= 0 || N <= 0 || T_max <= 1) return 0;
+    const int R = T_max - 1 < N ? T_max - 1 : N;
+    return (size_t)B * N * sizeof(float) + (size_t)B * R * sizeof(int32_t);
+}
+
+int32_t tw_tree_build(const int32_t* cand_parent, const int32_t* cand_token, const float* cand_prob,
+                      const int32_t* n_cand, const int32_t* root_token, int32_t N, int32_t B, int32_t T_max,
+                      int32_t* parent_out, int32_t* token_out, int32_t* src_out, int32_t* n_nodes_out,
+                      void* ws, size_t ws_bytes, void* stream) {
+    if (B < 0 || N < 0 || T_max < 1) return TW_ERR_INVALID_ARG;
+    if (T_max > TW_MAX_TREE || N > 8192) return TW_ERR_UNSUPPORTED;
+    if (B == 0) return TW_OK;
+    if (B > 65535) return TW_ERR_UNSUPPORTED;
+    if (!n_cand || !root_token || !parent_out || !token_out || !src_out || !n_nodes_out) return TW_ERR_INVALID_ARG;
+    if (N > 0 && (!cand_parent || !cand_token || !cand_prob)) return TW_ERR_INVALID_ARG;
+    const int R = T_max - 1 < N ? T_max - 1 : N;
+    const size_t need = tw_tree_build_workspace_bytes(B, N, T_max);
+    if (need > 0 && (!ws || ws_bytes < need)) return TW_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    float* conf = (float*)ws;
+    int32_t* kept = (int32_t*)((char*)ws + (size_t)B * N * sizeof(float));
+    if (R > 0) {
+        if (launch_tree_conf(cand_parent, cand_prob, n_cand, B, N, conf, s) != hipSuccess) return TW_ERR_LAUNCH;
+        if (launch_select(conf, B, N, R, kept, s) != hipSuccess) return TW_ERR_LAUNCH;
+    }
+    TreeBuildArgs a;
+    a.cand_parent = cand_parent;
+    a.cand_token = cand_token;
+    a.n_cand = n_cand;
+    a.root_token = root_token;
+    a.kept = kept;
+    a.parent_out = parent_out;
+    a.token_out = token_out;
+    a.src_out = src_out;
+    a.n_nodes_out = n_nodes_out;
+    a.N = N;
+    a.R = R;
+    a.T_max = T_max;
+    return launch_tree_emit(a, B, s) == hipSuccess ? TW_OK : TW_ERR_LAUNCH;
+}
+
 int32_t tw_validate_tree(const int32_t* parent_host, int32_t T) {
     if (!parent_host || T < 1) return TW_ERR_INVALID_ARG;
     if (T > TW_MAX_TREE) return TW_ERR_UNSUPPORTED;

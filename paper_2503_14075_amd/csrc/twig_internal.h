@@ -137,6 +137,25 @@ struct CompactBatch {
 hipError_t launch_compact(const CompactBatch& cb, int B, int n_out_max, const CompactTable& tab,
                           int n_tensors, size_t row_bytes, hipStream_t s);
 
+// --- draft-side tree build ------------------------------------------------------
+struct TreeBuildArgs {
+    const int32_t* cand_parent;  // [B][N]
+    const int32_t* cand_token;   // [B][N]
+    const int32_t* n_cand;       // [B]
+    const int32_t* root_token;   // [B]
+    const int32_t* kept;         // [B][R] ascending
+    int32_t* parent_out;         // [B][T_max]
+    int32_t* token_out;          // [B][T_max]
+    int32_t* src_out;            // [B][T_max]
+    int32_t* n_nodes_out;        // [B]
+    int32_t N, R, T_max;
+};
+hipError_t launch_rank_sort(const float* vals, int n, int V, int E, int32_t* ids, float* out_vals,
+                            hipStream_t s);
+hipError_t launch_tree_conf(const int32_t* cand_parent, const float* cand_prob, const int32_t* n_cand, int B,
+                            int N, float* conf, hipStream_t s);
+hipError_t launch_tree_emit(const TreeBuildArgs& a, int B, hipStream_t s);
+
 // --- commit of the accepted path ------------------------------------------------
 constexpr int kCommitMaxViews = 32;
 struct CommitArgs {

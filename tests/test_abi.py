@@ -101,6 +101,20 @@ def test_argument_validation_without_launch():
     assert kc(B=70000) == tw.TW_ERR_UNSUPPORTED
     assert kc(B=0) == tw.TW_OK
 
+    assert lib.tw_draft_topk(P, 2, 100, 101, P, P, None) == tw.TW_ERR_INVALID_ARG      # E > V
+    assert lib.tw_draft_topk(P, 2, 32000, 300, P, P, None) == tw.TW_ERR_UNSUPPORTED
+    assert lib.tw_draft_topk(None, 2, 100, 10, P, P, None) == tw.TW_ERR_INVALID_ARG
+    assert lib.tw_draft_topk(P, 0, 100, 10, P, P, None) == tw.TW_OK
+    tb = lambda **kw: lib.tw_tree_build(kw.get("cp", P), P, P, P, P, kw.get("N", 310), kw.get("B", 1),
+                                        kw.get("T", 61), P, P, P, P, kw.get("ws", None), kw.get("ws_bytes", 0), None)
+    assert tb(T=65) == tw.TW_ERR_UNSUPPORTED
+    assert tb(T=0) == tw.TW_ERR_INVALID_ARG
+    assert tb(N=9000) == tw.TW_ERR_UNSUPPORTED
+    assert tb(cp=None) == tw.TW_ERR_INVALID_ARG
+    assert tb() == tw.TW_ERR_WORKSPACE
+    assert tb(B=0) == tw.TW_OK
+    assert tw.tree_build_workspace_bytes(2, 310, 61) == 2 * 310 * 4 + 2 * 60 * 4
+
     f = ctypes.c_float(0.1)
     k, v = _view(), _view()
     call = lambda **kw: lib.tw_tree_verify_attn(

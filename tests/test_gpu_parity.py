@@ -517,6 +517,74 @@ def test_score_generic_path(tw):
 
 
 # ----------------------------------------------------------------------------
+# draft-side tree build
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("V,E", [(32000, 10), (301, 64), (50, 50), (7, 1)])
+def test_draft_topk_bit_exact(tw, V, E):
+    g = torch.Generator().manual_seed(V)
+    probs = torch.softmax(torch.randn(9, V, generator=g) * 4, dim=1)
+    probs[1, : V // 2] = probs[1, 0]          # plateau of ties
+    probs[2] = 1.0 / V
+    probs[3] = torch.round(probs[3] * 64) / 64  # few distinct values
+    ids = torch.full((9, E), -7, dtype=torch.int32, device=DEV)
+    vals = torch.full((9, E), -7.0, dtype=torch.float32, device=DEV)
+    tw.draft_topk(probs.to(DEV), E, ids, vals)
+    torch.cuda.synchronize()
+    wi, wv = oracle.draft_topk(probs, E)
+    assert torch.equal(ids.cpu(), wi) and torch.equal(vals.cpu(), wv)
+
+
+def test_tree_build_bit_exact_and_feeds_verification(tw):
+    B, E, K, D, T_max = 7, 10, 10, 4, 61          # the paper's defaults: N_max = 60 candidates + root
+    rng = W.HostRng(91, 0)
+    cands = []
+    for b in range(B):
+        par, tok, prob = [], [], []
+        prev = []
+        e_b = E if b else 3                        # one sequence with fewer candidates than room
+        k_b = K if b else 2
+        d_b = D if b else 2
+        for e in range(e_b):
+            par.append(-1), tok.append(rng.randint(0, 31999)), prob.append(rng.uniform()), prev.append(e)
+        for _ in range(1, d_b):
+            cur = []
+            for u in prev[:k_b]:
+                for _e in range(e_b):
+                    par.append(u), tok.append(rng.randint(0, 31999))
+                    prob.append(rng.uniform() if rng.uniform() > 0.1 else 1.0)   # some exact ties
+                    cur.append(len(par) - 1)
+            rng.shuffle(cur)
+            prev = cur
+        cands.append((par, tok, prob))
+    N = max(len(c[0]) for c in cands)
+    pad = lambda xs, v: xs + [v] * (N - len(xs))
+    cp = _i32([pad(c[0], 0) for c in cands])
+    ct = _i32([pad(c[1], 0) for c in cands])
+    pb = torch.tensor([pad(c[2], 0.0) for c in cands], dtype=torch.float32, device=DEV)
+    n_cand = _i32([len(c[0]) for c in cands])
+    root = _i32([100 + b for b in range(B)])
+    po = torch.full((B, T_max), -9, dtype=torch.int32, device=DEV)
+    to = torch.full((B, T_max), -9, dtype=torch.int32, device=DEV)
+    so = torch.full((B, T_max), -9, dtype=torch.int32, device=DEV)
+    nn = torch.full((B,), -9, dtype=torch.int32, device=DEV)
+    ws = torch.empty(tw.tree_build_workspace_bytes(B, N, T_max) // 4 + 1, dtype=torch.float32, device=DEV)
+    tw.tree_build(cp, ct, pb, n_cand, root, T_max, po, to, so, nn, ws)
+    torch.cuda.synchronize()
+    for b, (par, tok, prob) in enumerate(cands):
+        n, wp, wt, wsrc = oracle.tree_build(par, tok, prob, 100 + b, T_max)
+        assert int(nn[b]) == n
+        assert torch.equal(po[b].cpu(), wp) and torch.equal(to[b].cpu(), wt) and torch.equal(so[b].cpu(), wsrc)
+        assert tw.validate_tree(po[b].cpu()[:n].tolist()) == tw.TW_OK
+    # the emitted parent[] goes straight into the verification attention
+    H, d_h = 4, 128
+    ctx = [20 + 3 * b for b in range(B)]
+    trees = [po[b].cpu().tolist() for b in range(B)]
+    n_nodes = nn.cpu().tolist()
+    q, k, v, off = make_case(92, B, H, d_h, ctx, T_max, torch.bfloat16, trees)
+    check_verify(tw, q, k, v, ctx, n_nodes, trees, 1 / math.sqrt(d_h), row_off=off)
+
+
+# ----------------------------------------------------------------------------
 # the five configurations, whole path
 # ----------------------------------------------------------------------------
 def _path_parity(runner, cfg, verify_instances=None, check_compact_tensors=None):

@@ -542,3 +542,88 @@ def test_phead_score_with_unit_gates_is_the_attention_map_form():
     # a zero query gate makes every head uniform
     u = oracle.ttp_score_phead(q, torch.zeros_like(q), k, ones_k, [0], [0], 0, M, 0.4)
     assert torch.allclose(u, torch.full((1, M), 1.0 / M, dtype=torch.float64), atol=1e-15)
+
+
+# ----------------------------------------------------------------------------
+# draft-side tree build (Sec. 5.4, App. A)
+# ----------------------------------------------------------------------------
+def test_draft_topk_vs_stable_argsort():
+    g = torch.Generator().manual_seed(3)
+    probs = torch.softmax(torch.randn(5, 301, generator=g) * 3, dim=1)
+    probs[1, 7:40] = probs[1, 7]                      # a plateau of equal probabilities
+    probs[2] = 1.0 / 301                              # all equal
+    for E in (1, 10, 64):
+        ids, vals = oracle.draft_topk(probs, E)
+        for r in range(5):
+            order = np.argsort(-probs[r].numpy(), kind="stable")[:E]
+            assert ids[r].tolist() == order.tolist()
+            assert torch.equal(vals[r], probs[r][order])
+    with pytest.raises(ValueError):
+        oracle.draft_topk(probs, 302)
+
+
+def _drafted_candidates(rng, E, K, D):
+    """Level-wise expansion as in App. A with seeded probabilities: level 1 = E children of the
+    root, each later level expands K nodes of the previous level into E children."""
+    par, tok, prob, level = [], [], [], []
+    prev = []
+    for e in range(E):
+        par.append(-1), tok.append(rng.randint(0, 31999)), prob.append(rng.uniform()), prev.append(e)
+    for _ in range(1, D):
+        cur = []
+        for u in prev[:K]:
+            for _e in range(E):
+                par.append(u), tok.append(rng.randint(0, 31999)), prob.append(rng.uniform())
+                cur.append(len(par) - 1)
+        rng.shuffle(cur)
+        prev = cur
+    return par, tok, prob
+
+
+@pytest.mark.parametrize("seed", range(5))
+def test_tree_build_keeps_most_confident_ancestor_closed_set(seed):
+    rng = W.HostRng(seed, 9)
+    par, tok, prob = _drafted_candidates(rng, 4, 3, 4)
+    N, T_max = len(par), 17
+    n, p_out, t_out, s_out = oracle.tree_build(par, tok, prob, 123, T_max)
+    assert n == min(T_max, N + 1) and int(p_out[0]) == -1 and int(t_out[0]) == 123 and int(s_out[0]) == -1
+    # brute force: fp32 confidences, stable order (confidence desc, index asc), first T_max-1
+    conf = []
+    for i in range(N):
+        c, u = np.float32(1.0), i
+        while u >= 0:
+            c = np.float32(c * np.float32(prob[u]))
+            u = par[u]
+        conf.append(c)
+    order = sorted(range(N), key=lambda i: (-conf[i], i))[:T_max - 1]
+    keep = sorted(order)
+    assert s_out[1:n].tolist() == keep
+    node_of = {c: 1 + r for r, c in enumerate(keep)}
+    for r, c in enumerate(keep):
+        assert par[c] < 0 or par[c] in node_of                       # closed under taking parents
+        assert int(p_out[1 + r]) == (0 if par[c] < 0 else node_of[par[c]])
+        assert int(t_out[1 + r]) == tok[c]
+        assert 0 <= int(p_out[1 + r]) < 1 + r                        # topological: usable as parent[]
+    assert oracle.tree_ancestors(p_out[:n].tolist())                 # accepted by the tree routines
+    # every dropped candidate is no more confident than every kept one
+    dropped = [i for i in range(N) if i not in node_of]
+    if dropped and keep:
+        assert max(conf[i] for i in dropped) <= min(conf[i] for i in keep)
+
+
+def test_tree_build_special_cases():
+    # fewer candidates than room: everything is kept in generation order
+    n, p, t, s = oracle.tree_build([-1, 0, 1], [5, 6, 7], [0.5, 0.5, 0.5], 9, 8)
+    assert n == 4 and p.tolist() == [-1, 0, 1, 2, 0, 0, 0, 0] and t.tolist() == [9, 5, 6, 7, 0, 0, 0, 0]
+    assert s.tolist() == [-1, 0, 1, 2, -1, -1, -1, -1]
+    # equal confidences: lower index wins, so a parent is never dropped in favour of its child
+    n, p, t, s = oracle.tree_build([-1, 0, 1, 2], [1, 2, 3, 4], [1.0, 1.0, 1.0, 1.0], 0, 3)
+    assert n == 3 and s.tolist() == [-1, 0, 1]
+    # star: the two most probable children of the root
+    n, p, t, s = oracle.tree_build([-1, -1, -1, -1], [1, 2, 3, 4], [0.1, 0.4, 0.2, 0.3], 0, 3)
+    assert s.tolist() == [-1, 1, 3] and p.tolist() == [-1, 0, 0]
+    # no candidates: the root alone
+    n, p, t, s = oracle.tree_build([], [], [], 77, 4)
+    assert n == 1 and p.tolist() == [-1, 0, 0, 0] and int(t[0]) == 77
+    with pytest.raises(ValueError):
+        oracle.tree_build([-1, 1], [1, 2], [0.5, 0.5], 0, 4)          # parent not before child
