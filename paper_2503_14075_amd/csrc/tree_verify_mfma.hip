@@ -253,8 +253,7 @@ __device__ __forceinline__ void epilogue_merge(const WaveState<DH>& w, const Ver
 struct SeqInfo {
     int T, C, n_rows, r_begin, r_end;
 };
-__device__ __forceinline__ SeqInfo seq_info(const VerifyArgs& a, int b, int split, int tid, int* s_parent,
-                                            unsigned long long* s_anc) {
+__device__ __forceinline__ SeqInfo seq_info(const VerifyArgs& a, int b, int split) {
     SeqInfo s;
     int T = a.n_nodes[b];
     s.T = T < 1 ? 1 : (T > a.T_max ? a.T_max : T);
@@ -265,11 +264,17 @@ __device__ __forceinline__ SeqInfo seq_info(const VerifyArgs& a, int b, int spli
     per = (per + kChunk - 1) / kChunk * kChunk;
     s.r_begin = min(split * per, s.n_rows);
     s.r_end = min(s.r_begin + per, s.n_rows);
-    if (tid < TW_MAX_TREE) s_parent[tid] = tid < s.T ? a.parent[(int64_t)b * a.T_max + tid] : 0;
-    __syncthreads();
-    if (tid < TW_MAX_TREE) s_anc[tid] = tid < s.T ? ancestor_mask(s_parent, tid) : 0ull;
-    __syncthreads();
     return s;
+}
+
+// Ancestor masks of the sequence's tree into shared memory (workgroup-wide, two barriers).  Called
+// after the first K/V loads have been issued so that their latency overlaps this prologue.
+__device__ __forceinline__ void tree_masks(const VerifyArgs& a, int b, int T, int tid, int* s_parent,
+                                           unsigned long long* s_anc) {
+    if (tid < TW_MAX_TREE) s_parent[tid] = tid < T ? a.parent[(int64_t)b * a.T_max + tid] : 0;
+    __syncthreads();
+    if (tid < TW_MAX_TREE) s_anc[tid] = tid < T ? ancestor_mask(s_parent, tid) : 0ull;
+    __syncthreads();
 }
 
 // Pool row of cache row r (paged or contiguous), clamped into the pool.
@@ -299,16 +304,13 @@ __global__ __launch_bounds__(kMfThreads, 2) void verify_mfma_kernel(VerifyArgs a
     const int n_phase = a.n_phase;               // 1 (four heads per workgroup) or 4 (one head)
     const int phase = wave % n_phase;
     const int h = blockIdx.x * a.heads_per_wg + wave / n_phase;
-    const SeqInfo sq = seq_info(a, b, split, tid, s_parent, s_anc);
+    const SeqInfo sq = seq_info(a, b, split);
     const bool active = h < a.H;
     const int hc = active ? h : a.H - 1;
     const int t = li;                            // this lane's tree node
 
     unsigned char* ldsK = lds + wave * Cf::kStage;
     unsigned char* ldsV = ldsK + kChunk * Cf::kKStride;
-    WaveState<DH> w;
-    w.anc = s_anc[t];
-    load_q(w, a, b, hc, t, sq.T, g);
     const float sl2 = a.scale * kLog2e;
 
     // lane's share of a chunk load: row (lane / lanes_per_row) + rows_per_load * j,
@@ -354,6 +356,11 @@ __global__ __launch_bounds__(kMfThreads, 2) void verify_mfma_kernel(VerifyArgs a
         issue_loads(first);
         if (PAGED) lookup_pages(first + step);
     }
+    // the first chunk is in flight; now the tree masks and the Q fragments
+    tree_masks(a, b, sq.T, tid, s_parent, s_anc);
+    WaveState<DH> w;
+    w.anc = s_anc[t];
+    load_q(w, a, b, hc, t, sq.T, g);
     for (int base = first; active && base < sq.r_end; base += step) {
 #pragma unroll
         for (int j = 0; j < Cf::kLoads; ++j) {
@@ -395,15 +402,12 @@ __global__ __launch_bounds__(kMfThreads, 2) void verify_mfma_pair_kernel(VerifyA
     const int n_phase = a.n_phase;               // 1 (two heads per workgroup) or 2 (one head)
     const int phase = n_phase == 1 ? 0 : pair;
     const int h = blockIdx.x * a.heads_per_wg + (n_phase == 1 ? pair : 0);
-    const SeqInfo sq = seq_info(a, b, split, tid, s_parent, s_anc);
+    const SeqInfo sq = seq_info(a, b, split);
     const bool active = h < a.H;
     const int hc = active ? h : a.H - 1;
     const int t = 32 * blk + li;
 
     unsigned char* stage = lds + pair * 2 * Cf::kStage;   // two buffers of one K+V chunk
-    WaveState<DH> w;
-    w.anc = s_anc[t];
-    load_q(w, a, b, hc, t, sq.T, g);
     const float sl2 = a.scale * kLog2e;
 
     const int ld_row = lane / Cf::kLanesPerRow, ld_col = lane % Cf::kLanesPerRow;
@@ -445,6 +449,11 @@ __global__ __launch_bounds__(kMfThreads, 2) void verify_mfma_pair_kernel(VerifyA
     const int first = sq.r_begin + kChunk * phase;
     issue_loads(first, 0);
     issue_loads(first + step, 1);
+    // two chunks are in flight; now the tree masks and the Q fragments
+    tree_masks(a, b, sq.T, tid, s_parent, s_anc);
+    WaveState<DH> w;
+    w.anc = s_anc[t];
+    load_q(w, a, b, hc, t, sq.T, g);
     for (int it = 0; it < n_iter; it += 2) {
 #pragma unroll
         for (int half = 0; half < 2; ++half) {

@@ -655,3 +655,31 @@ def test_cfg3_ragged_paged_batch(runner):
 
 def test_cfg4_high_resolution(runner):
     _path_parity(runner, W.CONFIGS["cfg4"], verify_instances=[0, 3])
+
+
+def test_bench_launch_configuration_sampled(runner):
+    # the workload bench.py times (cfg1 x 128 sequences, generated on the device), checked on sampled
+    # sequences that the oracle computes one by one from the very bytes the GPU used
+    cfg = W.replicate(W.CONFIGS["cfg1"], 128)
+    w = W.make_workload(cfg, device=DEV)
+    dw = runner.DeviceWorkload(w, DEV)
+    dw.step()
+    torch.cuda.synchronize()
+    scores, kept, out = dw.scores.cpu(), dw.kept.cpu(), dw.out.cpu()
+    wa = oracle.tree_accept(w.draft, w.argmax, w.tree_seq, [cfg.T] * cfg.B)
+    assert torch.equal(dw.n_acc.cpu(), wa[0]) and torch.equal(dw.path.cpu(), wa[1]) and torch.equal(dw.bonus.cpu(), wa[2])
+    assert torch.equal(kept, oracle.ttp_select(scores, cfg.R))
+    for b in (0, 1, 63, 126, 127):
+        off, n_tot = w.score_row_off[b], w.n_tot[b]
+        want_sc = oracle.ttp_score(w.q_sel[b:b + 1].cpu(), w.k_score[off:off + n_tot].cpu(), [w.n_q[b]],
+                                   [w.q_pos0[b]], [n_tot], [0], 0, cfg.M, cfg.scale, True)[0]
+        assert float((scores[b].double() - want_sc).abs().max()) <= SCORE_TOL
+        d0 = w.compact_dst_off[b]
+        for src, dst in zip(w.compact_src, dw.compact_dst):
+            want = oracle.ttp_compact(kept[b], 0, cfg.M, src[off:off + n_tot].cpu())
+            assert torch.equal(dst[d0:d0 + want.shape[0]].cpu().view(torch.int16), want.view(torch.int16))
+        r0, nr = w.row_off[b], w.ctx_len[b] + cfg.T
+        want_o = oracle.tree_verify_attn(w.q_tree[b:b + 1].cpu(), w.k_pool[r0:r0 + nr].cpu(),
+                                         w.v_pool[r0:r0 + nr].cpu(), [w.ctx_len[b]], [cfg.T], [w.parent[b]],
+                                         cfg.scale, row_off=[0])[0]
+        assert float((out[b].double() - want_o).abs().max()) <= ATTN_TOL
