@@ -474,8 +474,18 @@ def test_score_span_not_at_zero_sharp_and_small_heads(tw):
     _check_score(tw, torch.bfloat16, 4, 128, 100, 5, [20], [20], False, q_std=6.0)
 
 
+def test_score_resident_limits(tw):
+    # the table of exponentials holds one 32-key chunk per chunk that the visual span touches:
+    # 23 of them fit beside 64 scoring rows, a 24th sends the call to the two-pass kernel
+    _check_score(tw, torch.bfloat16, 4, 128, 736, 0, [32], [64], True)
+    _check_score(tw, torch.bfloat16, 4, 128, 760, 0, [8], [40], True)
+    # a span that starts on an odd key, two row blocks, both head sizes
+    _check_score(tw, torch.bfloat16, 3, 128, 100, 31, [70, 40], [64, 50], True)
+    _check_score(tw, torch.bfloat16, 3, 64, 300, 33, [64, 20], [64, 20], False, q_std=4.0)
+
+
 def test_score_register_resident_boundary(tw):
-    # 768 keys is the longest prompt whose logits stay in registers; 769 takes the two-pass kernel
+    # 768 keys is the longest prompt that the one-pass kernel takes; 769 takes the two-pass kernel
     _check_score(tw, torch.bfloat16, 4, 128, 576, 0, [192, 100], [64, 33], True)
     _check_score(tw, torch.bfloat16, 4, 128, 576, 0, [193, 100], [64, 33], True)
     _check_score(tw, torch.bfloat16, 5, 128, 700, 20, [48], [17], False, q_std=5.0)
