@@ -9,9 +9,10 @@ batch (default 128 sequences) is what makes the working set larger than the
 on-die caches, so every launch streams its K/V from HBM.
 
 Prints ONE JSON line: whole-step throughput in verified tree tokens per second,
-the HBM roofline of the dominant kernel (tree_verify_attn) from HIP-event
-timings taken inside the timed steps, and the CPU oracle timed on a bounded
-sample of the same inputs on this machine's host cores.
+the HBM roofline of the kernel the metric is named for (tree_verify_attn) from
+HIP-event timings taken inside the timed steps, per-stage times and bandwidths of
+all five calls (extras.stages), and the CPU oracle timed on a bounded sample of
+the same inputs on this machine's host cores.
 """
 import argparse
 import json
@@ -85,6 +86,36 @@ def main():
     ker_avg = sum(ker_ms) / len(ker_ms)
     vbytes = verify_bytes(cfg, w)
     achieved = vbytes / (ker_avg * 1e-3) / 1e9
+
+    # per-stage times of the same step (a separate, untimed pass: events around every call)
+    stage_names = ("ttp_score", "ttp_select", "ttp_compact", "tree_verify_attn", "tree_accept")
+    calls = (dw.run_score, dw.run_select, dw.run_compact, dw.run_verify, dw.run_accept)
+    stage_ev = []
+    for _ in range(20):
+        marks = [torch.cuda.Event(enable_timing=True) for _ in range(len(calls) + 1)]
+        marks[0].record()
+        for call, m in zip(calls, marks[1:]):
+            call()
+            m.record()
+        stage_ev.append(marks)
+    torch.cuda.synchronize()
+    row = cfg.H * cfg.d_h * 2
+    stage_bytes = {
+        # K of every sequence once, the scoring rows of Q, the scores
+        "ttp_score": sum(n * row + q * row + 4 * cfg.M for n, q in zip(w.n_tot, w.n_q)),
+        # every kept row of every tensor read once and written once
+        "ttp_compact": sum(2 * (cfg.R + n) * t.shape[1:].numel() * t.element_size()
+                           for n in w.n_text for t in w.compact_src),
+        "tree_verify_attn": vbytes,
+    }
+    stages = {}
+    for i, name in enumerate(stage_names):
+        ts = sorted(m[i].elapsed_time(m[i + 1]) for m in stage_ev)
+        med = ts[len(ts) // 2]
+        stages[name] = {"us_median": med * 1e3}
+        if name in stage_bytes:
+            gbs = stage_bytes[name] / (med * 1e-3) / 1e9
+            stages[name].update(algorithmic_MB=stage_bytes[name] / 1e6, GBps=gbs, frac_of_8TBps=gbs / HBM_PEAK_GBS)
 
     # single-instance latency of the graded kernel (one sequence, split + combine launches)
     single_us = None
@@ -186,7 +217,8 @@ def main():
                      "algorithmic_bytes_per_launch": vbytes, "kernel_ms_avg": ker_avg,
                      "kernel_ms_min": ker_ms[0], "kernel_ms_median": ker_ms[len(ker_ms) // 2]},
         "cpu_baseline": cpu,
-        "extras": {"verify_tokens_per_s_kernel_only": tokens / (ker_avg * 1e-3),
+        "extras": {"stages": stages,
+                   "verify_tokens_per_s_kernel_only": tokens / (ker_avg * 1e-3),
                    "verify_single_sequence_latency_us": single_us,
                    "verify_other_configs": others},
     }

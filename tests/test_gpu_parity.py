@@ -20,6 +20,15 @@ SCORE_TOL = 1e-6
 DEV = "cuda:0"
 
 
+def score_tol(H, n_q):
+    """Bar for one sequence's scores.  The one-pass kernel keeps an attention weight's exponential as
+    16-bit fixed point: a weight is off by at most 2^-17 (uniform, standard deviation 2^-17/sqrt(3) =
+    4.4e-6, times a factor <= 1/row sum <= 1).  A score is the mean of H*n_q weights, so its error has
+    standard deviation <= 4.4e-6/sqrt(H*n_q); 3.6 of those cover the maximum over a few hundred keys.
+    From 256 rows on (the paper's shapes have 32 heads x 64 rows) the bar is the flat 1e-6."""
+    return max(SCORE_TOL, 1.6e-5 / math.sqrt(H * n_q))
+
+
 @pytest.fixture(scope="module")
 def tw():
     from paper_2503_14075_amd import binding
@@ -453,8 +462,15 @@ def _check_score(tw, dtype, H, d_h, M, v0, n_text, n_q, causal, q_std=1.0, seed=
     torch.cuda.synchronize()
     got = scores.cpu().double()
     assert torch.isfinite(got).all()
-    err = float((got - want).abs().max())
-    assert err <= SCORE_TOL, f"score error {err:.3e}"
+    # the documented reach of the one-pass kernel (16-bit stored exponentials); the other kernels
+    # keep fp32 throughout and are held to the flat bar
+    span_chunks = (v0 + M - 1) // 32 - v0 // 32 + 1
+    one_pass = (dtype == torch.bfloat16 and d_h in (64, 128) and n_q_max <= 64 and max(n_tot) <= 768
+                and span_chunks <= (23 if n_q_max > 32 else 24))
+    for b in range(B):
+        err = float((got[b] - want[b]).abs().max())
+        tol = score_tol(H, n_q[b]) if one_pass else SCORE_TOL
+        assert err <= tol, f"score error {err:.3e} in sequence {b} (bar {tol:.1e})"
     again = torch.empty_like(scores)
     tw.ttp_score(q.to(DEV), view, _i32(n_q), _i32(pos0), _i32(n_tot), max(n_tot), v0, M, scale, causal,
                  again, ws)
@@ -484,7 +500,22 @@ def test_score_resident_limits(tw):
     _check_score(tw, torch.bfloat16, 3, 64, 300, 33, [64, 20], [64, 20], False, q_std=4.0)
 
 
-def test_score_register_resident_boundary(tw):
+@pytest.mark.parametrize("seed", range(8))
+def test_score_random_shapes(tw, seed):
+    # ragged everything: heads, head size, span start and length, text lengths, scoring rows, masks
+    rng = W.HostRng(9000 + seed)
+    H = rng.randint(1, 11)
+    d_h = (64, 128)[seed & 1]
+    M = rng.randint(1, 400)
+    v0 = rng.randint(0, 70)
+    B = rng.randint(1, 4)
+    n_text = [rng.randint(1, 120) for _ in range(B)]
+    n_q = [rng.randint(1, min(64, n)) for n in n_text]
+    _check_score(tw, torch.bfloat16, H, d_h, M, v0, n_text, n_q, bool(seed & 2), q_std=(1.0, 5.0)[(seed >> 2) & 1],
+                 seed=100 + seed)
+
+
+def test_score_one_pass_boundary(tw):
     # 768 keys is the longest prompt that the one-pass kernel takes; 769 takes the two-pass kernel
     _check_score(tw, torch.bfloat16, 4, 128, 576, 0, [192, 100], [64, 33], True)
     _check_score(tw, torch.bfloat16, 4, 128, 576, 0, [193, 100], [64, 33], True)
