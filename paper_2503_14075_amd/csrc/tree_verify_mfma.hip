@@ -95,32 +95,36 @@ __device__ __forceinline__ void process_chunk(WaveState<DH>& w, const unsigned c
         const bf16x8 kf = as_bf16x8(*(const u32x4*)(ldsK + li * Cf::kKStride + 32 * c + 16 * g));
         s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, w.qf[c], s, 0, 0, 0);
     }
-    const bool need_mask = base + kChunk > C;
-    bf16x8 pf[2];
-    float x[16], mx = -INFINITY;
+    if (base + kChunk > C) {   // only chunks that touch tree rows test the ancestor masks
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        x[r] = s[r] * sl2;
-        if (need_mask) {
+        for (int r = 0; r < 16; ++r) {
             const int row = base + acc_row(r, g);
             const bool vis = row < C || (row < n_rows && ((w.anc >> (row - C)) & 1ull));
-            x[r] = vis ? x[r] : -INFINITY;
+            s[r] = vis ? s[r] : -INFINITY;
         }
-        mx = fmaxf(mx, x[r]);
     }
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    // scale > 0: the maximum of the scaled logits is the scaled maximum of the raw ones
+    float mx = s[0];
+#pragma unroll
+    for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[r]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * sl2;
     const float m_new = fmaxf(w.run_m, mx);
     const float m_safe = m_new == -INFINITY ? 0.f : m_new;
     const float alpha = fast_exp2(w.run_m - m_safe);   // 0 on the first visible chunk, 1 when the maximum holds
     float psum = 0.f;
+    uint32_t pw[8];
+    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        // the row sum is taken over the bf16-rounded weights that enter the PV
-        // product, so the normalised weights still sum to one
-        const __bf16 pb = (__bf16)fast_exp2(x[r] - m_safe);
-        psum += (float)pb;
-        pf[r >> 3][r & 7] = pb;
+    for (int r = 0; r < 16; r += 2) {
+        // the row sum is taken over the bf16-rounded weights that enter the PV product (a two-term
+        // dot product with ones adds a rounded pair), so the normalised weights still sum to one
+        const bf16x2 p2 = {(__bf16)fast_exp2(__builtin_fmaf(s[r], sl2, -m_safe)),
+                           (__bf16)fast_exp2(__builtin_fmaf(s[r + 1], sl2, -m_safe))};
+        psum = __builtin_amdgcn_fdot2_f32_bf16(p2, ones, psum, false);
+        pw[r >> 1] = __builtin_bit_cast(uint32_t, p2);
     }
+    const bf16x8 pf[2] = {as_bf16x8((u32x4){pw[0], pw[1], pw[2], pw[3]}),
+                          as_bf16x8((u32x4){pw[4], pw[5], pw[6], pw[7]})};
     w.run_l = w.run_l * alpha + psum;
     w.run_m = m_new;
     if (__any(alpha != 1.f)) {
@@ -277,14 +281,71 @@ __device__ __forceinline__ void tree_masks(const VerifyArgs& a, int b, int T, in
     __syncthreads();
 }
 
-// Pool row of cache row r (paged or contiguous), clamped into the pool.
+// Addresses of the K/V rows of one (sequence, head).  A load takes cache row base + r of a chunk,
+// 16-byte column `col` of the head's segment; rows past `last_row` read that row again.
+//   contiguous: everything up to the chunk is scalar (sequence start and chunk start, both kept
+//               inside the pool); a lane adds a 32-bit offset of at most 32 rows.
+//   paged:      the pool row comes from the page table, per lane, in 64 bits.
+struct ChunkAddr {
+    const unsigned char* base;   // contiguous: first row of the chunk; paged: row 0 of the pool
+    int lim;                     // contiguous: last_row - chunk start (>= 0)
+};
 template <bool PAGED>
-__device__ __forceinline__ uint32_t pool_row_of(const VerifyArgs& a, int r, int page, int64_t row0) {
-    int64_t prow = PAGED ? (int64_t)page * a.k.page_rows + (r % a.k.page_rows) : row0 + r;
-    const int64_t last = a.k.pool_rows - 1;
-    prow = prow < 0 ? 0 : (prow > last ? last : prow);
-    return (uint32_t)prow;
-}
+struct SeqAddr {
+    const unsigned char *k_seq, *v_seq;   // head segment of the sequence's first row (paged: of pool row 0)
+    const int32_t* ptab;
+    uint32_t stride;
+    int last_row;                          // contiguous: also kept inside the pool
+    __device__ __forceinline__ SeqAddr(const VerifyArgs& a, int b, int hc, int row_bytes, uint32_t pool_stride,
+                                       int last) {
+        stride = pool_stride;
+        const int64_t last_pool = a.k.pool_rows - 1;
+        int64_t row0 = 0;
+        if (PAGED) {
+            ptab = a.k.page_table + (int64_t)b * a.k.max_pages;
+            last_row = last;
+        } else {
+            ptab = nullptr;
+            row0 = (int64_t)a.k.row_off[b];
+            row0 = row0 < 0 ? 0 : (row0 > last_pool ? last_pool : row0);
+            const int64_t room = last_pool - row0;
+            last_row = last < room ? last : (int)room;
+        }
+        k_seq = (const unsigned char*)a.k.base + (uint64_t)row0 * pool_stride + (int64_t)hc * row_bytes;
+        v_seq = (const unsigned char*)a.v.base + (uint64_t)row0 * pool_stride + (int64_t)hc * row_bytes;
+    }
+    __device__ __forceinline__ int page(const VerifyArgs& a, int r) const {
+        r = r < last_row ? r : last_row;
+        int pi = r / a.k.page_rows;
+        pi = pi < a.k.max_pages ? pi : a.k.max_pages - 1;
+        return ptab[pi];
+    }
+    __device__ __forceinline__ ChunkAddr chunk(const unsigned char* seq, int base) const {
+        ChunkAddr c;
+        if (PAGED) {
+            c.base = seq;
+            c.lim = 0;
+        } else {
+            const int cb = base < last_row ? base : last_row;
+            c.base = seq + (uint64_t)(uint32_t)cb * stride;
+            c.lim = last_row - cb;
+        }
+        return c;
+    }
+    __device__ __forceinline__ const u32x4* at(const VerifyArgs& a, const ChunkAddr& c, int base, int r, int col,
+                                               int page) const {
+        if (PAGED) {
+            int row = base + r;
+            row = row < last_row ? row : last_row;
+            int64_t prow = (int64_t)page * a.k.page_rows + (row % a.k.page_rows);
+            const int64_t last_pool = a.k.pool_rows - 1;
+            prow = prow < 0 ? 0 : (prow > last_pool ? last_pool : prow);
+            return (const u32x4*)(c.base + (uint64_t)(uint32_t)prow * stride + 16 * col);
+        }
+        const int rr = r < c.lim ? r : c.lim;
+        return (const u32x4*)(c.base + ((uint32_t)rr * stride + 16u * (uint32_t)col));
+    }
+};
 
 // ---------------------------------------------------------------------------------------------
 // T <= 32: every wavefront stages its own chunks (K and V) in a private LDS area; no workgroup
@@ -298,7 +359,10 @@ __global__ __launch_bounds__(kMfThreads, 2) void verify_mfma_kernel(VerifyArgs a
     __shared__ int s_parent[TW_MAX_TREE];
     __shared__ unsigned long long s_anc[TW_MAX_TREE];
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    // the wavefront index in a scalar register: head, phase and chunk base are then scalars, branches
+    // on them real branches, and the addresses below a scalar base plus a 32-bit lane offset
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int g = lane >> 5, li = lane & 31;
     const int b = blockIdx.y, split = blockIdx.z;
     const int n_phase = a.n_phase;               // 1 (four heads per workgroup) or 4 (one head)
@@ -316,37 +380,27 @@ __global__ __launch_bounds__(kMfThreads, 2) void verify_mfma_kernel(VerifyArgs a
     // lane's share of a chunk load: row (lane / lanes_per_row) + rows_per_load * j,
     // 16-byte column lane % lanes_per_row of the head's segment
     const int ld_row = lane / Cf::kLanesPerRow, ld_col = lane % Cf::kLanesPerRow;
-    const unsigned char* kbase = (const unsigned char*)a.k.base + (int64_t)hc * Cf::kRowB + ld_col * 16;
-    const unsigned char* vbase = (const unsigned char*)a.v.base + (int64_t)hc * Cf::kRowB + ld_col * 16;
     const uint32_t pool_stride = (uint32_t)(a.H * Cf::kRowB);
-    const int32_t* ptab = PAGED ? a.k.page_table + (int64_t)b * a.k.max_pages : nullptr;
-    const int64_t row0 = PAGED ? 0 : (int64_t)a.k.row_off[b];
     // loads past the split re-read its last row (cached) and are masked
     const int last_row = sq.r_end > sq.r_begin ? sq.r_end - 1 : sq.r_begin;
     const int step = kChunk * n_phase;
+    const SeqAddr<PAGED> ad(a, b, hc, Cf::kRowB, pool_stride, last_row);
 
     // Paged caches: the page of every row this lane loads, looked up two chunks ahead
     // so the dependent data loads never wait on a table read.
     int pg[Cf::kLoads];
     auto lookup_pages = [&](int base) {
 #pragma unroll
-        for (int j = 0; j < Cf::kLoads; ++j) {
-            int r = base + ld_row + Cf::kRowsPerLoad * j;
-            r = r < last_row ? r : last_row;
-            int pi = r / a.k.page_rows;
-            pi = pi < a.k.max_pages ? pi : a.k.max_pages - 1;
-            pg[j] = ptab[pi];
-        }
+        for (int j = 0; j < Cf::kLoads; ++j) pg[j] = ad.page(a, base + ld_row + Cf::kRowsPerLoad * j);
     };
     u32x4 pk[Cf::kLoads], pv[Cf::kLoads];
     auto issue_loads = [&](int base) {
+        const ChunkAddr ck = ad.chunk(ad.k_seq, base), cv = ad.chunk(ad.v_seq, base);
 #pragma unroll
         for (int j = 0; j < Cf::kLoads; ++j) {
-            int r = base + ld_row + Cf::kRowsPerLoad * j;
-            r = r < last_row ? r : last_row;
-            const uint64_t off = (uint64_t)pool_row_of<PAGED>(a, r, PAGED ? pg[j] : 0, row0) * pool_stride;
-            pk[j] = __builtin_nontemporal_load((const u32x4*)(kbase + off));   // streamed once
-            pv[j] = __builtin_nontemporal_load((const u32x4*)(vbase + off));
+            const int r = ld_row + Cf::kRowsPerLoad * j;
+            pk[j] = __builtin_nontemporal_load(ad.at(a, ck, base, r, ld_col, PAGED ? pg[j] : 0));   // streamed once
+            pv[j] = __builtin_nontemporal_load(ad.at(a, cv, base, r, ld_col, PAGED ? pg[j] : 0));
         }
     };
 
@@ -395,7 +449,8 @@ __global__ __launch_bounds__(kMfThreads, 2) void verify_mfma_pair_kernel(VerifyA
     __shared__ int s_parent[TW_MAX_TREE];
     __shared__ unsigned long long s_anc[TW_MAX_TREE];
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // scalar, as in the kernel above
     const int g = lane >> 5, li = lane & 31;
     const int b = blockIdx.y, split = blockIdx.z;
     const int blk = wave & 1, pair = wave >> 1;
@@ -411,31 +466,23 @@ __global__ __launch_bounds__(kMfThreads, 2) void verify_mfma_pair_kernel(VerifyA
     const float sl2 = a.scale * kLog2e;
 
     const int ld_row = lane / Cf::kLanesPerRow, ld_col = lane % Cf::kLanesPerRow;
-    // the even wavefront of a pair streams K, the odd one V
-    const unsigned char* src = (const unsigned char*)(blk == 0 ? a.k.base : a.v.base) + (int64_t)hc * Cf::kRowB +
-                               ld_col * 16;
     const int dst_off = blk == 0 ? 0 : kChunk * Cf::kKStride;
     const int dst_stride = blk == 0 ? Cf::kKStride : Cf::kVStride;
     const uint32_t pool_stride = (uint32_t)(a.H * Cf::kRowB);
-    const int32_t* ptab = PAGED ? a.k.page_table + (int64_t)b * a.k.max_pages : nullptr;
-    const int64_t row0 = PAGED ? 0 : (int64_t)a.k.row_off[b];
     const int last_row = sq.r_end > sq.r_begin ? sq.r_end - 1 : sq.r_begin;
     const int step = kChunk * n_phase;
+    const SeqAddr<PAGED> ad(a, b, hc, Cf::kRowB, pool_stride, last_row);
+    // the even wavefront of a pair streams K, the odd one V
+    const unsigned char* seq_base = blk == 0 ? ad.k_seq : ad.v_seq;
 
     u32x4 pld[2][Cf::kLoads];
     auto issue_loads = [&](int base, int slot) {
+        const ChunkAddr cc = ad.chunk(seq_base, base);
 #pragma unroll
         for (int j = 0; j < Cf::kLoads; ++j) {
-            int r = base + ld_row + Cf::kRowsPerLoad * j;
-            r = r < last_row ? r : last_row;
-            int page = 0;
-            if (PAGED) {
-                int pi = r / a.k.page_rows;
-                pi = pi < a.k.max_pages ? pi : a.k.max_pages - 1;
-                page = ptab[pi];
-            }
-            const uint64_t off = (uint64_t)pool_row_of<PAGED>(a, r, page, row0) * pool_stride;
-            pld[slot][j] = __builtin_nontemporal_load((const u32x4*)(src + off));   // streamed once
+            const int r = ld_row + Cf::kRowsPerLoad * j;
+            const int page = PAGED ? ad.page(a, base + r) : 0;
+            pld[slot][j] = __builtin_nontemporal_load(ad.at(a, cc, base, r, ld_col, page));   // streamed once
         }
     };
     auto stage_chunk = [&](int slot, unsigned char* buf) {
@@ -492,7 +539,7 @@ bool verify_mfma_supported(const VerifyArgs& a, int dtype) {
     return dtype == TW_BF16 && (a.d_h == 64 || a.d_h == 128) && a.k.page_table == a.v.page_table &&
            a.k.row_off == a.v.row_off && a.k.page_rows == a.v.page_rows &&
            a.k.max_pages == a.v.max_pages && a.k.pool_rows == a.v.pool_rows &&
-           a.k.pool_rows <= 0x7FFFFFFFll;
+           a.k.pool_rows <= 0x7FFFFFFFll && a.scale > 0.f;
 }
 
 hipError_t launch_verify_mfma(const VerifyArgs& a, hipStream_t s) {
