@@ -162,33 +162,56 @@ __device__ __forceinline__ void process_chunk(WaveState<DH>& w, const unsigned c
 }
 
 // One unit per wavefront (n_phase == 1): normalise, or hand the partial to the combine kernel.
+// The accumulators hold, per lane, 16 scattered 16-byte pieces of one node's output row; stored
+// from there every store instruction would touch 64 different 128-byte lines (measured: 25 us for
+// the 55 MB of the bench launch).  The tile goes through `tile` (32 x kOStride floats of LDS that
+// this wavefront owns and no longer reads) so that a store instruction writes whole rows.
 template <int DH>
-__device__ __forceinline__ void epilogue_direct(const WaveState<DH>& w, const VerifyArgs& a, int b, int h,
-                                                int t, int split, int g) {
+__device__ __forceinline__ void epilogue_direct(const WaveState<DH>& w, const VerifyArgs& a, float* tile, int b,
+                                                int h, int T, int split, int lane, int node0 = 0) {
+    // T = nodes of this wavefront's block (may be <= 0), node0 = tree index of its first node
+    static_assert(32 * MfCfg<DH>::kOStride * 4 <= MfCfg<DH>::kStage, "the tile fits one K+V stage");
     using Cf = MfCfg<DH>;
+    const int g = lane >> 5, li = lane & 31;
     const float l = w.run_l + __shfl_xor(w.run_l, 32, 64);
-    float* dst;
-    float mul;
-    if (a.n_splits == 1) {
-        dst = a.out + (((int64_t)b * a.T_max + t) * a.H + h) * DH;
-        mul = 1.f / l;
-    } else {
-        const int64_t slot = (((int64_t)split * a.B + b) * a.H + h) * a.T_max + t;
-        dst = a.part_o + slot * DH;
-        mul = 1.f;
-        if (g == 0) {
-            a.part_ml[slot * 2] = w.run_m * kLn2;   // natural-log units for the combine
-            a.part_ml[slot * 2 + 1] = l;
-        }
-    }
+    const float mul = a.n_splits == 1 ? 1.f / l : 1.f;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");   // earlier reads of this LDS area are done
+    __builtin_amdgcn_wave_barrier();
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
-        float* p = dst + Cf::kNQ * acc_row(r, g);
+        float* p = tile + li * Cf::kOStride + Cf::kNQ * acc_row(r, g);
         if (Cf::kNQ == 4)
             *(float4*)p = make_float4(w.o[0][r] * mul, w.o[1][r] * mul, w.o[Cf::kNQ - 2][r] * mul,
                                       w.o[Cf::kNQ - 1][r] * mul);
         else
             *(float2*)p = make_float2(w.o[0][r] * mul, w.o[1][r] * mul);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    // lanes_per_row consecutive lanes store one node's row as consecutive 16-byte pieces
+    constexpr int kLanesPerRow = DH / 4, kRowsPerStore = 64 / kLanesPerRow;
+    const int sub = lane / kLanesPerRow, c4 = lane % kLanesPerRow;
+    float* dst;
+    int64_t node_stride;
+    if (a.n_splits == 1) {
+        dst = a.out + (((int64_t)b * a.T_max + node0) * a.H + h) * DH;
+        node_stride = (int64_t)a.H * DH;
+    } else {
+        const int64_t slot = (((int64_t)split * a.B + b) * a.H + h) * a.T_max + node0;
+        dst = a.part_o + slot * DH;
+        node_stride = DH;
+        if (g == 0 && li < T) {
+            a.part_ml[(slot + li) * 2] = w.run_m * kLn2;   // natural-log units for the combine
+            a.part_ml[(slot + li) * 2 + 1] = l;
+        }
+    }
+#pragma unroll
+    for (int n0 = 0; n0 < 32; n0 += kRowsPerStore) {
+        const int node = n0 + sub;
+        if (node < T)   // written once, not read again by this kernel: streaming stores
+            __builtin_nontemporal_store(*(const f32x4*)(tile + node * Cf::kOStride + 4 * c4),
+                                        (f32x4*)(dst + node * node_stride + 4 * c4));
     }
 }
 
@@ -448,7 +471,7 @@ __global__ __launch_bounds__(kMfThreads, 2) void verify_mfma_kernel(VerifyArgs a
         process_chunk<DH>(w, ldsK, ldsV, base, sq.C, sq.n_rows, sl2, g, li);
     }
     if (n_phase == 1) {
-        if (active && t < sq.T) epilogue_direct<DH>(w, a, b, h, t, split, g);
+        if (active) epilogue_direct<DH>(w, a, (float*)ldsK, b, h, sq.T, split, lane);
     } else {
         epilogue_merge<DH>(w, a, lds, b, h, sq.T, split, phase, 1, n_phase, g, li, tid);
     }
@@ -534,7 +557,9 @@ __global__ __launch_bounds__(kMfThreads, 2) void verify_mfma_pair_kernel(VerifyA
         }
     }
     if (n_phase == 1) {
-        if (active && t < sq.T) epilogue_direct<DH>(w, a, b, h, t, split, g);
+        __syncthreads();   // the partner is done with the shared stage; each wavefront takes one buffer of it
+        if (active)
+            epilogue_direct<DH>(w, a, (float*)(stage + blk * Cf::kStage), b, h, sq.T - 32 * blk, split, lane, 32 * blk);
     } else {
         epilogue_merge<DH>(w, a, lds, b, h, sq.T, split, blk * n_phase + phase, 2, n_phase, g, li, tid);
     }
