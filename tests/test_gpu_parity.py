@@ -186,6 +186,17 @@ def test_verify_paged_pool(tw):
                  page_table=w.page_table, page_rows=pr)
 
 
+def test_verify_and_score_with_negative_scale(tw):
+    # the matrix-core kernels take the maximum before scaling and need scale > 0; other scales go to
+    # the fp32 kernels and give the same softmax(scale * q.k)
+    H, d_h, T = 4, 128, 20
+    ctx = [97, 16]
+    trees = [W.random_parent_tree(W.HostRng(35, b), T, 4) for b in range(2)]
+    q, k, v, off = make_case(36, 2, H, d_h, ctx, T, torch.bfloat16, trees, kv_std=1.0, q_std=1.0)
+    check_verify(tw, q, k, v, ctx, [T] * 2, trees, -1 / math.sqrt(d_h), row_off=off)
+    _check_score(tw, torch.bfloat16, 4, 128, 100, 5, [20, 9], [20, 9], True, scale=-1 / math.sqrt(128))
+
+
 def test_verify_is_deterministic(tw):
     H, d_h, T = 32, 128, 26
     trees = [W.fanout_tree(W.HostRng(1, 1), T, (4, 3, 2, 1, 1))]
@@ -439,7 +450,7 @@ def test_compact_batched_ragged_pools(tw):
 # ----------------------------------------------------------------------------
 # ttp_score
 # ----------------------------------------------------------------------------
-def _check_score(tw, dtype, H, d_h, M, v0, n_text, n_q, causal, q_std=1.0, seed=1):
+def _check_score(tw, dtype, H, d_h, M, v0, n_text, n_q, causal, q_std=1.0, seed=1, scale=None):
     B = len(n_text)
     n_tot = [v0 + M + n for n in n_text]
     off, acc = [], 2
@@ -450,7 +461,7 @@ def _check_score(tw, dtype, H, d_h, M, v0, n_text, n_q, causal, q_std=1.0, seed=
     q = W.normal(seed, 1, (B, n_q_max, H, d_h), q_std, dtype)
     k = W.normal(seed, 2, (acc, H, d_h), 1.0, dtype)
     pos0 = [nt - nq for nt, nq in zip(n_tot, n_q)]
-    scale = 1 / math.sqrt(d_h)
+    scale = 1 / math.sqrt(d_h) if scale is None else scale
     want = oracle.ttp_score(q, k, n_q, pos0, n_tot, off, v0, M, scale, causal)
     kd, ro = k.to(DEV), _i32(off)          # the view only holds pointers: keep the tensors alive
     view = tw.kv_view(kd, row_off=ro)
@@ -466,7 +477,7 @@ def _check_score(tw, dtype, H, d_h, M, v0, n_text, n_q, causal, q_std=1.0, seed=
     # keep fp32 throughout and are held to the flat bar
     span_chunks = (v0 + M - 1) // 32 - v0 // 32 + 1
     one_pass = (dtype == torch.bfloat16 and d_h in (64, 128) and n_q_max <= 64 and max(n_tot) <= 768
-                and span_chunks <= (23 if n_q_max > 32 else 24))
+                and span_chunks <= (23 if n_q_max > 32 else 24) and scale > 0)
     for b in range(B):
         err = float((got[b] - want[b]).abs().max())
         tol = score_tol(H, n_q[b]) if one_pass else SCORE_TOL
