@@ -206,35 +206,40 @@ __global__ __launch_bounds__(kRsThreads, 2) void score_resident_kernel(ScoreArgs
 #pragma unroll
         for (int c = 0; c < kRsCpw; ++c) {
             const int chunk = wave + kRsWaves * c, base = kRsChunk * chunk, slot = c & 1;
-            // Staging and the refill of the slot run for every chunk, also one past the end of the
-            // sequence (its loads point at the last key).  The 16-row stage takes the chunk in two
-            // halves; lane (j, g) of the half that holds key j reads its operand fragments
-            // K[key base+j][16dc + 8g .. +7].
+            // The refill of the slot runs for every chunk, also one past the end of the sequence (its
+            // loads point at the last key; its staging and arithmetic are skipped): no load sits inside
+            // a branch.  The 16-row stage takes the chunk in two halves; lane (j, g) of the half that
+            // holds key j reads its operand fragments K[key base+j][16dc + 8g .. +7].
+            const bool live = base < n_tot;
             u32x4 kf[Cf::kDC];
 #pragma unroll
             for (int half = 0; half < 2; ++half) {
+                if (live) {
 #pragma unroll
-                for (int jj = 0; jj < Cf::kHalf; ++jj)
-                    *(u32x4*)(stage + (ld_row + Cf::kRowsPerLoad * jj) * Cf::kStride + ld_col * 16) =
-                        pk[slot][half * Cf::kHalf + jj];
+                    for (int jj = 0; jj < Cf::kHalf; ++jj)
+                        *(u32x4*)(stage + (ld_row + Cf::kRowsPerLoad * jj) * Cf::kStride + ld_col * 16) =
+                            pk[slot][half * Cf::kHalf + jj];
+                }
                 if (half == 1) {
                     // the slot's registers are free again: chunk 2 of this pair after chunk 0, then
                     // chunks 1 and 0 of the next pair
                     if (c == 0) issue_chunk(cur, 2, 0, true);
                     else issue_chunk(nxt, c == 1 ? 1 : 0, slot, has_next);
                 }
-                lds_sync();
-                if ((li >> 4) == half) {
+                if (live) {
+                    lds_sync();
+                    if ((li >> 4) == half) {
 #pragma unroll
-                    for (int dc = 0; dc < Cf::kDC; ++dc)
-                        kf[dc] = *(const u32x4*)(stage + (li & 15) * Cf::kStride + 32 * dc + 16 * g);
+                        for (int dc = 0; dc < Cf::kDC; ++dc)
+                            kf[dc] = *(const u32x4*)(stage + (li & 15) * Cf::kStride + 32 * dc + 16 * g);
+                    }
+                    lds_sync();   // fragment reads done before the stage is written again
                 }
-                lds_sync();   // fragment reads done before the stage is written again
             }
             const bool in_span = base < span_end && base + kRsChunk > a.v_start;
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb) ref[c][nb] = 0.f;
-            if (base < n_tot) {
+            if (live) {
 #pragma unroll
                 for (int nb = 0; nb < NB; ++nb) {
                     // one 32-row block at a time keeps a single accumulator tile live
