@@ -132,27 +132,40 @@ __global__ __launch_bounds__(kGenThreads) void verify_generic_kernel(VerifyArgs 
     }
 }
 
-// Merge the per-split partial results in split order.  grid (T_max, H, B), d_h lanes.
-__global__ void verify_combine_kernel(VerifyArgs a) {
-    const int t = blockIdx.x, h = blockIdx.y, b = blockIdx.z, c = threadIdx.x;
+// Merge the per-split partial results in split order.  d_h/4 lanes per (sequence, node, head) row,
+// four output columns each; a workgroup takes as many consecutive rows as fit 256 threads, so its
+// stores cover a contiguous piece of `out`.
+constexpr int kCombineThreads = 256;
+__global__ __launch_bounds__(kCombineThreads) void verify_combine_kernel(VerifyArgs a) {
+    const int lanes = a.d_h / 4, rows_per_wg = kCombineThreads / lanes;
+    const int sub = threadIdx.x / lanes, c4 = threadIdx.x % lanes;
+    const int64_t row = (int64_t)blockIdx.x * rows_per_wg + sub;   // (b * T_max + t) * H + h
+    if (sub >= rows_per_wg || row >= (int64_t)a.B * a.T_max * a.H) return;
+    const int h = (int)(row % a.H), t = (int)((row / a.H) % a.T_max), b = (int)(row / ((int64_t)a.H * a.T_max));
     int T = a.n_nodes[b];
     T = T < 1 ? 1 : (T > a.T_max ? a.T_max : T);
-    if (t >= T || c >= a.d_h) return;
+    if (t >= T) return;
     float m = -INFINITY;
     for (int s = 0; s < a.n_splits; ++s) {
         const int64_t slot = (((int64_t)s * a.B + b) * a.H + h) * a.T_max + t;
         m = fmaxf(m, a.part_ml[slot * 2]);
     }
-    float l = 0.f, acc = 0.f;
+    float l = 0.f;
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
     for (int s = 0; s < a.n_splits; ++s) {
         const int64_t slot = (((int64_t)s * a.B + b) * a.H + h) * a.T_max + t;
         const float ms = a.part_ml[slot * 2];
         if (ms == -INFINITY) continue;   // a split in which this node saw no key
         const float w = expf(ms - m);
         l += a.part_ml[slot * 2 + 1] * w;
-        acc += a.part_o[slot * a.d_h + c] * w;
+        const float4 v = *(const float4*)(a.part_o + slot * a.d_h + 4 * c4);
+        acc.x += v.x * w;
+        acc.y += v.y * w;
+        acc.z += v.z * w;
+        acc.w += v.w * w;
     }
-    a.out[(((int64_t)b * a.T_max + t) * a.H + h) * a.d_h + c] = acc / l;
+    const float inv = 1.f / l;
+    *(float4*)(a.out + row * a.d_h + 4 * c4) = make_float4(acc.x * inv, acc.y * inv, acc.z * inv, acc.w * inv);
 }
 
 hipError_t launch_verify_generic(const VerifyArgs& a, int dtype, hipStream_t s) {
@@ -167,7 +180,10 @@ hipError_t launch_verify_generic(const VerifyArgs& a, int dtype, hipStream_t s) 
 }
 
 hipError_t launch_verify_combine(const VerifyArgs& a, hipStream_t s) {
-    hipLaunchKernelGGL(verify_combine_kernel, dim3(a.T_max, a.H, a.B), dim3(a.d_h), 0, s, a);
+    const int rows_per_wg = kCombineThreads / (a.d_h / 4);
+    const int64_t rows = (int64_t)a.B * a.T_max * a.H;
+    hipLaunchKernelGGL(verify_combine_kernel, dim3((unsigned)((rows + rows_per_wg - 1) / rows_per_wg)),
+                       dim3(kCombineThreads), 0, s, a);
     return hipGetLastError();
 }
 
