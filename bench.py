@@ -45,6 +45,8 @@ def main():
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the CPU oracle leg (0 = skip)")
     ap.add_argument("--other-configs", type=int, default=1,
                     help="also time tree_verify_attn on cfg2 (three prefix lengths), cfg3 and cfg4 (0 = skip)")
+    ap.add_argument("--graph-iters", type=int, default=50,
+                    help="replays of the HIP-graph leg (0 = skip)")
     ap.add_argument("--single-iters", type=int, default=200,
                     help="launches of the single-sequence latency leg (0 = skip)")
     args = ap.parse_args()
@@ -116,6 +118,28 @@ def main():
         if name in stage_bytes:
             gbs = stage_bytes[name] / (med * 1e-3) / 1e9
             stages[name].update(algorithmic_MB=stage_bytes[name] / 1e6, GBps=gbs, frac_of_8TBps=gbs / HBM_PEAK_GBS)
+
+    # the same step replayed from a HIP graph (the library only enqueues kernels, so a step can be
+    # captured once); reported beside the eager figure, which stays the headline
+    graph_ms = None
+    if args.graph_iters > 0:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            dw.step()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            dw.step()
+        for _ in range(3):
+            graph.replay()
+        torch.cuda.synchronize()
+        tg = time.perf_counter()
+        for _ in range(args.graph_iters):
+            graph.replay()
+        torch.cuda.synchronize()
+        graph_ms = (time.perf_counter() - tg) * 1e3 / args.graph_iters
 
     # single-instance latency of the graded kernel (one sequence, split + combine launches)
     single_us = None
@@ -217,7 +241,7 @@ def main():
                      "algorithmic_bytes_per_launch": vbytes, "kernel_ms_avg": ker_avg,
                      "kernel_ms_min": ker_ms[0], "kernel_ms_median": ker_ms[len(ker_ms) // 2]},
         "cpu_baseline": cpu,
-        "extras": {"stages": stages,
+        "extras": {"stages": stages, "ms_per_step_hip_graph": graph_ms,
                    "verify_tokens_per_s_kernel_only": tokens / (ker_avg * 1e-3),
                    "verify_single_sequence_latency_us": single_us,
                    "verify_other_configs": others},

@@ -735,3 +735,39 @@ def test_bench_launch_configuration_sampled(runner):
                                          w.v_pool[r0:r0 + nr].cpu(), [w.ctx_len[b]], [cfg.T], [w.parent[b]],
                                          cfg.scale, row_off=[0])[0]
         assert float((out[b].double() - want_o).abs().max()) <= ATTN_TOL
+
+
+def test_step_replays_from_a_hip_graph(runner):
+    # the library only enqueues kernels on the caller's stream (no allocation, no synchronisation, no
+    # memset nodes), so a whole step can be captured once and replayed; every replay must reproduce
+    # the eager results bit for bit, with other work on the device between the replays
+    cfg = W.replicate(W.CONFIGS["cfg1"], 4)
+    w = W.make_workload(cfg)
+    dw = runner.DeviceWorkload(w, DEV)
+    outs = lambda: [dw.scores, dw.kept, dw.out, dw.n_acc, dw.path, dw.bonus] + list(dw.compact_dst)
+    dw.step()
+    torch.cuda.synchronize()
+    ref = [t.clone() for t in outs()]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        dw.step()                                   # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        dw.step()
+    scratch = torch.zeros(1 << 20, device=DEV)
+    for i in range(3):
+        for t in outs():
+            t.fill_(-1 if t.dtype in (torch.int32, torch.int64) else float("nan"))
+        scratch.add_(1.0).mul_(0.5)                 # unrelated eager work between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for got, want in zip(outs(), ref):
+            if got.dtype.is_floating_point:
+                assert torch.equal(got.view(torch.int16 if got.element_size() == 2 else torch.int32),
+                                   want.view(torch.int16 if want.element_size() == 2 else torch.int32)), f"replay {i}"
+            else:
+                assert torch.equal(got, want), f"replay {i}"
