@@ -186,6 +186,27 @@ def test_verify_paged_pool(tw):
                  page_table=w.page_table, page_rows=pr)
 
 
+@pytest.mark.parametrize("seed", range(8))
+def test_verify_random_shapes(tw, seed):
+    # ragged everything, contiguous and paged pools, both head sizes, trees up to 64 nodes
+    rng = W.HostRng(7000 + seed)
+    B, H = rng.randint(1, 9), rng.randint(1, 12)
+    d_h = (64, 128)[seed & 1]
+    T_max = rng.randint(1, 64)
+    if seed & 2:
+        cfg = W.Config(**{**W.CONFIGS["cfg3"].__dict__, "name": f"rand{seed}", "seed": 70 + seed, "B": B, "H": H,
+                          "d_h": d_h, "hidden": H * d_h, "T": T_max, "P": (0, 700), "tree": ("random", 6)})
+        w = W.make_workload(cfg, with_compact=False, with_score=False)
+        check_verify(tw, w.q_tree, w.k_pool, w.v_pool, w.ctx_len, w.n_nodes, w.parent, cfg.scale,
+                     page_table=w.page_table, page_rows=cfg.page_rows)
+    else:
+        ctx = [rng.randint(0, 600) for _ in range(B)]
+        n_nodes = [rng.randint(1, T_max) for _ in range(B)]
+        trees = [W.random_parent_tree(W.HostRng(seed, b), n, 6) for b, n in enumerate(n_nodes)]
+        q, k, v, off = make_case(300 + seed, B, H, d_h, ctx, T_max, torch.bfloat16, trees)
+        check_verify(tw, q, k, v, ctx, n_nodes, padded(trees, T_max), 1 / math.sqrt(d_h), row_off=off)
+
+
 def test_verify_and_score_with_negative_scale(tw):
     # the matrix-core kernels take the maximum before scaling and need scale > 0; other scales go to
     # the fp32 kernels and give the same softmax(scale * q.k)
