@@ -170,11 +170,7 @@ __global__ __launch_bounds__(kRsThreads, 2) void score_resident_kernel(ScoreArgs
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     };
 
-    // Consecutive workgroups go to the eight XCDs round-robin.  Renumbered, the workgroups of one XCD
-    // take consecutive (sequence, head) pairs -- all heads of a sequence when there are 8*H
-    // workgroups -- so an XCD reads complete K rows instead of an eighth of every row.
-    int pair = blockIdx.x;
-    if ((gridDim.x & 7) == 0) pair = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
+    int pair = blockIdx.x;   // (numbering the pairs so that an XCD takes whole sequences changes nothing here)
     if (pair >= n_pairs) return;
     PairInfo cur = pair_info(pair);
     issue_chunk(cur, 0, 0, true);
