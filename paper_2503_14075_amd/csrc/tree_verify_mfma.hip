@@ -307,8 +307,8 @@ __device__ __forceinline__ void tree_masks(const VerifyArgs& a, int b, int T, in
 // (head group, sequence) of a workgroup.  The hardware hands consecutive workgroups to the eight
 // XCDs (each with its own L2) round-robin; taken in grid order, XCD x would get head group x of
 // every sequence, i.e. one eighth of every cache row.  Renumbered, an XCD gets whole sequences: its
-// workgroups read complete 8 KB rows at about the same time (2 % faster on the bench launch; the
-// opposite order, sequences fastest, is 4 % slower).  Grids that are not a multiple of 8 keep grid order.
+// workgroups read complete 8 KB rows at about the same time (1.5 % faster on the bench launch, A/B on
+// one machine; the opposite order, sequences fastest, is 4 % slower).  Grids that are not a multiple of 8 keep grid order.
 __device__ __forceinline__ void unit_of_block(int& hg, int& b) {
     const int total = gridDim.x * gridDim.y, id = blockIdx.x + gridDim.x * blockIdx.y;
     hg = blockIdx.x;
