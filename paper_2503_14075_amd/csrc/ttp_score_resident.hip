@@ -151,7 +151,7 @@ __global__ __launch_bounds__(kRsThreads, 2) void score_resident_kernel(ScoreArgs
             const int i = piece / Cf::kPieces, col = piece % Cf::kPieces;
             const int ic = i < p.n_q ? i : p.n_q - 1;
             const uint16_t* sbase = qb + ((int64_t)p.b * a.n_q_max * a.H + p.h) * DH;   // scalar part
-            qn[u] = *(const u32x4*)(sbase + (uint32_t)(ic * a.H * DH + 8 * col));
+            qn[u] = __builtin_nontemporal_load((const u32x4*)(sbase + (uint32_t)(ic * a.H * DH + 8 * col)));
         }
     };
     auto store_q = [&](const PairInfo& p) {
