@@ -45,6 +45,8 @@ def main():
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the CPU oracle leg (0 = skip)")
     ap.add_argument("--other-configs", type=int, default=1,
                     help="also time tree_verify_attn on cfg2 (three prefix lengths), cfg3 and cfg4 (0 = skip)")
+    ap.add_argument("--bf16-out-iters", type=int, default=25,
+                    help="launches of the bf16-output leg of tree_verify_attn (0 = skip)")
     ap.add_argument("--graph-iters", type=int, default=50,
                     help="replays of the HIP-graph leg (0 = skip)")
     ap.add_argument("--single-iters", type=int, default=200,
@@ -118,6 +120,25 @@ def main():
         if name in stage_bytes:
             gbs = stage_bytes[name] / (med * 1e-3) / 1e9
             stages[name].update(algorithmic_MB=stage_bytes[name] / 1e6, GBps=gbs, frac_of_8TBps=gbs / HBM_PEAK_GBS)
+
+    # tree_verify_attn with bf16 output (what a following bf16 projection consumes; half the bytes
+    # written).  The headline and the parity bar use the fp32 output.
+    verify_bf16_us = None
+    if args.bf16_out_iters > 0:
+        from paper_2503_14075_amd import binding as tw
+        out16 = torch.empty(dw.out.shape, dtype=torch.bfloat16, device=dev)
+        ev16 = []
+        for _ in range(args.bf16_out_iters + 5):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            tw.tree_verify_attn(dw.q_tree, dw.k_view, dw.v_view, dw.ctx_len, dw.max_ctx_len, dw.parent,
+                                dw.n_nodes, cfg.scale, out16, dw.verify_ws)
+            e1.record()
+            ev16.append((e0, e1))
+        torch.cuda.synchronize()
+        t16 = sorted(x.elapsed_time(y) for x, y in ev16[5:])
+        verify_bf16_us = t16[len(t16) // 2] * 1e3
+        del out16
 
     # the same step replayed from a HIP graph (the library only enqueues kernels, so a step can be
     # captured once); reported beside the eager figure, which stays the headline
@@ -242,6 +263,7 @@ def main():
                      "kernel_ms_min": ker_ms[0], "kernel_ms_median": ker_ms[len(ker_ms) // 2]},
         "cpu_baseline": cpu,
         "extras": {"stages": stages, "ms_per_step_hip_graph": graph_ms,
+                   "verify_bf16_output_us_median": verify_bf16_us,
                    "verify_tokens_per_s_kernel_only": tokens / (ker_avg * 1e-3),
                    "verify_single_sequence_latency_us": single_us,
                    "verify_other_configs": others},

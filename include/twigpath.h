@@ -189,13 +189,19 @@ int32_t tw_tree_ancestor_masks(const int32_t* parent, const int32_t* n_nodes, in
  *   k, v     [host structs] same dtype/H/d_h/paging mode
  *   ctx_len  [dev] [B];  max_ctx_len = host upper bound
  *   parent   [dev] [B][T_max];  n_nodes [dev] [B], 1 <= n_nodes[b] <= T_max
- *   out      [dev] [B][T_max][H][d_h] fp32 (rows past n_nodes[b] are not written)
- * Errors: INVALID_ARG, UNSUPPORTED (T_max > 64, d_h, view mismatch), WORKSPACE.
+ *   out      [dev] [B][T_max][H][d_h], 16-byte aligned, dtype out_dtype: TW_F32, or TW_BF16
+ *            (the fp32 result rounded to nearest even once, at the store; what a following
+ *            bf16 projection consumes, and half the bytes written).  Rows past n_nodes[b]
+ *            are not written.
+ * Accuracy for bf16 inputs: fp32 accumulation; the softmax weights enter the value
+ * product as bf16, normalised by their rounded sum: max-abs error <= 2e-3 for fp32 out,
+ * plus half a bf16 unit in the last place of the result for bf16 out.
+ * Errors: INVALID_ARG, UNSUPPORTED (T_max > 64, d_h, view mismatch, out_dtype), WORKSPACE.
  */
 int32_t tw_tree_verify_attn(const void* q, const tw_kv_view* k, const tw_kv_view* v,
                             const int32_t* ctx_len, int32_t max_ctx_len, const int32_t* parent,
                             const int32_t* n_nodes, int32_t T_max, int32_t B, float scale,
-                            float* out, void* ws, size_t ws_bytes, void* stream);
+                            void* out, int32_t out_dtype, void* ws, size_t ws_bytes, void* stream);
 
 /*
  * Greedy acceptance walk with bonus token (Sec. 5.4, App. A, last steps of

@@ -63,7 +63,7 @@ _lib.tw_tree_ancestor_masks.restype = _i32
 _lib.tw_tree_ancestor_masks.argtypes = [_vp, _vp, _i32, _i32, _vp, _vp]
 _lib.tw_tree_verify_attn.restype = _i32
 _lib.tw_tree_verify_attn.argtypes = [_vp, ctypes.POINTER(KvView), ctypes.POINTER(KvView), _vp, _i32, _vp,
-                                     _vp, _i32, _i32, _f32, _vp, _vp, _sz, _vp]
+                                     _vp, _i32, _i32, _f32, _vp, _i32, _vp, _sz, _vp]
 _lib.tw_tree_accept.restype = _i32
 _lib.tw_tree_accept.argtypes = [_vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp, _vp, _vp]
 _lib.tw_kv_commit.restype = _i32
@@ -181,7 +181,7 @@ def tree_verify_attn(q: torch.Tensor, k: KvView, v: KvView, ctx_len: torch.Tenso
     B, T_max = q.shape[0], q.shape[1]
     _check("tw_tree_verify_attn", _lib.tw_tree_verify_attn(
         _ptr(q), ctypes.byref(k), ctypes.byref(v), _ptr(ctx_len), max_ctx_len, _ptr(parent),
-        _ptr(n_nodes), T_max, B, scale, _ptr(out), _ptr(ws),
+        _ptr(n_nodes), T_max, B, scale, _ptr(out), _dtype_code(out), _ptr(ws),
         0 if ws is None else ws.numel() * ws.element_size(), _stream()))
 
 

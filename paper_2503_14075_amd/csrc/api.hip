@@ -203,9 +203,10 @@ int32_t tw_tree_ancestor_masks(const int32_t* parent, const int32_t* n_nodes, in
 int32_t tw_tree_verify_attn(const void* q, const tw_kv_view* k, const tw_kv_view* v,
                             const int32_t* ctx_len, int32_t max_ctx_len, const int32_t* parent,
                             const int32_t* n_nodes, int32_t T_max, int32_t B, float scale,
-                            float* out, void* ws, size_t ws_bytes, void* stream) {
+                            void* out, int32_t out_dtype, void* ws, size_t ws_bytes, void* stream) {
     if (B < 0 || T_max < 1 || max_ctx_len < 0) return TW_ERR_INVALID_ARG;
     if (T_max > TW_MAX_TREE) return TW_ERR_UNSUPPORTED;
+    if (out_dtype != TW_F32 && out_dtype != TW_BF16) return TW_ERR_UNSUPPORTED;
     if (B == 0) return TW_OK;
     if (!q || !ctx_len || !parent || !n_nodes || !out) return TW_ERR_INVALID_ARG;
     int vs = view_status(k, true);
@@ -220,6 +221,7 @@ int32_t tw_tree_verify_attn(const void* q, const tw_kv_view* k, const tw_kv_view
     VerifyArgs a;
     a.q = q;
     a.out = out;
+    a.out_bf16 = out_dtype == TW_BF16;
     a.k = to_dev(*k);
     a.v = to_dev(*v);
     a.ctx_len = ctx_len;

@@ -114,11 +114,15 @@ __global__ __launch_bounds__(kGenThreads) void verify_generic_kernel(VerifyArgs 
     l += __shfl_xor(l, 2, 64);
     if (t >= T) return;
     if (a.n_splits == 1) {
-        float* out = a.out + (((int64_t)b * a.T_max + t) * a.H + h) * d_h;
+        const int64_t row = (((int64_t)b * a.T_max + t) * a.H + h) * d_h;
         const float inv = 1.f / l;
 #pragma unroll
-        for (int cc = 0; cc < 32; ++cc)
-            if (cc < cq) out[qd + 4 * cc] = o[cc] * inv;
+        for (int cc = 0; cc < 32; ++cc) {
+            if (cc < cq) {
+                if (a.out_bf16) ((uint16_t*)a.out)[row + qd + 4 * cc] = f32_to_bf16(o[cc] * inv);
+                else ((float*)a.out)[row + qd + 4 * cc] = o[cc] * inv;
+            }
+        }
     } else {
         const int64_t slot = (((int64_t)split * a.B + b) * a.H + h) * a.T_max + t;
         float* po = a.part_o + slot * d_h;
@@ -165,7 +169,7 @@ __global__ __launch_bounds__(kCombineThreads) void verify_combine_kernel(VerifyA
         acc.w += v.w * w;
     }
     const float inv = 1.f / l;
-    *(float4*)(a.out + row * a.d_h + 4 * c4) = make_float4(acc.x * inv, acc.y * inv, acc.z * inv, acc.w * inv);
+    store_out4(a.out, a.out_bf16, row * a.d_h + 4 * c4, acc.x * inv, acc.y * inv, acc.z * inv, acc.w * inv, false);
 }
 
 hipError_t launch_verify_generic(const VerifyArgs& a, int dtype, hipStream_t s) {

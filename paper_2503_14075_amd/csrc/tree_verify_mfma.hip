@@ -192,26 +192,46 @@ __device__ __forceinline__ void epilogue_direct(const WaveState<DH>& w, const Ve
     // lanes_per_row consecutive lanes store one node's row as consecutive 16-byte pieces
     constexpr int kLanesPerRow = DH / 4, kRowsPerStore = 64 / kLanesPerRow;
     const int sub = lane / kLanesPerRow, c4 = lane % kLanesPerRow;
-    float* dst;
-    int64_t node_stride;
     if (a.n_splits == 1) {
-        dst = a.out + (((int64_t)b * a.T_max + node0) * a.H + h) * DH;
-        node_stride = (int64_t)a.H * DH;
+        // written once, not read again by this kernel: streaming stores
+        const int64_t first = (((int64_t)b * a.T_max + node0) * a.H + h) * DH + 4 * c4;   // node 0 of the block
+        const int64_t node_stride = (int64_t)a.H * DH;
+        if (a.out_bf16) {
+            typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
+            uint16_t* dst = (uint16_t*)a.out + first;
+#pragma unroll
+            for (int n0 = 0; n0 < 32; n0 += kRowsPerStore) {
+                const int node = n0 + sub;
+                if (node < T) {
+                    const f32x4 v = *(const f32x4*)(tile + node * Cf::kOStride + 4 * c4);
+                    const u32x2 p = {pack_bf16x2(v.x, v.y), pack_bf16x2(v.z, v.w)};
+                    __builtin_nontemporal_store(p, (u32x2*)(dst + node * node_stride));
+                }
+            }
+        } else {
+            float* dst = (float*)a.out + first;
+#pragma unroll
+            for (int n0 = 0; n0 < 32; n0 += kRowsPerStore) {
+                const int node = n0 + sub;
+                if (node < T)
+                    __builtin_nontemporal_store(*(const f32x4*)(tile + node * Cf::kOStride + 4 * c4),
+                                                (f32x4*)(dst + node * node_stride));
+            }
+        }
     } else {
         const int64_t slot = (((int64_t)split * a.B + b) * a.H + h) * a.T_max + node0;
-        dst = a.part_o + slot * DH;
-        node_stride = DH;
+        float* dst = a.part_o + slot * DH;
         if (g == 0 && li < T) {
             a.part_ml[(slot + li) * 2] = w.run_m * kLn2;   // natural-log units for the combine
             a.part_ml[(slot + li) * 2 + 1] = l;
         }
-    }
 #pragma unroll
-    for (int n0 = 0; n0 < 32; n0 += kRowsPerStore) {
-        const int node = n0 + sub;
-        if (node < T)   // written once, not read again by this kernel: streaming stores
-            __builtin_nontemporal_store(*(const f32x4*)(tile + node * Cf::kOStride + 4 * c4),
-                                        (f32x4*)(dst + node * node_stride + 4 * c4));
+        for (int n0 = 0; n0 < 32; n0 += kRowsPerStore) {
+            const int node = n0 + sub;
+            if (node < T)
+                __builtin_nontemporal_store(*(const f32x4*)(tile + node * Cf::kOStride + 4 * c4),
+                                            (f32x4*)(dst + node * DH + 4 * c4));
+        }
     }
 }
 
@@ -263,8 +283,8 @@ __device__ __forceinline__ void epilogue_merge(const WaveState<DH>& w, const Ver
         }
         if (a.n_splits == 1) {
             const float inv = 1.f / l;
-            float* dst = a.out + (((int64_t)b * a.T_max + node) * a.H + h) * DH + 4 * d4;
-            *(float4*)dst = make_float4(acc.x * inv, acc.y * inv, acc.z * inv, acc.w * inv);
+            store_out4(a.out, a.out_bf16, (((int64_t)b * a.T_max + node) * a.H + h) * DH + 4 * d4, acc.x * inv,
+                       acc.y * inv, acc.z * inv, acc.w * inv, false);
         } else {
             const int64_t slot = (((int64_t)split * a.B + b) * a.H + h) * a.T_max + node;
             *(float4*)(a.part_o + slot * DH + 4 * d4) = acc;

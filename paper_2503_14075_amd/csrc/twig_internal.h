@@ -47,6 +47,33 @@ __device__ __forceinline__ int64_t pool_row(const KvDev& kv, int b, int r) {
 
 __device__ __forceinline__ float bf16_to_f32(uint16_t x) { return __uint_as_float((uint32_t)x << 16); }
 
+// fp32 -> bf16, round to nearest even (the hardware conversion), two values in one word
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+    typedef __bf16 bf2_t __attribute__((ext_vector_type(2)));
+    const bf2_t p = {(__bf16)lo, (__bf16)hi};
+    return __builtin_bit_cast(uint32_t, p);
+}
+__device__ __forceinline__ uint16_t f32_to_bf16(float x) { return (uint16_t)(pack_bf16x2(x, 0.f) & 0xFFFFu); }
+
+// Four consecutive elements of an attention output (element index i, a multiple of 4) in its dtype.
+// `streaming` marks data this kernel does not read again.
+__device__ __forceinline__ void store_out4(void* out, int out_bf16, int64_t i, float x, float y, float z, float w,
+                                           bool streaming) {
+    typedef __attribute__((ext_vector_type(4))) float f4_t;
+    typedef __attribute__((ext_vector_type(2))) unsigned int u2_t;
+    if (out_bf16) {
+        const u2_t v = {pack_bf16x2(x, y), pack_bf16x2(z, w)};
+        u2_t* p = (u2_t*)((uint16_t*)out + i);
+        if (streaming) __builtin_nontemporal_store(v, p);
+        else *p = v;
+    } else {
+        const f4_t v = {x, y, z, w};
+        f4_t* p = (f4_t*)((float*)out + i);
+        if (streaming) __builtin_nontemporal_store(v, p);
+        else *p = v;
+    }
+}
+
 // Ancestor-or-self mask of node i from a parent array held in shared memory.
 // Parents are clamped to [0, i) so the walk always ends at the root.
 __device__ __forceinline__ uint64_t ancestor_mask(const int* s_parent, int i) {
@@ -64,7 +91,8 @@ __device__ __forceinline__ uint64_t ancestor_mask(const int* s_parent, int i) {
 // --- verification attention -------------------------------------------------
 struct VerifyArgs {
     const void* q;
-    float* out;
+    void* out;        // [B][T_max][H][d_h], fp32 or bf16
+    int32_t out_bf16;
     KvDev k, v;
     const int32_t* ctx_len;
     const int32_t* parent;

@@ -119,14 +119,15 @@ def test_argument_validation_without_launch():
     k, v = _view(), _view()
     call = lambda **kw: lib.tw_tree_verify_attn(
         kw.get("q", P), ctypes.byref(kw.get("k", k)), ctypes.byref(kw.get("v", v)), P,
-        kw.get("max_ctx", 4096), P, P, kw.get("T", 26), kw.get("B", 1), f, P, kw.get("ws", None),
-        kw.get("ws_bytes", 0), None)
+        kw.get("max_ctx", 4096), P, P, kw.get("T", 26), kw.get("B", 1), f, P, kw.get("out_dtype", tw.TW_F32),
+        kw.get("ws", None), kw.get("ws_bytes", 0), None)
     assert call(T=65) == tw.TW_ERR_UNSUPPORTED
     assert call(T=0) == tw.TW_ERR_INVALID_ARG
     assert call(q=None) == tw.TW_ERR_INVALID_ARG
     assert call(k=_view(d_h=100)) == tw.TW_ERR_UNSUPPORTED
     assert call(k=_view(d_h=256)) == tw.TW_ERR_UNSUPPORTED
     assert call(k=_view(dtype=7)) == tw.TW_ERR_UNSUPPORTED
+    assert call(out_dtype=5) == tw.TW_ERR_UNSUPPORTED
     assert call(v=_view(H=16)) == tw.TW_ERR_UNSUPPORTED                 # views disagree
     assert call(v=_view(dtype=tw.TW_F32)) == tw.TW_ERR_UNSUPPORTED
     assert call(k=_view(row_off=None)) == tw.TW_ERR_INVALID_ARG         # neither offsets nor pages

@@ -218,6 +218,39 @@ def test_verify_and_score_with_negative_scale(tw):
     _check_score(tw, torch.bfloat16, 4, 128, 100, 5, [20, 9], [20, 9], True, scale=-1 / math.sqrt(128))
 
 
+@pytest.mark.parametrize("case", ["direct", "pair", "phases", "split", "generic"])
+def test_verify_bf16_output(tw, case):
+    # the same result rounded once to bf16 at the store: fp32-output bar plus half a unit in the last
+    # place of the exact value, on every path that writes `out`
+    B, H, d_h, T, ctx, dtype = {"direct": (64, 32, 128, 20, 90, torch.bfloat16),     # 4 heads per workgroup
+                                "pair": (40, 32, 128, 50, 70, torch.bfloat16),       # two node blocks
+                                "phases": (3, 8, 128, 20, 200, torch.bfloat16),      # merge through LDS
+                                "split": (1, 32, 128, 26, 2050, torch.bfloat16),     # partials + combine kernel
+                                "generic": (2, 4, 40, 20, 97, torch.bfloat16)}[case]
+    ctxs = [ctx + 13 * (b % 5) for b in range(B)]
+    trees = [W.random_parent_tree(W.HostRng(51, b), T, 5) for b in range(B)]
+    q, k, v, off = make_case(52, B, H, d_h, ctxs, T, dtype, trees, kv_std=1.0, q_std=1.0)
+    scale = 1 / math.sqrt(d_h)
+    want = oracle.tree_verify_attn(q, k, v, ctxs, [T] * B, trees, scale, row_off=off)
+    qd, kd, vd, ro = q.to(DEV), k.to(DEV), v.to(DEV), _i32(off)
+    kv, vv = tw.kv_view(kd, ro), tw.kv_view(vd, ro)
+    nbytes = tw.workspace_bytes(tw.TW_CALL_TREE_VERIFY_ATTN, B, T, H, d_h, max(ctxs) + T)
+    assert (nbytes > 0) == (case == "split")
+    ws = torch.empty(max(nbytes, 4) // 4, dtype=torch.float32, device=DEV) if nbytes else None
+    out = torch.full((B, T, H, d_h), float("nan"), dtype=torch.bfloat16, device=DEV)
+    tw.tree_verify_attn(qd, kv, vv, _i32(ctxs), max(ctxs), _i32(trees), _i32([T] * B), scale, out, ws)
+    torch.cuda.synchronize()
+    got = out.cpu().double()
+    assert torch.isfinite(got).all()
+    half_ulp = torch.clamp(want.abs(), min=2.0 ** -126) * 2.0 ** -8      # >= half a bf16 ulp of the exact value
+    assert bool(((got - want).abs() <= ATTN_TOL + half_ulp).all())
+    # and it is the fp32 result, rounded: no second source of error
+    out32 = torch.empty((B, T, H, d_h), dtype=torch.float32, device=DEV)
+    tw.tree_verify_attn(qd, kv, vv, _i32(ctxs), max(ctxs), _i32(trees), _i32([T] * B), scale, out32, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(out32.to(torch.bfloat16).view(torch.int16), out.view(torch.int16))
+
+
 def test_verify_is_deterministic(tw):
     H, d_h, T = 32, 128, 26
     trees = [W.fanout_tree(W.HostRng(1, 1), T, (4, 3, 2, 1, 1))]
