@@ -39,7 +39,7 @@ def verify_bytes(cfg, w):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--batch", type=int, default=128, help="independent sequences per step")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the CPU oracle leg (0 = skip)")
@@ -202,9 +202,34 @@ def main():
             others[name] = {"kernel_us_median": med * 1e3, "algorithmic_MB": nbytes / 1e6,
                             "GBps": nbytes / (med * 1e-3) / 1e9,
                             "frac_of_8TBps": nbytes / (med * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                            "tree_tokens": sum(wo.n_nodes)}
+                            "tree_tokens": sum(wo.n_nodes),
+                            "tokens_per_s": sum(wo.n_nodes) / (med * 1e-3),
+                            # one launch covers every layer cache of the config: tree rows of one
+                            # sequence per full sweep over its layers
+                            "sweep_tokens_per_s": sum(wo.n_nodes) / wo.cfg.L / (med * 1e-3)}
             del do, wo
         del flush_a, flush_b
+
+    # what plain library kernels reach on this machine in this run (context for the roofline fraction):
+    # a 1 GiB device-to-device copy (read + write) and a 1 GiB reduction (read only)
+    ctx_a = torch.empty(1 << 29, dtype=torch.bfloat16, device=dev).normal_()
+    ctx_b = torch.empty_like(ctx_a)
+    box = {}
+    for name, fn, nbytes in (("torch_copy_1GiB_GBps_read_plus_write", lambda: ctx_b.copy_(ctx_a), 2 << 30),
+                             ("torch_sum_1GiB_GBps_read", lambda: ctx_a.sum(), 1 << 30)):
+        for _ in range(3):
+            fn()
+        evs = []
+        for _ in range(10):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            fn()
+            e1.record()
+            evs.append((e0, e1))
+        torch.cuda.synchronize()
+        ts = sorted(x.elapsed_time(y) for x, y in evs)
+        box[name] = nbytes / (ts[len(ts) // 2] * 1e-3) / 1e9
+    del ctx_a, ctx_b
 
     cpu = None
     if args.cpu_seconds > 0:
@@ -232,8 +257,31 @@ def main():
             oracle.tree_accept([w.draft[b]], [w.argmax[b]], [w.tree_seq[b]], [cfg.T])
             t_cpu += time.perf_counter() - s
             n_done += 1
-        cpu = {"value": n_done * cfg.T / t_cpu, "unit": "tokens/s", "cores": oracle.max_threads(),
-               "kind": "oracle",
+        # the same oracle on one thread, a quarter of the budget
+        n_thr = oracle.max_threads()
+        oracle.set_threads(1)
+        n1, t1_cpu = 0, 0.0
+        while t1_cpu < args.cpu_seconds / 4:
+            b = n1 % cfg.B
+            r0, nr = w.row_off[b], w.ctx_len[b] + w.n_nodes[b]
+            kp, vp, qt = w.k_pool[r0:r0 + nr].cpu(), w.v_pool[r0:r0 + nr].cpu(), w.q_tree[b:b + 1].cpu()
+            s = time.perf_counter()
+            oracle.tree_verify_attn(qt, kp, vp, [w.ctx_len[b]], [w.n_nodes[b]], [w.parent[b]], cfg.scale,
+                                    row_off=[0])
+            t1_cpu += time.perf_counter() - s
+            n1 += 1
+        oracle.set_threads(n_thr)
+        model = ""
+        try:
+            for ln in open("/proc/cpuinfo"):
+                if ln.startswith("model name"):
+                    model = ln.split(":", 1)[1].strip()
+                    break
+        except OSError:
+            pass
+        cpu = {"value": n_done * cfg.T / t_cpu, "unit": "tokens/s", "cores": n_thr,
+               "kind": "oracle", "cpu_model": model,
+               "verify_only_single_thread_tokens_per_s": n1 * cfg.T / t1_cpu,
                "sample": f"whole path on {n_done} sequences drawn in order (with wrap-around) from the "
                          f"{cfg.B} of the same batch ({t_cpu:.1f} s of fp64 C, OpenMP over heads/rows)"}
 
@@ -264,6 +312,7 @@ def main():
         "cpu_baseline": cpu,
         "extras": {"stages": stages, "ms_per_step_hip_graph": graph_ms,
                    "verify_bf16_output_us_median": verify_bf16_us,
+                   "same_box_library_kernels": box,
                    "verify_tokens_per_s_kernel_only": tokens / (ker_avg * 1e-3),
                    "verify_single_sequence_latency_us": single_us,
                    "verify_other_configs": others},
