@@ -73,7 +73,9 @@ int32_t tw_version(void);
  * Scratch bytes needed by a call.  `which` is a tw_call.  For
  * TW_CALL_TTP_SCORE: rows = n_q_max, max_rows = n_tot_max.  For
  * TW_CALL_TREE_VERIFY_ATTN: rows = T_max, max_rows = max_ctx_len + T_max.
- * Returns 0 for calls that need none or for invalid arguments.
+ * Returns 0 for calls that need none or for invalid arguments.  The buffer
+ * handed to the call is device memory, 16-byte aligned; its contents on entry
+ * do not matter and are undefined on return.
  */
 size_t tw_workspace_bytes(int32_t which, int32_t B, int32_t rows, int32_t H, int32_t d_h,
                           int32_t max_rows);

@@ -25,26 +25,27 @@ int view_status(const tw_kv_view* v, bool allow_paged) {
 namespace tw {
 
 // Wavefront layout and row split of tree verification.  A node block is 32 tree rows.  With at
-// least 2048 (sequence, head, node block) units every wavefront takes its own unit (four heads,
-// or two heads x two blocks, per workgroup); with fewer, a workgroup takes one head and its
-// wavefronts share the head's rows round-robin.  The cache rows are split over several workgroups
-// only while the launch has fewer than 512 workgroups, and never below 256 rows per split (a
-// split costs a partial-output round trip worth about 65 rows of K and V).
+// least 768 (sequence, head, node block) units every wavefront takes its own unit (four heads,
+// or two heads x two blocks, per workgroup) and the cache is never split; with fewer, a workgroup
+// takes one head and its wavefronts share the head's rows round-robin.  Then the cache rows are
+// additionally split over several workgroups while the launch has fewer than 256 of them (one
+// per compute unit), never below 256 rows per split: a split costs a second prologue, a partial
+// output round trip and the merge launch, 15 to 20 us in all.  Thresholds from timing sweeps
+// over B = 1..96, 282..4160 rows, T = 26 and 64.
 VerifyPlan verify_plan(int B, int H, int T_max, int max_rows) {
     VerifyPlan p;
     p.n_blk = T_max > 32 ? 2 : 1;
     const long units = (long)B * H * p.n_blk;
-    long wgs;
-    if (units >= 2048) {
+    p.n_splits = 1;
+    if (units >= 768) {
         p.heads_per_wg = 4 / p.n_blk;
         p.n_phase = 1;
-        wgs = (long)B * ((H + p.heads_per_wg - 1) / p.heads_per_wg);
-    } else {
-        p.heads_per_wg = 1;
-        p.n_phase = 4 / p.n_blk;
-        wgs = (long)B * H;
+        return p;
     }
-    long want = wgs >= 512 || wgs <= 0 ? 1 : (512 + wgs - 1) / wgs;
+    p.heads_per_wg = 1;
+    p.n_phase = 4 / p.n_blk;
+    const long wgs = (long)B * H;
+    long want = wgs >= 256 || wgs <= 0 ? 1 : (256 + wgs - 1) / wgs;
     long cap = max_rows / 256;
     if (cap < 1) cap = 1;
     if (cap > 64) cap = 64;
@@ -243,6 +244,7 @@ int32_t tw_tree_verify_attn(const void* q, const tw_kv_view* k, const tw_kv_view
     if (a.n_splits > 1) {
         const size_t need = verify_workspace_bytes(B, a.H, T_max, a.d_h, max_rows);
         if (!ws || ws_bytes < need) return TW_ERR_WORKSPACE;
+        if ((uintptr_t)ws % 16) return TW_ERR_INVALID_ARG;
         a.part_o = (float*)ws;
         a.part_ml = a.part_o + (size_t)a.n_splits * B * a.H * T_max * a.d_h;
     }

@@ -138,36 +138,49 @@ __global__ __launch_bounds__(kGenThreads) void verify_generic_kernel(VerifyArgs 
 
 // Merge the per-split partial results in split order.  d_h/4 lanes per (sequence, node, head) row,
 // four output columns each; a workgroup takes as many consecutive rows as fit 256 threads, so its
-// stores cover a contiguous piece of `out`.
+// stores cover a contiguous piece of `out`.  The partials of four splits are requested together
+// and before anything depends on them (the kernel is a few microseconds of pure memory latency);
+// the merge itself is the online-softmax update, one split at a time.
 constexpr int kCombineThreads = 256;
+constexpr int kCombineBatch = 4;
 __global__ __launch_bounds__(kCombineThreads) void verify_combine_kernel(VerifyArgs a) {
     const int lanes = a.d_h / 4, rows_per_wg = kCombineThreads / lanes;
     const int sub = threadIdx.x / lanes, c4 = threadIdx.x % lanes;
     const int64_t row = (int64_t)blockIdx.x * rows_per_wg + sub;   // (b * T_max + t) * H + h
     if (sub >= rows_per_wg || row >= (int64_t)a.B * a.T_max * a.H) return;
     const int h = (int)(row % a.H), t = (int)((row / a.H) % a.T_max), b = (int)(row / ((int64_t)a.H * a.T_max));
-    int T = a.n_nodes[b];
-    T = T < 1 ? 1 : (T > a.T_max ? a.T_max : T);
-    if (t >= T) return;
-    float m = -INFINITY;
-    for (int s = 0; s < a.n_splits; ++s) {
-        const int64_t slot = (((int64_t)s * a.B + b) * a.H + h) * a.T_max + t;
-        m = fmaxf(m, a.part_ml[slot * 2]);
-    }
-    float l = 0.f;
+    const int T_raw = a.n_nodes[b];
+    const int64_t split_stride = (int64_t)a.B * a.H * a.T_max;
+    const int64_t slot0 = ((int64_t)b * a.H + h) * a.T_max + t;
+    float m = -INFINITY, l = 0.f;
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int s = 0; s < a.n_splits; ++s) {
-        const int64_t slot = (((int64_t)s * a.B + b) * a.H + h) * a.T_max + t;
-        const float ms = a.part_ml[slot * 2];
-        if (ms == -INFINITY) continue;   // a split in which this node saw no key
-        const float w = expf(ms - m);
-        l += a.part_ml[slot * 2 + 1] * w;
-        const float4 v = *(const float4*)(a.part_o + slot * a.d_h + 4 * c4);
-        acc.x += v.x * w;
-        acc.y += v.y * w;
-        acc.z += v.z * w;
-        acc.w += v.w * w;
+    for (int s0 = 0; s0 < a.n_splits; s0 += kCombineBatch) {
+        float2 ml[kCombineBatch];
+        float4 v[kCombineBatch];
+#pragma unroll
+        for (int i = 0; i < kCombineBatch; ++i) {
+            const int s = min(s0 + i, a.n_splits - 1);   // past the last split: re-read it, unused
+            const int64_t slot = slot0 + s * split_stride;
+            ml[i] = *(const float2*)(a.part_ml + slot * 2);
+            v[i] = *(const float4*)(a.part_o + slot * a.d_h + 4 * c4);
+        }
+#pragma unroll
+        for (int i = 0; i < kCombineBatch; ++i) {
+            // a split in which this node saw no key carries max = -inf and is skipped
+            if (s0 + i < a.n_splits && ml[i].x != -INFINITY) {
+                const float m_new = fmaxf(m, ml[i].x);
+                const float keep = expf(m - m_new), w = expf(ml[i].x - m_new);
+                l = l * keep + ml[i].y * w;
+                acc.x = acc.x * keep + v[i].x * w;
+                acc.y = acc.y * keep + v[i].y * w;
+                acc.z = acc.z * keep + v[i].z * w;
+                acc.w = acc.w * keep + v[i].w * w;
+                m = m_new;
+            }
+        }
     }
+    const int T = T_raw < 1 ? 1 : (T_raw > a.T_max ? a.T_max : T_raw);
+    if (t >= T) return;
     const float inv = 1.f / l;
     store_out4(a.out, a.out_bf16, row * a.d_h + 4 * c4, acc.x * inv, acc.y * inv, acc.z * inv, acc.w * inv, false);
 }
