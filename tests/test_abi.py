@@ -134,6 +134,7 @@ def test_argument_validation_without_launch():
     assert call(k=_view(pt=P, max_pages=0, page_rows=16)) == tw.TW_ERR_INVALID_ARG
     assert call() == tw.TW_ERR_WORKSPACE                                 # split launch, no workspace
     assert call(ws=P, ws_bytes=16) == tw.TW_ERR_WORKSPACE
+    assert call(ws=P + 4, ws_bytes=1 << 30) == tw.TW_ERR_INVALID_ARG    # workspace not 16-byte aligned
     assert call(B=0) == tw.TW_OK
 
     sc = lambda **kw: lib.tw_ttp_score(
