@@ -85,6 +85,7 @@ int32_t tw_ttp_score(const void* q_sel, int32_t n_q_max, const int32_t* n_q, con
     if ((int64_t)v_start + M > n_tot_max || n_q_max > n_tot_max) return TW_ERR_INVALID_ARG;
     const size_t need = score_workspace_bytes(B, k->H, n_q_max, n_tot_max);
     if (!ws || ws_bytes < need) return TW_ERR_WORKSPACE;
+    if ((uintptr_t)ws % 16) return TW_ERR_INVALID_ARG;
     ScoreArgs a;
     a.q_sel = q_sel;
     a.k = to_dev(*k);

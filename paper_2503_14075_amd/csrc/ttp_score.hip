@@ -12,6 +12,11 @@
 // score_reduce then adds the heads in a fixed order.  No floating-point
 // atomics: results are bit-identical from run to run.
 //
+// A launch with few (sequence, head) pairs and long sequences splits the keys
+// over workgroups instead, in two launches: the first leaves per-row
+// (max, sum) of every key split in the workspace, the second merges them in
+// split order and takes one share of the visual columns per workgroup.
+//
 // bf16 with d_h 64/128 and at most 128 scoring rows runs on the matrix cores:
 // one wavefront per head, 32-key chunks staged through LDS exactly as in the
 // verification kernel.  Pass 1 forms K.Q^T (a lane owns one scoring row, so
@@ -41,7 +46,10 @@ struct ScCfg {
     static constexpr int kWaveLds = kScChunk * kKStride + 128 * 4;   // K chunk + per-row statistics
 };
 
-template <int DH, int NB>
+// MODE 0: both passes, one wavefront per (sequence, head).  MODE 1: row statistics of key split
+// blockIdx.z only.  MODE 2: merge the statistics of all splits, then the weights of column split
+// blockIdx.z.
+template <int DH, int NB, int MODE>
 __global__ __launch_bounds__(kScMfThreads, (NB <= 2 ? 2 : 1)) void score_mfma_kernel(ScoreArgs a) {
     using Cf = ScCfg<DH>;
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
@@ -55,8 +63,11 @@ __global__ __launch_bounds__(kScMfThreads, (NB <= 2 ? 2 : 1)) void score_mfma_ke
     n_tot = n_tot < 0 ? 0 : (n_tot > a.n_tot_max ? a.n_tot_max : n_tot);
     const int pos0 = a.q_pos0[b];
     float* partial = a.ws + ((int64_t)b * a.H + h) * a.M;
+    const int split = MODE == 0 ? 0 : blockIdx.z;
+    float2* stats = (float2*)a.stats + (((int64_t)b * a.H + h) * a.n_splits) * (32 * NB);   // [split][row]
     if (n_tot == 0) {
-        for (int m = lane; m < a.M; m += 64) partial[m] = 0.f;
+        if (MODE != 1 && split == 0)
+            for (int m = lane; m < a.M; m += 64) partial[m] = 0.f;
         return;
     }
     unsigned char* ldsK = lds + wave * Cf::kWaveLds;
@@ -85,11 +96,11 @@ __global__ __launch_bounds__(kScMfThreads, (NB <= 2 ? 2 : 1)) void score_mfma_ke
     const int64_t last_pool_row = a.k.pool_rows - 1;
     const int64_t row0 = (int64_t)a.k.row_off[b];
     u32x4 pk[Cf::kLoads];
-    auto issue_loads = [&](int base) {
+    auto issue_loads = [&](int base, int end) {
 #pragma unroll
         for (int j = 0; j < Cf::kLoads; ++j) {
             int r = base + ld_row + Cf::kRowsPerLoad * j;
-            r = r < n_tot - 1 ? r : n_tot - 1;   // past the end: re-read the last key (cached), masked below
+            r = r < end - 1 ? r : end - 1;   // past the end: re-read the last key (cached), masked below
             int64_t prow = row0 + r;
             prow = prow < 0 ? 0 : (prow > last_pool_row ? last_pool_row : prow);
             pk[j] = *(const u32x4*)(kbase + prow * pool_stride);
@@ -117,10 +128,27 @@ __global__ __launch_bounds__(kScMfThreads, (NB <= 2 ? 2 : 1)) void score_mfma_ke
         run_l[nb] = 0.f;
         vis_end[nb] = a.causal ? min(pos0 + 32 * nb + li + 1, n_tot) : n_tot;
     }
-    issue_loads(0);
-    for (int base = 0; base < n_tot; base += kScChunk) {
+    // key range of pass 1: everything, or this split's share in whole chunks
+    int k_begin = 0, k_end = n_tot;
+    if (MODE == 1) {
+        const int per = ((n_tot + a.n_splits - 1) / a.n_splits + kScChunk - 1) / kScChunk * kScChunk;
+        k_begin = min(split * per, n_tot);
+        k_end = min(k_begin + per, n_tot);
+    }
+    // column range of pass 2: the chunks that cover the visual span, or this split's share of them
+    const int span_end = a.v_start + a.M;
+    int c_begin = a.v_start / kScChunk * kScChunk, c_end = span_end;
+    if (MODE == 2) {
+        const int chunks = (span_end - c_begin + kScChunk - 1) / kScChunk;
+        const int per = (chunks + a.n_splits - 1) / a.n_splits * kScChunk;
+        c_begin = min(c_begin + split * per, span_end);
+        c_end = min(c_begin + per, span_end);
+    }
+    const int c_load_end = max(1, min(c_end, n_tot));
+    if (MODE != 2) issue_loads(k_begin, k_end);   // k_end >= 1 here
+    for (int base = k_begin; MODE != 2 && base < k_end; base += kScChunk) {
         stage();
-        issue_loads(base + kScChunk);
+        issue_loads(base + kScChunk, k_end);
         lds_sync();
         floatx16 s[NB];
 #pragma unroll
@@ -153,6 +181,30 @@ __global__ __launch_bounds__(kScMfThreads, (NB <= 2 ? 2 : 1)) void score_mfma_ke
             run_m[nb] = m_new;
         }
     }
+    if (MODE == 2) {
+        issue_loads(c_begin, c_load_end);   // in flight while the statistics are merged
+        // (max, sum) of row i over all key splits, merged in split order; both lane groups compute it
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+            const float2* st = stats + 32 * nb + li;
+            float m = -INFINITY, l = 0.f;
+            for (int s0 = 0; s0 < a.n_splits; s0 += 4) {
+                float2 v[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) v[u] = st[(int64_t)min(s0 + u, a.n_splits - 1) * (32 * NB)];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    if (s0 + u >= a.n_splits) continue;
+                    const float m_new = fmaxf(m, v[u].x);
+                    const float m_safe = m_new == -INFINITY ? 0.f : m_new;
+                    l = l * fast_exp2(m - m_safe) + v[u].y * fast_exp2(v[u].x - m_safe);
+                    m = m_new;
+                }
+            }
+            run_m[nb] = m;
+            run_l[nb] = g == 0 ? l : 0.f;   // the lane-group merge below adds the two halves
+        }
+    }
     // merge the two lane groups of a row; publish max + log2(sum) per row
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
@@ -161,8 +213,13 @@ __global__ __launch_bounds__(kScMfThreads, (NB <= 2 ? 2 : 1)) void score_mfma_ke
         const float m_safe = m == -INFINITY ? 0.f : m;
         const float l = run_l[nb] * fast_exp2(run_m[nb] - m_safe) + ol * fast_exp2(om - m_safe);
         const int i = 32 * nb + li;
-        if (g == 0) s_stat[i] = (i < n_q && l > 0.f) ? m + log2f(l) : INFINITY;   // +inf: row contributes nothing
+        if (MODE == 1) {
+            if (g == 0) stats[(int64_t)split * (32 * NB) + i] = make_float2(m, l);
+        } else if (g == 0) {
+            s_stat[i] = (i < n_q && l > 0.f) ? m + log2f(l) : INFINITY;   // +inf: row contributes nothing
+        }
     }
+    if (MODE == 1) return;
     lds_sync();
     float mc[NB][16];
 #pragma unroll
@@ -171,13 +228,11 @@ __global__ __launch_bounds__(kScMfThreads, (NB <= 2 ? 2 : 1)) void score_mfma_ke
         for (int r = 0; r < 16; ++r) mc[nb][r] = s_stat[32 * nb + acc_row(r, g)];
 
     // ---- pass 2: weights on the visual keys, summed over scoring rows -----------
-    const int span_end = a.v_start + a.M;
-    const int base2 = a.v_start / kScChunk * kScChunk;
-    issue_loads(base2);
-    for (int base = base2; base < span_end; base += kScChunk) {
+    if (MODE != 2) issue_loads(c_begin, c_load_end);
+    for (int base = c_begin; base < c_end; base += kScChunk) {
         lds_sync();   // fragment reads of the previous chunk are complete before it is overwritten
         stage();
-        issue_loads(base + kScChunk);
+        issue_loads(base + kScChunk, c_load_end);
         lds_sync();
         floatx16 d[NB];
 #pragma unroll
@@ -374,15 +429,42 @@ __global__ __launch_bounds__(256) void score_reduce_kernel(ScoreArgs a) {
     a.scores[(int64_t)b * a.M + m] = acc / ((float)a.H * (float)n_q);
 }
 
+// Key splits of the two-pass matrix-core kernel: up to 256 workgroups in all (more brought
+// nothing in timing sweeps over 1..16 sequences of 700..3000 keys, and cost time with 128
+// scoring rows, where a compute unit holds one workgroup), at least two 32-key chunks per split.
+int score_key_splits(int B, int H, int n_tot_max) {
+    const long wgs = (long)B * ((H + 3) / 4);
+    if (wgs <= 0 || wgs >= 256) return 1;
+    long want = (256 + wgs - 1) / wgs, cap = n_tot_max / 64;
+    want = want < cap ? want : cap;
+    return (int)(want < 1 ? 1 : (want > 32 ? 32 : want));
+}
+
+static size_t score_partial_floats(int B, int H, int n_tot_max) {
+    return ((size_t)B * H * n_tot_max + 3) / 4 * 4;   // keeps the statistics behind it 16-byte aligned
+}
+
 size_t score_workspace_bytes(int B, int H, int n_q_max, int n_tot_max) {
     (void)n_q_max;
-    return (size_t)B * H * n_tot_max * sizeof(float);   // per-head partial sums, at most n_tot_max visual keys
+    // per-head partial sums (at most n_tot_max visual keys), then (max, sum) of up to 128 scoring
+    // rows per (sequence, head, key split)
+    const int ns = score_key_splits(B, H, n_tot_max);
+    return (score_partial_floats(B, H, n_tot_max) + (ns > 1 ? (size_t)B * H * ns * 128 * 2 : 0)) * sizeof(float);
 }
 
 template <int DH, int NB>
-static hipError_t launch_score_mfma(const ScoreArgs& a, hipStream_t s) {
+static hipError_t launch_score_mfma(const ScoreArgs& a0, hipStream_t s) {
+    ScoreArgs a = a0;
     const size_t lds = 4 * (size_t)ScCfg<DH>::kWaveLds;
-    hipLaunchKernelGGL((score_mfma_kernel<DH, NB>), dim3((a.H + 3) / 4, a.B), dim3(kScMfThreads), lds, s, a);
+    a.n_splits = score_key_splits(a.B, a.H, a.n_tot_max);
+    a.stats = a.ws + score_partial_floats(a.B, a.H, a.n_tot_max);
+    const dim3 grid((a.H + 3) / 4, a.B, a.n_splits);
+    if (a.n_splits == 1) {
+        hipLaunchKernelGGL((score_mfma_kernel<DH, NB, 0>), grid, dim3(kScMfThreads), lds, s, a);
+    } else {
+        hipLaunchKernelGGL((score_mfma_kernel<DH, NB, 1>), grid, dim3(kScMfThreads), lds, s, a);
+        hipLaunchKernelGGL((score_mfma_kernel<DH, NB, 2>), grid, dim3(kScMfThreads), lds, s, a);
+    }
     return hipGetLastError();
 }
 

@@ -125,9 +125,12 @@ struct ScoreArgs {
     const int32_t* n_tot;
     float* scores;
     float* ws;
+    float* stats = nullptr;    // per-split row statistics, inside ws (set by the launcher)
+    int32_t n_splits = 1;
     int32_t n_q_max, n_tot_max, B, H, d_h, v_start, M, causal;
     float scale;
 };
+int score_key_splits(int B, int H, int n_tot_max);
 size_t score_workspace_bytes(int B, int H, int n_q_max, int n_tot_max);
 hipError_t launch_score(const ScoreArgs& a, int dtype, hipStream_t s);
 hipError_t launch_score_reduce(const ScoreArgs& a, hipStream_t s);

@@ -543,6 +543,17 @@ def _check_score(tw, dtype, H, d_h, M, v0, n_text, n_q, causal, q_std=1.0, seed=
     assert torch.equal(again, scores)          # fixed summation order
 
 
+def test_score_key_splits(tw):
+    # few (sequence, head) pairs and long sequences: the keys are split over workgroups (a row
+    # statistics launch, then a weights launch that merges them).  Ragged lengths leave some key
+    # and column splits of the short sequence empty.
+    assert tw.workspace_bytes(tw.TW_CALL_TTP_SCORE, 2, 70, 8, 128, 1820) > 2 * 8 * 1820 * 4
+    _check_score(tw, torch.bfloat16, 8, 128, 300, 20, [1500, 10], [16, 70], True)
+    _check_score(tw, torch.bfloat16, 4, 64, 1000, 0, [200], [128], False, q_std=4.0)
+    _check_score(tw, torch.bfloat16, 32, 128, 2880, 0, [128, 77], [16, 16], True)   # high-resolution prompt
+    _check_score(tw, torch.bfloat16, 3, 128, 257, 31, [1, 600], [1, 33], True, q_std=5.0)
+
+
 @pytest.mark.parametrize("n_q", [[1, 1, 1], [8, 5, 8], [33, 64, 40], [128, 100, 65]])
 @pytest.mark.parametrize("causal", [True, False])
 def test_score_bf16_matrix_core_path(tw, n_q, causal):
