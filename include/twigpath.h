@@ -239,8 +239,8 @@ int32_t tw_kv_commit(const int32_t* path, const int32_t* n_acc, int32_t T_max, c
                      void* stream);
 
 /*
- * Rank-ordered top-E of each row (the per-node expansion of the draft tree,
- * Sec. 5.4 / App. A: "its top-E predicted tokens").  ids[r] / vals[r] receive the
+ * Rank-ordered top-E of each row (the per-node expansion of the draft tree by
+ * its E most probable tokens, Sec. 5.4 / App. A).  ids[r] / vals[r] receive the
  * E largest entries of probs[r][0..V), larger value first, equal values lower
  * index first.  probs [dev] [n][V] fp32 finite; ids [dev] [n][E] int32; vals [dev]
  * [n][E] fp32.  Errors: INVALID_ARG (E > V, null pointers), UNSUPPORTED (E > 256,
