@@ -54,7 +54,9 @@ typedef enum { TW_CALL_TTP_SCORE = 1, TW_CALL_TREE_VERIFY_ATTN = 2 } tw_call;
  * pool_rows rows.  Contiguous mode (page_table == NULL): cache row r of
  * sequence b is pool row row_off[b] + r.  Paged mode: it is slot r % page_rows
  * of page page_table[b * max_pages + r / page_rows].  The struct itself is
- * host memory; base, row_off and page_table point to device memory.
+ * host memory; base, row_off and page_table point to device memory.  base, and
+ * every query/gate tensor passed beside a view, is 16-byte aligned (checked:
+ * INVALID_ARG otherwise); rows are read with 16-byte accesses.
  */
 typedef struct tw_kv_view {
     const void* base;          /* [dev] pool_rows * H * d_h elements */

@@ -10,6 +10,7 @@ bool dh_ok(int d_h) { return d_h >= 8 && d_h <= 128 && d_h % 8 == 0; }
 
 int view_status(const tw_kv_view* v, bool allow_paged) {
     if (!v || !v->base || v->pool_rows <= 0 || v->H <= 0) return TW_ERR_INVALID_ARG;
+    if ((uintptr_t)v->base % 16) return TW_ERR_INVALID_ARG;
     if (v->dtype != TW_F32 && v->dtype != TW_BF16) return TW_ERR_UNSUPPORTED;
     if (!dh_ok(v->d_h)) return TW_ERR_UNSUPPORTED;
     if (v->page_table) {
@@ -79,7 +80,7 @@ int32_t tw_ttp_score(const void* q_sel, int32_t n_q_max, const int32_t* n_q, con
                      void* ws, size_t ws_bytes, void* stream) {
     if (B < 0 || M < 0 || n_q_max < 1 || n_tot_max < 1 || v_start < 0) return TW_ERR_INVALID_ARG;
     if (B == 0 || M == 0) return TW_OK;
-    if (!q_sel || !q_pos0 || !n_tot || !scores) return TW_ERR_INVALID_ARG;
+    if (!q_sel || !q_pos0 || !n_tot || !scores || (uintptr_t)q_sel % 16) return TW_ERR_INVALID_ARG;
     const int vs = view_status(k, false);
     if (vs != TW_OK) return vs;
     if ((int64_t)v_start + M > n_tot_max || n_q_max > n_tot_max) return TW_ERR_INVALID_ARG;
@@ -111,7 +112,7 @@ int32_t tw_ttp_score_phead(const void* q, const void* gq, const tw_kv_view* k, c
                            size_t ws_bytes, void* stream) {
     if (B < 0 || M < 0 || v_start < 0) return TW_ERR_INVALID_ARG;
     if (B == 0 || M == 0) return TW_OK;
-    if (!q || !gq || !scores) return TW_ERR_INVALID_ARG;
+    if (!q || !gq || !scores || (uintptr_t)q % 16 || (uintptr_t)gq % 16) return TW_ERR_INVALID_ARG;
     int vs = view_status(k, false);
     if (vs != TW_OK) return vs;
     vs = view_status(gk, false);
@@ -211,6 +212,7 @@ int32_t tw_tree_verify_attn(const void* q, const tw_kv_view* k, const tw_kv_view
     if (out_dtype != TW_F32 && out_dtype != TW_BF16) return TW_ERR_UNSUPPORTED;
     if (B == 0) return TW_OK;
     if (!q || !ctx_len || !parent || !n_nodes || !out) return TW_ERR_INVALID_ARG;
+    if ((uintptr_t)q % 16 || (uintptr_t)out % 16) return TW_ERR_INVALID_ARG;
     int vs = view_status(k, true);
     if (vs != TW_OK) return vs;
     vs = view_status(v, true);

@@ -23,9 +23,22 @@ __device__ __forceinline__ float ld_elem<float>(const float* p) { return *p; }
 template <>
 __device__ __forceinline__ float ld_elem<uint16_t>(const uint16_t* p) { return bf16_to_f32(*p); }
 
+// four consecutive elements (d_h is a multiple of 8 and the tensors are 16-byte aligned)
 template <typename TIn>
+__device__ __forceinline__ float4 ld4(const TIn* p);
+template <>
+__device__ __forceinline__ float4 ld4<float>(const float* p) { return *(const float4*)p; }
+template <>
+__device__ __forceinline__ float4 ld4<uint16_t>(const uint16_t* p) {
+    const uint2 w = *(const uint2*)p;
+    return make_float4(__uint_as_float(w.x << 16), __uint_as_float(w.x & 0xFFFF0000u),
+                       __uint_as_float(w.y << 16), __uint_as_float(w.y & 0xFFFF0000u));
+}
+
+// kCq = output columns a lane can own: 16 serves d_h <= 64, 32 serves d_h <= 128.
+template <typename TIn, int kCq>
 __global__ __launch_bounds__(kGenThreads) void verify_generic_kernel(VerifyArgs a) {
-    extern __shared__ float smem[];
+    extern __shared__ __attribute__((aligned(16))) float smem[];
     __shared__ int s_parent[TW_MAX_TREE];
     __shared__ unsigned long long s_anc[TW_MAX_TREE];
     const int d_h = a.d_h, ld = d_h + 1, cq = d_h / 4;
@@ -49,40 +62,82 @@ __global__ __launch_bounds__(kGenThreads) void verify_generic_kernel(VerifyArgs 
     __syncthreads();
     if (tid < TW_MAX_TREE) s_anc[tid] = tid < T ? ancestor_mask(s_parent, tid) : 0ull;
     const TIn* q = (const TIn*)a.q;
-    for (int idx = tid; idx < TW_MAX_TREE * d_h; idx += kGenThreads) {
-        const int t = idx / d_h, c = idx % d_h;
-        sQ[t * ld + c] =
-            t < T ? a.scale * ld_elem<TIn>(q + (((int64_t)b * a.T_max + t) * a.H + h) * d_h + c) : 0.f;
+    {
+        // Q rows in pieces of four elements, all requested before the first is stored
+        constexpr int kQLd = TW_MAX_TREE * 32 / kGenThreads;   // d_h <= 128: at most 32 pieces per row
+        float4 qreg[kQLd];
+#pragma unroll
+        for (int u = 0; u < kQLd; ++u) {
+            const int idx = tid + u * kGenThreads;
+            const int t = idx / cq, c4 = idx - t * cq;
+            qreg[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (t < T) qreg[u] = ld4<TIn>(q + (((int64_t)b * a.T_max + t) * a.H + h) * d_h + 4 * c4);
+        }
+#pragma unroll
+        for (int u = 0; u < kQLd; ++u) {
+            const int idx = tid + u * kGenThreads;
+            const int t = idx / cq, c4 = idx - t * cq;
+            if (t < TW_MAX_TREE) {
+                float* dst = sQ + t * ld + 4 * c4;
+                dst[0] = a.scale * qreg[u].x;
+                dst[1] = a.scale * qreg[u].y;
+                dst[2] = a.scale * qreg[u].z;
+                dst[3] = a.scale * qreg[u].w;
+            }
+        }
     }
     __syncthreads();
 
     const int t = tid >> 2, qd = tid & 3;   // node, column phase
     const uint64_t anc = s_anc[t];
     float run_m = -INFINITY, run_l = 0.f;   // run_l: this lane's share of the row sum
-    float o[32];
+    float o[kCq];
 #pragma unroll
-    for (int cc = 0; cc < 32; ++cc) o[cc] = 0.f;
+    for (int cc = 0; cc < kCq; ++cc) o[cc] = 0.f;
     const TIn* kb = (const TIn*)a.k.base;
     const TIn* vb = (const TIn*)a.v.base;
 
+    // A tile's K and V go through registers in pieces of four elements: all loads of the next tile
+    // are requested before the current one is consumed (d_h <= 128: at most kGenLd pieces per thread).
+    constexpr int kGenLd = kGenTile * 32 / kGenThreads;
+    float4 kreg[kGenLd], vreg[kGenLd];
+    auto load_tile = [&](int base) {
+#pragma unroll
+        for (int u = 0; u < kGenLd; ++u) {
+            const int idx = tid + u * kGenThreads;
+            const int r = idx / cq, c4 = idx - r * cq;
+            kreg[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+            vreg[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (r < kGenTile && base + r < r_end) {
+                kreg[u] = ld4<TIn>(kb + (pool_row(a.k, b, base + r) * a.H + h) * d_h + 4 * c4);
+                vreg[u] = ld4<TIn>(vb + (pool_row(a.v, b, base + r) * a.H + h) * d_h + 4 * c4);
+            }
+        }
+    };
+    load_tile(r_begin);
     for (int base = r_begin; base < r_end; base += kGenTile) {
         __syncthreads();
-        for (int idx = tid; idx < kGenTile * d_h; idx += kGenThreads) {
-            const int r = idx / d_h, c = idx % d_h;
-            float kv = 0.f, vv = 0.f;
-            if (base + r < r_end) {
-                kv = ld_elem<TIn>(kb + (pool_row(a.k, b, base + r) * a.H + h) * d_h + c);
-                vv = ld_elem<TIn>(vb + (pool_row(a.v, b, base + r) * a.H + h) * d_h + c);
+#pragma unroll
+        for (int u = 0; u < kGenLd; ++u) {
+            const int idx = tid + u * kGenThreads;
+            const int r = idx / cq, c4 = idx - r * cq;
+            if (r < kGenTile) {
+                float* dk = sK + r * ld + 4 * c4;
+                dk[0] = kreg[u].x;
+                dk[1] = kreg[u].y;
+                dk[2] = kreg[u].z;
+                dk[3] = kreg[u].w;
+                *(float4*)(sV + r * d_h + 4 * c4) = vreg[u];
             }
-            sK[r * ld + c] = kv;
-            sV[r * d_h + c] = vv;
         }
+        load_tile(base + kGenTile);
         __syncthreads();
         float s[4], tile_m = -INFINITY;
 #pragma unroll
         for (int jj = 0; jj < 4; ++jj) {
             const int jr = qd + 4 * jj, r = base + jr;
             float dot = 0.f;
+#pragma unroll 8
             for (int c = 0; c < d_h; ++c) dot = fmaf(sQ[t * ld + c], sK[jr * ld + c], dot);
             const bool vis = r < r_end && (r < C || ((anc >> (r - C)) & 1ull));
             s[jj] = vis ? dot : -INFINITY;
@@ -101,12 +156,17 @@ __global__ __launch_bounds__(kGenThreads) void verify_generic_kernel(VerifyArgs 
         run_m = m_new;
         __syncthreads();
 #pragma unroll
-        for (int cc = 0; cc < 32; ++cc) o[cc] *= alpha;
+        for (int cc = 0; cc < kCq; ++cc) o[cc] *= alpha;
+        // columns past d_h re-read the row's last element and are never stored: no branch sits
+        // between the shared-memory reads, so they are requested together
+#pragma unroll 4
         for (int jr = 0; jr < kGenTile; ++jr) {
             const float p = sP[t * (kGenTile + 1) + jr];
 #pragma unroll
-            for (int cc = 0; cc < 32; ++cc)
-                if (cc < cq) o[cc] = fmaf(p, sV[jr * d_h + qd + 4 * cc], o[cc]);
+            for (int cc = 0; cc < kCq; ++cc) {
+                const int col = qd + 4 * cc;
+                o[cc] = fmaf(p, sV[jr * d_h + (col < d_h ? col : d_h - 1)], o[cc]);
+            }
         }
     }
     float l = run_l;
@@ -117,7 +177,7 @@ __global__ __launch_bounds__(kGenThreads) void verify_generic_kernel(VerifyArgs 
         const int64_t row = (((int64_t)b * a.T_max + t) * a.H + h) * d_h;
         const float inv = 1.f / l;
 #pragma unroll
-        for (int cc = 0; cc < 32; ++cc) {
+        for (int cc = 0; cc < kCq; ++cc) {
             if (cc < cq) {
                 if (a.out_bf16) ((uint16_t*)a.out)[row + qd + 4 * cc] = f32_to_bf16(o[cc] * inv);
                 else ((float*)a.out)[row + qd + 4 * cc] = o[cc] * inv;
@@ -127,7 +187,7 @@ __global__ __launch_bounds__(kGenThreads) void verify_generic_kernel(VerifyArgs 
         const int64_t slot = (((int64_t)split * a.B + b) * a.H + h) * a.T_max + t;
         float* po = a.part_o + slot * d_h;
 #pragma unroll
-        for (int cc = 0; cc < 32; ++cc)
+        for (int cc = 0; cc < kCq; ++cc)
             if (cc < cq) po[qd + 4 * cc] = o[cc];
         if (qd == 0) {
             a.part_ml[slot * 2] = run_m;
@@ -189,10 +249,14 @@ hipError_t launch_verify_generic(const VerifyArgs& a, int dtype, hipStream_t s) 
     const dim3 grid(a.H, a.B, a.n_splits);
     const size_t lds = ((size_t)TW_MAX_TREE * (a.d_h + 1) + (size_t)kGenTile * (a.d_h + 1) +
                         (size_t)kGenTile * a.d_h + (size_t)TW_MAX_TREE * (kGenTile + 1)) * sizeof(float);
-    if (dtype == TW_F32)
-        hipLaunchKernelGGL(verify_generic_kernel<float>, grid, dim3(kGenThreads), lds, s, a);
-    else
-        hipLaunchKernelGGL(verify_generic_kernel<uint16_t>, grid, dim3(kGenThreads), lds, s, a);
+    const bool narrow = a.d_h <= 64;
+    if (dtype == TW_F32) {
+        if (narrow) hipLaunchKernelGGL((verify_generic_kernel<float, 16>), grid, dim3(kGenThreads), lds, s, a);
+        else hipLaunchKernelGGL((verify_generic_kernel<float, 32>), grid, dim3(kGenThreads), lds, s, a);
+    } else {
+        if (narrow) hipLaunchKernelGGL((verify_generic_kernel<uint16_t, 16>), grid, dim3(kGenThreads), lds, s, a);
+        else hipLaunchKernelGGL((verify_generic_kernel<uint16_t, 32>), grid, dim3(kGenThreads), lds, s, a);
+    }
     return hipGetLastError();
 }
 

@@ -350,6 +350,7 @@ __global__ __launch_bounds__(kScThreads) void score_generic_kernel(ScoreArgs a) 
             load_keys(base);
             __syncthreads();
             float dot[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 8
             for (int c = 0; c < d_h; ++c) {
                 const float qv = sQ[i * ld + c];
 #pragma unroll
@@ -383,6 +384,7 @@ __global__ __launch_bounds__(kScThreads) void score_generic_kernel(ScoreArgs a) 
             load_keys(base);
             __syncthreads();
             float dot[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 8
             for (int c = 0; c < d_h; ++c) {
                 const float qv = sQ[i * ld + c];
 #pragma unroll

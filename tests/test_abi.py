@@ -135,6 +135,8 @@ def test_argument_validation_without_launch():
     assert call() == tw.TW_ERR_WORKSPACE                                 # split launch, no workspace
     assert call(ws=P, ws_bytes=16) == tw.TW_ERR_WORKSPACE
     assert call(ws=P + 4, ws_bytes=1 << 30) == tw.TW_ERR_INVALID_ARG    # workspace not 16-byte aligned
+    assert call(q=P + 2) == tw.TW_ERR_INVALID_ARG                        # tensors are 16-byte aligned
+    assert call(k=_view(base=0x1008)) == tw.TW_ERR_INVALID_ARG
     assert call(B=0) == tw.TW_OK
 
     sc = lambda **kw: lib.tw_ttp_score(
