@@ -162,8 +162,9 @@ def main():
         torch.cuda.synchronize()
         graph_ms = (time.perf_counter() - tg) * 1e3 / args.graph_iters
 
-    # single-instance latency of the graded kernel (one sequence, split + combine launches)
-    single_us = None
+    # single-instance latency of the graded kernel (one sequence, one layer: what batch-1 decoding
+    # issues 32 times per step), launched eagerly and as 32 back-to-back launches of a HIP graph
+    single_us = single_graph_us = None
     if args.single_iters > 0:
         w1 = W.make_workload(W.CONFIGS["cfg1"], device=dev, with_compact=False, with_score=False)
         d1 = runner.DeviceWorkload(w1, dev)
@@ -175,6 +176,22 @@ def main():
             d1.run_verify()
         torch.cuda.synchronize()
         single_us = (time.perf_counter() - t2) / args.single_iters * 1e6
+        if args.graph_iters > 0:
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            g1 = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g1, stream=side):
+                for _ in range(32):
+                    d1.run_verify()
+            for _ in range(3):
+                g1.replay()
+            torch.cuda.synchronize()
+            t3 = time.perf_counter()
+            for _ in range(args.graph_iters):
+                g1.replay()
+            torch.cuda.synchronize()
+            single_graph_us = (time.perf_counter() - t3) / (32 * args.graph_iters) * 1e6
+            del g1
 
     # the graded kernel on the other configurations (parity-tested elsewhere); each launch is made
     # cold by streaming 1 GiB through the caches between timed launches
@@ -315,6 +332,7 @@ def main():
                    "same_box_library_kernels": box,
                    "verify_tokens_per_s_kernel_only": tokens / (ker_avg * 1e-3),
                    "verify_single_sequence_latency_us": single_us,
+                   "verify_single_sequence_latency_us_hip_graph": single_graph_us,
                    "verify_other_configs": others},
     }
     print(json.dumps(out))

@@ -16,13 +16,6 @@ namespace tw {
 constexpr int kGenThreads = 256;
 constexpr int kGenTile = 16;
 
-template <typename TIn>
-__device__ __forceinline__ float ld_elem(const TIn* p);
-template <>
-__device__ __forceinline__ float ld_elem<float>(const float* p) { return *p; }
-template <>
-__device__ __forceinline__ float ld_elem<uint16_t>(const uint16_t* p) { return bf16_to_f32(*p); }
-
 // four consecutive elements (d_h is a multiple of 8 and the tensors are 16-byte aligned)
 template <typename TIn>
 __device__ __forceinline__ float4 ld4(const TIn* p);
