@@ -21,8 +21,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const float* __rest
                                                              int R, int32_t* __restrict__ kept) {
     __shared__ uint32_t s_hist[256];
     __shared__ uint32_t s_prefix, s_need;
-    __shared__ uint32_t s_wave_a[kSelThreads / 64], s_wave_b[kSelThreads / 64];
-    __shared__ uint32_t s_run_eq, s_run_sel;
+    __shared__ uint32_t s_wave_a[kSelThreads / 64];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const float* sc = scores + (int64_t)blockIdx.x * M;
     int32_t* out = kept + (int64_t)blockIdx.x * R;
@@ -34,7 +33,6 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const float* __rest
         const int m = tid + u * kSelThreads;
         keys[u] = m < M ? order_key(sc[m]) : 0u;
     }
-    auto key_at = [&](int u, int m) -> uint32_t { return KPT > 0 ? keys[u] : order_key(sc[m]); };
     const int n_iter = (M + kSelThreads - 1) / kSelThreads;
 
     if (tid == 0) {
@@ -49,19 +47,30 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const float* __rest
         __syncthreads();
         const uint32_t prefix = s_prefix, need = s_need;
         const uint32_t hi_mask = shift == 24 ? 0u : (0xFFFFFFFFu << (shift + 8));
+        // Scores of one row share most of their leading bits, so in the first passes a wavefront's
+        // keys fall into very few buckets: the lanes that share the first lane's bucket add their
+        // count with one atomic, the others add one each.
+        auto count = [&](bool valid, uint32_t key) {
+            const uint32_t bucket = (key >> shift) & 0xFFu;
+            const uint64_t vmask = __ballot(valid);
+            if (vmask == 0ull) return;
+            const int leader = __ffsll((unsigned long long)vmask) - 1;
+            const uint32_t b0 = __shfl(bucket, leader, 64);
+            const uint64_t same = __ballot(valid && bucket == b0);
+            if (lane == leader) atomicAdd(&s_hist[b0], (uint32_t)__popcll(same));
+            if (valid && bucket != b0) atomicAdd(&s_hist[bucket], 1u);
+        };
         if (KPT > 0) {
 #pragma unroll
             for (int u = 0; u < KPT; ++u) {
                 const int m = tid + u * kSelThreads;
-                if (m < M && (keys[u] & hi_mask) == prefix) atomicAdd(&s_hist[(keys[u] >> shift) & 0xFFu], 1u);
+                count(m < M && (keys[u] & hi_mask) == prefix, keys[u]);
             }
         } else {
             for (int u = 0; u < n_iter; ++u) {
                 const int m = tid + u * kSelThreads;
-                if (m < M) {
-                    const uint32_t key = key_at(u, m);
-                    if ((key & hi_mask) == prefix) atomicAdd(&s_hist[(key >> shift) & 0xFFu], 1u);
-                }
+                const uint32_t key = m < M ? order_key(sc[m]) : 0u;
+                count(m < M && (key & hi_mask) == prefix, key);
             }
         }
         __syncthreads();
@@ -85,44 +94,73 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const float* __rest
     }
     const uint32_t thr = s_prefix;   // key of the R-th largest score
     const uint32_t need = s_need;    // how many elements equal to it are kept (lowest indices)
-    if (tid == 0) {
-        s_run_eq = 0u;
-        s_run_sel = 0u;
-    }
-    __syncthreads();
+    // Output in ascending index order.  Element m = u * 256 + tid belongs to (round u, wavefront):
+    // rounds, and wavefronts inside a round, are in index order, so an element's rank among the
+    // equal keys and its output position are a count inside its wavefront (ballot) plus the totals
+    // of all earlier (round, wavefront) cells, which every wavefront scans for itself.  A row held
+    // in registers (KPT rounds) is one sweep; a longer one takes sweeps of 16 rounds, the running
+    // totals carried over.
+    constexpr int kWaves = kSelThreads / 64, kMaxCells = 64;
+    constexpr int kSweep = KPT > 0 ? KPT : kMaxCells / kWaves;
+    static_assert(kSweep * kWaves <= kMaxCells, "one lane per cell");
+    __shared__ uint32_t s_cell[kMaxCells];
     const uint64_t below = (1ull << lane) - 1ull;
-    for (int u = 0; u < n_iter; ++u) {
-        const int m = u * kSelThreads + tid;
-        bool eq = false, gt = false;
-        if (m < M) {
-            const uint32_t key = key_at(u, m);
-            eq = key == thr;
-            gt = key > thr;
-        }
-        // rank of this element among the equal keys, in index order
-        const uint64_t eq_ballot = __ballot(eq);
-        if (lane == 0) s_wave_a[wave] = (uint32_t)__popcll(eq_ballot);
-        __syncthreads();
-        uint32_t eq_rank = s_run_eq + (uint32_t)__popcll(eq_ballot & below);
-        for (int w = 0; w < wave; ++w) eq_rank += s_wave_a[w];
-        const bool sel = gt || (eq && eq_rank < need);
-        const uint64_t sel_ballot = __ballot(sel);
-        if (lane == 0) s_wave_b[wave] = (uint32_t)__popcll(sel_ballot);
-        __syncthreads();
-        uint32_t pos = s_run_sel + (uint32_t)__popcll(sel_ballot & below);
-        for (int w = 0; w < wave; ++w) pos += s_wave_b[w];
-        if (sel && pos < (uint32_t)R) out[pos] = m;
-        __syncthreads();
-        if (tid == 0) {
-            uint32_t e = 0u, s2 = 0u;
-            for (int w = 0; w < kSelThreads / 64; ++w) {
-                e += s_wave_a[w];
-                s2 += s_wave_b[w];
+    uint32_t run_eq = 0u, run_sel = 0u;   // totals of the sweeps before this one (same in every thread)
+    for (int u0 = 0; u0 < n_iter; u0 += kSweep) {
+        const int nu = min(kSweep, n_iter - u0);
+        uint64_t eq_b[kSweep], gt_b[kSweep];
+#pragma unroll
+        for (int du = 0; du < kSweep; ++du) {
+            const int u = u0 + du, m = u * kSelThreads + tid;
+            bool eq = false, gt = false;
+            if (du < nu && m < M) {
+                const uint32_t key = KPT > 0 ? keys[KPT > 0 ? du : 0] : order_key(sc[m]);   // KPT > 0: u0 == 0
+                eq = key == thr;
+                gt = key > thr;
             }
-            s_run_eq += e;
-            s_run_sel += s2;
+            eq_b[du] = __ballot(eq);
+            gt_b[du] = __ballot(gt);
+            if (lane == 0) s_cell[du * kWaves + wave] = (uint32_t)__popcll(eq_b[du]);
         }
         __syncthreads();
+        // exclusive scan of the equal-key counts over the cells, by every wavefront for itself
+        uint32_t c = lane < nu * kWaves ? s_cell[lane] : 0u, incl = c;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const uint32_t up = __shfl_up(incl, off, 64);
+            if (lane >= off) incl += up;
+        }
+        const uint32_t eq_total = __shfl(incl, 63, 64);
+        const uint32_t eq_excl = incl - c;
+        __syncthreads();   // every wavefront has read the equal-key counts
+        uint64_t sel_b[kSweep];
+#pragma unroll
+        for (int du = 0; du < kSweep; ++du) {
+            const uint32_t cell_base = __shfl(eq_excl, du * kWaves + wave, 64);
+            const uint32_t eq_rank = run_eq + cell_base + (uint32_t)__popcll(eq_b[du] & below);
+            const bool eq = (eq_b[du] >> lane) & 1ull, gt = (gt_b[du] >> lane) & 1ull;
+            sel_b[du] = __ballot(gt || (eq && eq_rank < need));
+            if (lane == 0) s_cell[du * kWaves + wave] = (uint32_t)__popcll(sel_b[du]);
+        }
+        __syncthreads();
+        c = lane < nu * kWaves ? s_cell[lane] : 0u;
+        incl = c;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const uint32_t up = __shfl_up(incl, off, 64);
+            if (lane >= off) incl += up;
+        }
+        const uint32_t sel_total = __shfl(incl, 63, 64);
+        const uint32_t sel_excl = incl - c;
+#pragma unroll
+        for (int du = 0; du < kSweep; ++du) {
+            const uint32_t pos = run_sel + __shfl(sel_excl, du * kWaves + wave, 64) +
+                                 (uint32_t)__popcll(sel_b[du] & below);
+            if (((sel_b[du] >> lane) & 1ull) && pos < (uint32_t)R) out[pos] = (u0 + du) * kSelThreads + tid;
+        }
+        run_eq += eq_total;
+        run_sel += sel_total;
+        __syncthreads();   // the cells are rewritten by the next sweep
     }
 }
 
