@@ -501,6 +501,107 @@ def test_compact_batched_ragged_pools(tw):
             assert torch.equal(got.view(torch.int32), want.view(torch.int32))
 
 
+def test_pools_larger_than_4_gib(tw):
+    # Sequences parked at the far end of two 4.7 GiB pools: byte offsets past 2^32 (row * stride past
+    # 2^31 already) in every kernel that addresses a pool.  The pools are left uninitialised except
+    # for the rows of the sequences, which also shows that nothing outside them is read into a result.
+    H, d_h, T, pr = 32, 128, 26, 16
+    pool_rows, far = 620_000, 600_000                 # 8 KB rows: the data starts 4.58 GiB into a pool
+    ctx = [100, 300]
+    scale = 1 / math.sqrt(d_h)
+    trees = [W.random_parent_tree(W.HostRng(61, b), T, 5) for b in range(2)]
+    q, k, v, off = make_case(61, 2, H, d_h, ctx, T, torch.bfloat16, trees)
+    n = k.shape[0]
+    big_k = torch.empty((pool_rows, H, d_h), dtype=torch.bfloat16, device=DEV)
+    big_v = torch.empty_like(big_k)
+    big_k[far:far + n] = k.to(DEV)
+    big_v[far:far + n] = v.to(DEV)
+    ro = _i32([o + far for o in off])
+    qd = q.to(DEV)
+
+    # verification, contiguous
+    want = oracle.tree_verify_attn(q, k, v, ctx, [T, T], trees, scale, row_off=off)
+    out = torch.full((2, T, H, d_h), float("nan"), dtype=torch.float32, device=DEV)
+    tw.tree_verify_attn(qd, tw.kv_view(big_k, ro), tw.kv_view(big_v, ro), _i32(ctx), max(ctx), _i32(trees),
+                        _i32([T, T]), scale, out, None)
+    torch.cuda.synchronize()
+    assert float((out.cpu().double() - want).abs().max()) <= ATTN_TOL
+
+    # verification, paged: the same rows reached through pages near the end of the pools
+    page0 = (far + n + pr) // pr
+    pt, nxt = [], page0
+    for b in range(2):
+        n_pages = (ctx[b] + T + pr - 1) // pr
+        ids = list(range(nxt, nxt + n_pages))[::-1]          # descending page numbers
+        nxt += n_pages
+        for j, pg in enumerate(ids):
+            r0, r1 = j * pr, min((j + 1) * pr, ctx[b] + T)
+            big_k[pg * pr:pg * pr + r1 - r0] = k[off[b] + r0:off[b] + r1].to(DEV)
+            big_v[pg * pr:pg * pr + r1 - r0] = v[off[b] + r0:off[b] + r1].to(DEV)
+        pt.append(ids + [0] * (32 - n_pages))
+    assert nxt * pr <= pool_rows
+    ptd = _i32(pt)
+    out.fill_(float("nan"))
+    tw.tree_verify_attn(qd, tw.kv_view(big_k, None, ptd, pr), tw.kv_view(big_v, None, ptd, pr), _i32(ctx),
+                        max(ctx), _i32(trees), _i32([T, T]), scale, out, None)
+    torch.cuda.synchronize()
+    assert float((out.cpu().double() - want).abs().max()) <= ATTN_TOL
+
+    # pruning score over the same keys: one-pass kernel, then the two-pass kernel with key splits
+    n_tot = [c + T for c in ctx]
+    v0, M = 5, 90
+    for n_q in ([16, 40], [70, 100]):
+        qs = W.normal(62, len(n_q) + n_q[0], (2, max(n_q), H, d_h), 1.0, torch.bfloat16)
+        pos0 = [nt - nq for nt, nq in zip(n_tot, n_q)]
+        want_s = oracle.ttp_score(qs, k, n_q, pos0, n_tot, off, v0, M, scale, True)
+        nbytes = tw.workspace_bytes(tw.TW_CALL_TTP_SCORE, 2, max(n_q), H, d_h, max(n_tot))
+        ws = torch.empty(nbytes // 4, dtype=torch.float32, device=DEV)
+        scores = torch.full((2, M), float("nan"), dtype=torch.float32, device=DEV)
+        tw.ttp_score(qs.to(DEV), tw.kv_view(big_k, row_off=ro), _i32(n_q), _i32(pos0), _i32(n_tot), max(n_tot),
+                     v0, M, scale, True, scores, ws)
+        torch.cuda.synchronize()
+        for b in range(2):
+            err = float((scores[b].cpu().double() - want_s[b]).abs().max())
+            assert err <= score_tol(H, n_q[b]), f"score error {err:.3e}"
+
+    # P-Head form: keys from one pool, their gates from the other
+    qp = W.normal(64, 1, (2, H, d_h), 1.0, torch.bfloat16)
+    gqp = W.normal(64, 2, (2, H, d_h), 1.0, torch.bfloat16)
+    want_p = oracle.ttp_score_phead(qp, gqp, k, v, off, off, v0, M, scale)
+    ws = torch.empty(tw.workspace_bytes(tw.TW_CALL_TTP_SCORE, 2, 1, H, d_h, M) // 4, dtype=torch.float32, device=DEV)
+    scores = torch.full((2, M), float("nan"), dtype=torch.float32, device=DEV)
+    tw.ttp_score_phead(qp.to(DEV), gqp.to(DEV), tw.kv_view(big_k, row_off=ro), tw.kv_view(big_v, row_off=ro), v0, M,
+                       scale, scores, ws)
+    torch.cuda.synchronize()
+    assert float(((scores.cpu().double() - want_p).abs() / (1e-6 + 2e-5 * want_p)).max()) <= 1.0
+
+    # compaction out of the far rows, and commit of an accepted path inside them
+    R = 9
+    g = torch.Generator().manual_seed(6)
+    kept = torch.stack([torch.sort(torch.randperm(M, generator=g)[:R]).values for _ in n_tot]).to(torch.int32)
+    n_keep = [nt - M + R for nt in n_tot]
+    dst_off = [0, n_keep[0]]
+    dst = [torch.zeros((sum(n_keep), H, d_h), dtype=torch.bfloat16, device=DEV) for _ in range(2)]
+    tw.ttp_compact_batched(kept.to(DEV), R, v0, M, _i32(n_tot), max(n_tot), ro, _i32(dst_off), [big_k, big_v],
+                           dst, H * d_h * 2)
+    torch.cuda.synchronize()
+    for host, d in zip((k, v), dst):
+        for b in range(2):
+            want_c = oracle.ttp_compact(kept[b], v0, M, host[off[b]:off[b] + n_tot[b]])
+            got_c = d[dst_off[b]:dst_off[b] + n_keep[b]].cpu()
+            assert torch.equal(got_c.view(torch.int16), want_c.view(torch.int16))
+    rng = W.HostRng(63, 0)
+    toks = [W.plant_tokens(rng, t, vocab=3, p_match=0.9) for t in trees]
+    n_acc, path, _ = oracle.tree_accept([x[0] for x in toks], [x[1] for x in toks], trees, [T, T])
+    new_len = torch.zeros(2, dtype=torch.int32, device=DEV)
+    tw.kv_commit(path.to(DEV), n_acc.to(DEV), [tw.kv_view(big_k, ro), tw.kv_view(big_v, ro)], _i32(ctx), new_len)
+    torch.cuda.synchronize()
+    for host, big in zip((k, v), (big_k, big_v)):
+        want_len = oracle.kv_commit(host, ctx, [T, T], path, n_acc.tolist(), row_off=off)
+        assert new_len.cpu().tolist() == want_len
+        assert torch.equal(big[far:far + n].cpu().view(torch.int16), host.view(torch.int16))
+
+
 # ----------------------------------------------------------------------------
 # ttp_score
 # ----------------------------------------------------------------------------
