@@ -450,6 +450,17 @@ def test_select_adversarial(tw, M):
         _check_select(tw, sc, R)
 
 
+def test_select_maximum_size(tw):
+    # the longest row the call accepts (2^20 scores): many sweeps of the output scan
+    M = 1 << 20
+    g = torch.Generator().manual_seed(9)
+    sc = torch.stack([torch.randint(0, 5, (M,), generator=g).float(),      # five distinct values
+                      torch.rand(M, generator=g) * 1e-3,
+                      torch.arange(M).float()])
+    for R in (1, 1000, M // 2, M):
+        _check_select(tw, sc, R)
+
+
 # ----------------------------------------------------------------------------
 # ttp_compact
 # ----------------------------------------------------------------------------
