@@ -140,6 +140,20 @@ def test_verify_split_cache_single_sequence(tw):
         check_verify(tw, q, k, v, ctx, [T], trees, 1 / math.sqrt(d_h), row_off=off)
 
 
+def test_verify_and_score_long_context_at_the_split_caps(tw):
+    # one sequence, four heads, 17000 rows: the row split of verification reaches its cap of 64
+    # workgroups per head, the key split of the score its cap of 32
+    H, d_h = 4, 128
+    for T in (26, 40):
+        ctx = [17000]
+        trees = [W.random_parent_tree(W.HostRng(15, T), T, 6)]
+        q, k, v, off = make_case(16, 1, H, d_h, ctx, T, torch.bfloat16, trees)
+        ws_bytes = tw.workspace_bytes(tw.TW_CALL_TREE_VERIFY_ATTN, 1, T, H, d_h, ctx[0] + T)
+        assert ws_bytes == 64 * H * T * (d_h + 2) * 4
+        check_verify(tw, q, k, v, ctx, [T], trees, 1 / math.sqrt(d_h), row_off=off)
+    _check_score(tw, torch.bfloat16, H, d_h, 16000, 100, [900], [16], True)
+
+
 @pytest.mark.parametrize("B,H,T", [(64, 32, 20), (40, 32, 50), (3, 8, 20), (3, 7, 50), (1, 32, 64)])
 def test_verify_wave_layouts(tw, B, H, T):
     # 4 heads / 2 heads x 2 node blocks per workgroup (many units), and one head per
