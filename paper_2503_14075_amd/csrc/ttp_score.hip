@@ -442,16 +442,21 @@ int score_key_splits(int B, int H, int n_tot_max) {
     return (int)(want < 1 ? 1 : (want > 32 ? 32 : want));
 }
 
+// Workspace layout, in floats: per-head partial sums (at most n_tot_max visual keys) | (max, sum)
+// of up to 128 scoring rows per (sequence, head, key split) | tables of the long-prompt kernel.
+// Every part starts 16-byte aligned.
+constexpr int kLongPrompt = 768;   // longest prompt the shared-memory one-pass kernel takes
 static size_t score_partial_floats(int B, int H, int n_tot_max) {
-    return ((size_t)B * H * n_tot_max + 3) / 4 * 4;   // keeps the statistics behind it 16-byte aligned
+    return ((size_t)B * H * n_tot_max + 3) / 4 * 4;
+}
+static size_t score_stats_floats(int B, int H, int n_tot_max) {
+    return (size_t)B * H * score_key_splits(B, H, n_tot_max) * 128 * 2;
 }
 
 size_t score_workspace_bytes(int B, int H, int n_q_max, int n_tot_max) {
-    (void)n_q_max;
-    // per-head partial sums (at most n_tot_max visual keys), then (max, sum) of up to 128 scoring
-    // rows per (sequence, head, key split)
-    const int ns = score_key_splits(B, H, n_tot_max);
-    return (score_partial_floats(B, H, n_tot_max) + (ns > 1 ? (size_t)B * H * ns * 128 * 2 : 0)) * sizeof(float);
+    size_t n = score_partial_floats(B, H, n_tot_max) + score_stats_floats(B, H, n_tot_max);
+    if (n_q_max <= 32 && n_tot_max > kLongPrompt) n += score_stream_workspace_floats(B, H, n_q_max, n_tot_max);
+    return n * sizeof(float);
 }
 
 template <int DH, int NB>
@@ -487,6 +492,11 @@ hipError_t launch_score(const ScoreArgs& a, int dtype, hipStream_t s) {
     hipError_t e;
     if (score_resident_supported(a, dtype)) {
         e = launch_score_resident(a, s);
+    } else if (score_stream_supported(a, dtype) && a.n_tot_max > kLongPrompt) {
+        ScoreArgs al = a;
+        al.n_splits = score_key_splits(a.B, a.H, a.n_tot_max);
+        al.stats = a.ws + score_partial_floats(a.B, a.H, a.n_tot_max);
+        e = launch_score_stream(al, al.stats + score_stats_floats(a.B, a.H, a.n_tot_max), s);
     } else if (dtype == TW_BF16 && (a.d_h == 64 || a.d_h == 128) && a.n_q_max <= 128) {
         e = a.d_h == 128 ? launch_score_mfma_rows<128>(a, s) : launch_score_mfma_rows<64>(a, s);
     } else {

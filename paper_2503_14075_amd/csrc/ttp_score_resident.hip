@@ -32,11 +32,6 @@ constexpr int kRsCpw = 3;                                  // chunks per wavefro
 constexpr int kRsMaxKeys = kRsWaves * kRsCpw * kRsChunk;   // 768
 constexpr int kRsLdsBytes = 160 * 1024;                    // LDS of a compute unit
 
-// Two weights in (0, 1] as 16-bit fixed point (v_cvt_pknorm_u16_f32): absolute step 2^-16.
-__device__ __forceinline__ uint32_t pack_unorm16(float a, float b) {
-    return __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pknorm_u16(a, b));
-}
-
 // Value of the lane's neighbour inside its group of four (DPP quad_perm control: 0xB1 swaps lanes
 // 0<->1 and 2<->3, 0x4E swaps 0<->2 and 1<->3).
 template <int CTRL>

@@ -126,6 +126,8 @@ struct ScoreArgs {
     float* scores;
     float* ws;
     float* stats = nullptr;    // per-split row statistics, inside ws (set by the launcher)
+    float* rtab = nullptr;     // long-prompt kernel: per-chunk reference maxima, inside ws
+    uint16_t* etab = nullptr;  // long-prompt kernel: per-chunk exponentials, inside ws
     int32_t n_splits = 1;
     int32_t n_q_max, n_tot_max, B, H, d_h, v_start, M, causal;
     float scale;
@@ -135,6 +137,9 @@ size_t score_workspace_bytes(int B, int H, int n_q_max, int n_tot_max);
 hipError_t launch_score(const ScoreArgs& a, int dtype, hipStream_t s);
 hipError_t launch_score_reduce(const ScoreArgs& a, hipStream_t s);
 bool score_resident_supported(const ScoreArgs& a, int dtype);
+bool score_stream_supported(const ScoreArgs& a, int dtype);
+size_t score_stream_workspace_floats(int B, int H, int n_q_max, int n_tot_max);
+hipError_t launch_score_stream(const ScoreArgs& a, float* tables, hipStream_t s);
 hipError_t launch_score_resident(const ScoreArgs& a, hipStream_t s);
 
 // --- pruning score, P-Head form ------------------------------------------------

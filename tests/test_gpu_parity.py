@@ -658,6 +658,8 @@ def _check_score(tw, dtype, H, d_h, M, v0, n_text, n_q, causal, q_std=1.0, seed=
     span_chunks = (v0 + M - 1) // 32 - v0 // 32 + 1
     one_pass = (dtype == torch.bfloat16 and d_h in (64, 128) and n_q_max <= 64 and max(n_tot) <= 768
                 and span_chunks <= (23 if n_q_max > 32 else 24) and scale > 0)
+    # long prompts with at most 32 scoring rows: the same 16-bit table, kept in global memory
+    one_pass = one_pass or (dtype == torch.bfloat16 and d_h in (64, 128) and n_q_max <= 32 and max(n_tot) > 768)
     for b in range(B):
         err = float((got[b] - want[b]).abs().max())
         tol = score_tol(H, n_q[b]) if one_pass else SCORE_TOL
@@ -678,6 +680,17 @@ def test_score_key_splits(tw):
     _check_score(tw, torch.bfloat16, 4, 64, 1000, 0, [200], [128], False, q_std=4.0)
     _check_score(tw, torch.bfloat16, 32, 128, 2880, 0, [128, 77], [16, 16], True)   # high-resolution prompt
     _check_score(tw, torch.bfloat16, 3, 128, 257, 31, [1, 600], [1, 33], True, q_std=5.0)
+
+
+@pytest.mark.parametrize("d_h", [64, 128])
+def test_score_long_prompt_one_pass(tw, d_h):
+    # more than 768 keys and at most 32 scoring rows: one read of the keys, the exponentials of the
+    # visual span parked in the workspace.  Span not chunk-aligned, ragged lengths (the short
+    # sequence never reaches the later chunks and splits), all heads of a partial head group.
+    _check_score(tw, torch.bfloat16, 6, d_h, 1500, 37, [300, 9], [32, 5], True)
+    _check_score(tw, torch.bfloat16, 32, d_h, 2880, 0, [128, 128, 100, 16], [16, 16, 16, 16], True)
+    _check_score(tw, torch.bfloat16, 3, d_h, 801, 5, [40], [17], False, q_std=5.0)
+    _check_score(tw, torch.bfloat16, 2, d_h, 1000, 0, [30, 31], [1, 30], True, scale=-1 / math.sqrt(d_h))
 
 
 @pytest.mark.parametrize("n_q", [[1, 1, 1], [8, 5, 8], [33, 64, 40], [128, 100, 65]])
