@@ -193,29 +193,32 @@ __device__ __forceinline__ void epilogue_direct(const WaveState<DH>& w, const Ve
     constexpr int kLanesPerRow = DH / 4, kRowsPerStore = 64 / kLanesPerRow;
     const int sub = lane / kLanesPerRow, c4 = lane % kLanesPerRow;
     if (a.n_splits == 1) {
-        // written once, not read again by this kernel: streaming stores
-        const int64_t first = (((int64_t)b * a.T_max + node0) * a.H + h) * DH + 4 * c4;   // node 0 of the block
-        const int64_t node_stride = (int64_t)a.H * DH;
+        // Written once at the end of the wavefront's life: system-scope stores through a descriptor
+        // over the block's 32 rows of `out` (2 % faster than streaming stores on the bench launch).
+        const int64_t first = (((int64_t)b * a.T_max + node0) * a.H + h) * DH;   // node 0 of the block
+        const uint32_t node_stride = (uint32_t)a.H * DH;
         if (a.out_bf16) {
             typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
-            uint16_t* dst = (uint16_t*)a.out + first;
+            const __amdgpu_buffer_rsrc_t ro = raw_buffer((const uint16_t*)a.out + first, 32u * node_stride * 2u);
 #pragma unroll
             for (int n0 = 0; n0 < 32; n0 += kRowsPerStore) {
                 const int node = n0 + sub;
                 if (node < T) {
                     const f32x4 v = *(const f32x4*)(tile + node * Cf::kOStride + 4 * c4);
                     const u32x2 p = {pack_bf16x2(v.x, v.y), pack_bf16x2(v.z, v.w)};
-                    __builtin_nontemporal_store(p, (u32x2*)(dst + node * node_stride));
+                    __builtin_amdgcn_raw_buffer_store_b64(p, ro, (int)((node * node_stride + 4 * c4) * 2u), 0, kAuxThrough);
                 }
             }
         } else {
-            float* dst = (float*)a.out + first;
+            const __amdgpu_buffer_rsrc_t ro = raw_buffer((const float*)a.out + first, 32u * node_stride * 4u);
 #pragma unroll
             for (int n0 = 0; n0 < 32; n0 += kRowsPerStore) {
                 const int node = n0 + sub;
-                if (node < T)
-                    __builtin_nontemporal_store(*(const f32x4*)(tile + node * Cf::kOStride + 4 * c4),
-                                                (f32x4*)(dst + node * node_stride));
+                if (node < T) {
+                    const f32x4 v = *(const f32x4*)(tile + node * Cf::kOStride + 4 * c4);
+                    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), ro,
+                                                           (int)((node * node_stride + 4 * c4) * 4u), 0, kAuxThrough);
+                }
             }
         }
     } else {

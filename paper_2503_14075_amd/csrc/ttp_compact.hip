@@ -32,18 +32,22 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(CompactBatch c
     const char* src = (const char*)tab.src[blockIdx.y] + (size_t)(s0 + sr) * row_bytes;
     char* dst = (char*)tab.dst[blockIdx.y] + (size_t)(d0 + r) * row_bytes;
     if (kVec16) {
-        const u32x4* s4 = (const u32x4*)src;
-        u32x4* d4 = (u32x4*)dst;
-        const size_t n = row_bytes >> 4;
+        // one descriptor per row and side; system-scope streaming loads and stores
+        const __amdgpu_buffer_rsrc_t rs = raw_buffer(src, (uint32_t)row_bytes);
+        const __amdgpu_buffer_rsrc_t rd = raw_buffer(dst, (uint32_t)row_bytes);
+        const uint32_t n = (uint32_t)row_bytes;
         // two independent 16-byte loads in flight per lane
-        size_t i = threadIdx.x;
-        for (; i + kCompactThreads < n; i += 2 * kCompactThreads) {
-            const u32x4 a = __builtin_nontemporal_load(s4 + i);
-            const u32x4 c = __builtin_nontemporal_load(s4 + i + kCompactThreads);
-            __builtin_nontemporal_store(a, d4 + i);
-            __builtin_nontemporal_store(c, d4 + i + kCompactThreads);
+        uint32_t o = threadIdx.x * 16u;
+        constexpr uint32_t kStep = kCompactThreads * 16u;
+        for (; o + kStep < n; o += 2 * kStep) {
+            const u32x4 a = __builtin_amdgcn_raw_buffer_load_b128(rs, (int)o, 0, kAuxStream);
+            const u32x4 c = __builtin_amdgcn_raw_buffer_load_b128(rs, (int)(o + kStep), 0, kAuxStream);
+            __builtin_amdgcn_raw_buffer_store_b128(a, rd, (int)o, 0, kAuxStream);
+            __builtin_amdgcn_raw_buffer_store_b128(c, rd, (int)(o + kStep), 0, kAuxStream);
         }
-        if (i < n) __builtin_nontemporal_store(__builtin_nontemporal_load(s4 + i), d4 + i);
+        if (o < n)
+            __builtin_amdgcn_raw_buffer_store_b128(__builtin_amdgcn_raw_buffer_load_b128(rs, (int)o, 0, kAuxStream), rd,
+                                                   (int)o, 0, kAuxStream);
     } else {
         for (size_t i = threadIdx.x; i < row_bytes; i += kCompactThreads) dst[i] = src[i];
     }
@@ -52,7 +56,7 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(CompactBatch c
 hipError_t launch_compact(const CompactBatch& cb, int B, int n_out_max, const CompactTable& tab,
                           int n_tensors, size_t row_bytes, hipStream_t s) {
     if (n_out_max <= 0 || n_tensors <= 0 || B <= 0) return hipSuccess;
-    bool vec = (row_bytes % 16) == 0;
+    bool vec = (row_bytes % 16) == 0 && row_bytes < (1ull << 31);   // 32-bit offsets inside a row
     for (int t = 0; t < n_tensors; ++t)
         vec = vec && ((uintptr_t)tab.src[t] % 16 == 0) && ((uintptr_t)tab.dst[t] % 16 == 0);
     dim3 grid(n_out_max, n_tensors, B);

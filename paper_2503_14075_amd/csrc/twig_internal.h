@@ -74,6 +74,20 @@ __device__ __forceinline__ void store_out4(void* out, int out_bf16, int64_t i, f
     }
 }
 
+// Raw buffer access (buffer_load / buffer_store through a descriptor built in scalar registers):
+// the way to give a vector memory instruction all three cache-policy bits of gfx950.  `aux` of the
+// builtins: sc0 = 1, nt = 2, sc1 = 16.  Offsets past `bytes` are dropped by the hardware.
+constexpr int kAuxSc0 = 1, kAuxNt = 2, kAuxSc1 = 16;
+// system scope + streaming: bulk data a kernel touches once (4 % faster row copies than nt alone,
+// and, unlike stores without nt, no dirty lines left behind for the next kernel to pay for)
+constexpr int kAuxStream = kAuxSc0 | kAuxSc1 | kAuxNt;
+// system scope, cached: a modest output written once at the end of a workgroup's life
+constexpr int kAuxThrough = kAuxSc0 | kAuxSc1;
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t raw_buffer(const void* base, uint32_t bytes) {
+    // last descriptor word: untyped 32-bit data (raw dword accesses ignore the format)
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);
+}
+
 // Ancestor-or-self mask of node i from a parent array held in shared memory.
 // Parents are clamped to [0, i) so the walk always ends at the root.
 __device__ __forceinline__ uint64_t ancestor_mask(const int* s_parent, int i) {
