@@ -121,6 +121,27 @@ def main():
             gbs = stage_bytes[name] / (med * 1e-3) / 1e9
             stages[name].update(algorithmic_MB=stage_bytes[name] / 1e6, GBps=gbs, frac_of_8TBps=gbs / HBM_PEAK_GBS)
 
+    # the pruning score again with only the last 8 text rows scoring (the configurations that name a
+    # row count use 8 or 16; the timed step scores with all 64 text rows, as Eq. 3 of the paper sums)
+    from paper_2503_14075_amd import binding as tw
+    q8 = dw.q_sel[:, -8:].contiguous()
+    n8 = torch.full((args.batch,), 8, dtype=torch.int32, device=dev)
+    pos8 = (dw.q_pos0 + dw.n_q - 8).to(torch.int32)
+    ev8 = []
+    for i in range(12):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        tw.ttp_score(q8, dw.k_score_view, n8, pos8, dw.n_tot, dw.n_tot_max, 0, cfg.M, cfg.scale, True, dw.scores,
+                     dw.score_ws)
+        e1.record()
+        ev8.append((e0, e1))
+    torch.cuda.synchronize()
+    t8 = sorted(x.elapsed_time(y) for x, y in ev8[2:])
+    b8 = sum(n * row + 8 * row + 4 * cfg.M for n in w.n_tot)
+    stages["ttp_score_last_8_rows"] = {"us_median": t8[len(t8) // 2] * 1e3, "algorithmic_MB": b8 / 1e6,
+                                       "GBps": b8 / (t8[len(t8) // 2] * 1e-3) / 1e9}
+    dw.run_score()   # leave the scores of the timed configuration in place
+
     # tree_verify_attn with bf16 output (what a following bf16 projection consumes; half the bytes
     # written).  The headline and the parity bar use the fp32 output.
     verify_bf16_us = None
