@@ -941,11 +941,14 @@ def test_bench_launch_configuration_sampled(runner):
         assert float((out[b].double() - want_o).abs().max()) <= ATTN_TOL
 
 
-def test_step_replays_from_a_hip_graph(runner):
+@pytest.mark.parametrize("name", ["cfg1", "cfg4"])
+def test_step_replays_from_a_hip_graph(runner, name):
     # the library only enqueues kernels on the caller's stream (no allocation, no synchronisation, no
     # memset nodes), so a whole step can be captured once and replayed; every replay must reproduce
-    # the eager results bit for bit, with other work on the device between the replays
-    cfg = W.replicate(W.CONFIGS["cfg1"], 4)
+    # the eager results bit for bit, with other work on the device between the replays.  cfg4 takes
+    # the multi-launch paths: key-split score with its tables in the workspace, row-split
+    # verification with the merge launch.
+    cfg = W.replicate(W.CONFIGS["cfg1"], 4) if name == "cfg1" else W.CONFIGS["cfg4"]
     w = W.make_workload(cfg)
     dw = runner.DeviceWorkload(w, DEV)
     outs = lambda: [dw.scores, dw.kept, dw.out, dw.n_acc, dw.path, dw.bonus] + list(dw.compact_dst)
