@@ -411,23 +411,27 @@ __global__ __launch_bounds__(kScThreads) void score_generic_kernel(ScoreArgs a) 
     }
 }
 
-// scores[b][m] = mean over heads and scoring rows; heads are added in index order.
+// scores[b][m] = mean over heads and scoring rows; the planes of partial sums (one per head, and
+// per half of the scoring rows when they were taken in two launches) are added in index order.
 __global__ __launch_bounds__(256) void score_reduce_kernel(ScoreArgs a) {
     const int b = blockIdx.y, m = blockIdx.x * 256 + threadIdx.x;
     if (m >= a.M) return;
-    int n_q = a.n_q ? a.n_q[b] : a.n_q_max;
-    n_q = n_q < 1 ? 1 : (n_q > a.n_q_max ? a.n_q_max : n_q);
-    const float* p = a.ws + (int64_t)b * a.H * a.M + m;
+    const int q_rows = a.q_stride ? a.q_stride : a.n_q_max;
+    int n_q = a.n_q ? a.n_q[b] : q_rows;
+    n_q = n_q < 1 ? 1 : (n_q > q_rows ? q_rows : n_q);
     float acc = 0.f;
-    int h = 0;
-    for (; h + 8 <= a.H; h += 8) {   // eight independent loads in flight, added in head order
-        float v[8];
+    for (int half = 0; half < a.n_halves; ++half) {
+        const float* p = a.ws + ((int64_t)half * a.B + b) * a.H * a.M + m;
+        int h = 0;
+        for (; h + 8 <= a.H; h += 8) {   // eight independent loads in flight, added in head order
+            float v[8];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) v[u] = p[(int64_t)(h + u) * a.M];
+            for (int u = 0; u < 8; ++u) v[u] = p[(int64_t)(h + u) * a.M];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) acc += v[u];
+            for (int u = 0; u < 8; ++u) acc += v[u];
+        }
+        for (; h < a.H; ++h) acc += p[(int64_t)h * a.M];
     }
-    for (; h < a.H; ++h) acc += p[(int64_t)h * a.M];
     a.scores[(int64_t)b * a.M + m] = acc / ((float)a.H * (float)n_q);
 }
 
@@ -446,15 +450,17 @@ int score_key_splits(int B, int H, int n_tot_max) {
 // of up to 128 scoring rows per (sequence, head, key split) | tables of the long-prompt kernel.
 // Every part starts 16-byte aligned.
 constexpr int kLongPrompt = 768;   // longest prompt the shared-memory one-pass kernel takes
-static size_t score_partial_floats(int B, int H, int n_tot_max) {
-    return ((size_t)B * H * n_tot_max + 3) / 4 * 4;
+static size_t score_partial_floats(int B, int H, int n_tot_max, int n_q_max = 0) {
+    // two planes per head when 65..128 scoring rows may be taken in two launches
+    const size_t planes = n_q_max > 64 && n_tot_max <= kLongPrompt ? 2 : 1;
+    return (planes * B * H * n_tot_max + 3) / 4 * 4;
 }
 static size_t score_stats_floats(int B, int H, int n_tot_max) {
     return (size_t)B * H * score_key_splits(B, H, n_tot_max) * 128 * 2;
 }
 
 size_t score_workspace_bytes(int B, int H, int n_q_max, int n_tot_max) {
-    size_t n = score_partial_floats(B, H, n_tot_max) + score_stats_floats(B, H, n_tot_max);
+    size_t n = score_partial_floats(B, H, n_tot_max, n_q_max) + score_stats_floats(B, H, n_tot_max);
     if (n_q_max <= 32 && n_tot_max > kLongPrompt) n += score_stream_workspace_floats(B, H, n_q_max, n_tot_max);
     return n * sizeof(float);
 }
@@ -464,7 +470,7 @@ static hipError_t launch_score_mfma(const ScoreArgs& a0, hipStream_t s) {
     ScoreArgs a = a0;
     const size_t lds = 4 * (size_t)ScCfg<DH>::kWaveLds;
     a.n_splits = score_key_splits(a.B, a.H, a.n_tot_max);
-    a.stats = a.ws + score_partial_floats(a.B, a.H, a.n_tot_max);
+    a.stats = a.ws + score_partial_floats(a.B, a.H, a.n_tot_max, a.n_q_max);
     const dim3 grid((a.H + 3) / 4, a.B, a.n_splits);
     if (a.n_splits == 1) {
         hipLaunchKernelGGL((score_mfma_kernel<DH, NB, 0>), grid, dim3(kScMfThreads), lds, s, a);
@@ -490,8 +496,23 @@ hipError_t launch_score_reduce(const ScoreArgs& a, hipStream_t s) {
 hipError_t launch_score(const ScoreArgs& a, int dtype, hipStream_t s) {
     if (a.B == 0 || a.M == 0) return hipSuccess;
     hipError_t e;
+    ScoreArgs lo = a;   // rows 0..63 of a 65..128-row request
+    lo.n_q_max = 64;
+    lo.q_stride = a.n_q_max;
     if (score_resident_supported(a, dtype)) {
         e = launch_score_resident(a, s);
+    } else if (a.n_q_max > 64 && a.n_q_max <= 128 && score_resident_supported(lo, dtype)) {
+        // the shared-memory one-pass kernel twice: rows 0..63, then rows 64.. into a second plane
+        ScoreArgs hi = lo;
+        hi.row0 = 64;
+        hi.n_q_max = a.n_q_max - 64;
+        hi.ws = a.ws + (size_t)a.B * a.H * a.M;
+        e = launch_score_resident(lo, s);
+        if (e == hipSuccess) e = launch_score_resident(hi, s);
+        if (e != hipSuccess) return e;
+        ScoreArgs all = a;
+        all.n_halves = 2;
+        return launch_score_reduce(all, s);
     } else if (score_stream_supported(a, dtype) && a.n_tot_max > kLongPrompt) {
         ScoreArgs al = a;
         al.n_splits = score_key_splits(a.B, a.H, a.n_tot_max);

@@ -97,11 +97,15 @@ __global__ __launch_bounds__(kRsThreads, 2) void score_resident_kernel(ScoreArgs
         PairInfo p;
         p.b = __builtin_amdgcn_readfirstlane(pr / a.H);
         p.h = __builtin_amdgcn_readfirstlane(pr - p.b * a.H);
-        int n_q = a.n_q ? ((ctab)a.n_q)[p.b] : a.n_q_max;
-        p.n_q = n_q < 1 ? 1 : (n_q > a.n_q_max ? a.n_q_max : n_q);
+        // rows of the sequence that fall into this launch's window (none: every row is masked out
+        // and the pair's partial sums come out as zeros)
+        const int q_rows = a.q_stride ? a.q_stride : a.n_q_max;
+        int n_q = a.n_q ? ((ctab)a.n_q)[p.b] : q_rows;
+        n_q = (n_q < 1 ? 1 : (n_q > q_rows ? q_rows : n_q)) - a.row0;
+        p.n_q = n_q < 0 ? 0 : (n_q > a.n_q_max ? a.n_q_max : n_q);
         int n_tot = ((ctab)a.n_tot)[p.b];
         p.n_tot = n_tot < 0 ? 0 : (n_tot > a.n_tot_max ? a.n_tot_max : n_tot);
-        p.pos0 = ((ctab)a.q_pos0)[p.b];
+        p.pos0 = ((ctab)a.q_pos0)[p.b] + a.row0;
         p.row0 = (int64_t)((ctab)a.k.row_off)[p.b];
         return p;
     };
@@ -144,8 +148,9 @@ __global__ __launch_bounds__(kRsThreads, 2) void score_resident_kernel(ScoreArgs
         for (int u = 0; u < kQLoads; ++u) {
             const int piece = t + u * kRsThreads;
             const int i = piece / Cf::kPieces, col = piece % Cf::kPieces;
-            const int ic = i < p.n_q ? i : p.n_q - 1;
-            const uint16_t* sbase = qb + ((int64_t)p.b * a.n_q_max * a.H + p.h) * DH;   // scalar part
+            const int ic = a.row0 + (i < p.n_q ? i : (p.n_q > 0 ? p.n_q - 1 : 0));
+            const uint16_t* sbase =
+                qb + ((int64_t)p.b * (a.q_stride ? a.q_stride : a.n_q_max) * a.H + p.h) * DH;   // scalar part
             qn[u] = __builtin_nontemporal_load((const u32x4*)(sbase + (uint32_t)(ic * a.H * DH + 8 * col)));
         }
     };

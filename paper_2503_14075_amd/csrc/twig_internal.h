@@ -143,6 +143,10 @@ struct ScoreArgs {
     float* rtab = nullptr;     // long-prompt kernel: per-chunk reference maxima, inside ws
     uint16_t* etab = nullptr;  // long-prompt kernel: per-chunk exponentials, inside ws
     int32_t n_splits = 1;
+    // Scoring rows taken in two launches (rows 0..63, then the rest) by the shared-memory one-pass
+    // kernel: a launch covers rows row0 .. row0 + n_q_max - 1 of the q_stride rows that q_sel holds
+    // per sequence (q_stride == 0: n_q_max), and n_halves partial planes are added at the end.
+    int32_t row0 = 0, q_stride = 0, n_halves = 1;
     int32_t n_q_max, n_tot_max, B, H, d_h, v_start, M, causal;
     float scale;
 };

@@ -656,7 +656,7 @@ def _check_score(tw, dtype, H, d_h, M, v0, n_text, n_q, causal, q_std=1.0, seed=
     # the documented reach of the one-pass kernel (16-bit stored exponentials); the other kernels
     # keep fp32 throughout and are held to the flat bar
     span_chunks = (v0 + M - 1) // 32 - v0 // 32 + 1
-    one_pass = (dtype == torch.bfloat16 and d_h in (64, 128) and n_q_max <= 64 and max(n_tot) <= 768
+    one_pass = (dtype == torch.bfloat16 and d_h in (64, 128) and n_q_max <= 128 and max(n_tot) <= 768
                 and span_chunks <= (23 if n_q_max > 32 else 24) and scale > 0)
     # long prompts with at most 32 scoring rows: the same 16-bit table, kept in global memory
     one_pass = one_pass or (dtype == torch.bfloat16 and d_h in (64, 128) and n_q_max <= 32 and max(n_tot) > 768)
