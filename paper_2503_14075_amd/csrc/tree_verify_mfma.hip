@@ -378,7 +378,7 @@ struct SeqAddr {
     }
     __device__ __forceinline__ int page(const VerifyArgs& a, int r) const {
         r = r < last_row ? r : last_row;
-        int pi = r / a.k.page_rows;
+        int pi = a.k.page_shift >= 0 ? r >> a.k.page_shift : r / a.k.page_rows;
         pi = pi < a.k.max_pages ? pi : a.k.max_pages - 1;
         return ptab[pi];
     }
@@ -399,7 +399,8 @@ struct SeqAddr {
         if (PAGED) {
             int row = base + r;
             row = row < last_row ? row : last_row;
-            int64_t prow = (int64_t)page * a.k.page_rows + (row % a.k.page_rows);
+            const int slot = a.k.page_shift >= 0 ? row & (a.k.page_rows - 1) : row % a.k.page_rows;
+            int64_t prow = (int64_t)page * a.k.page_rows + slot;
             const int64_t last_pool = a.k.pool_rows - 1;
             prow = prow < 0 ? 0 : (prow > last_pool ? last_pool : prow);
             return (const u32x4*)(c.base + (uint64_t)(uint32_t)prow * stride + 16 * col);
@@ -542,13 +543,21 @@ __global__ __launch_bounds__(kMfThreads, 2) void verify_mfma_pair_kernel(VerifyA
     const unsigned char* seq_base = blk == 0 ? ad.k_seq : ad.v_seq;
 
     u32x4 pld[2][Cf::kLoads];
+    // Paged caches: the pages of the chunk that a slot takes next are looked up when the slot's
+    // current chunk is issued (four chunks ahead of its use), so data loads never wait on a table.
+    int pg[2][PAGED ? Cf::kLoads : 1];
+    auto lookup_pages = [&](int base, int slot) {
+        if (PAGED) {
+#pragma unroll
+            for (int j = 0; j < Cf::kLoads; ++j) pg[slot][j] = ad.page(a, base + ld_row + Cf::kRowsPerLoad * j);
+        }
+    };
     auto issue_loads = [&](int base, int slot) {
         const ChunkAddr cc = ad.chunk(seq_base, base);
 #pragma unroll
         for (int j = 0; j < Cf::kLoads; ++j) {
             const int r = ld_row + Cf::kRowsPerLoad * j;
-            const int page = PAGED ? ad.page(a, base + r) : 0;
-            pld[slot][j] = __builtin_nontemporal_load(ad.at(a, cc, base, r, ld_col, page));   // streamed once
+            pld[slot][j] = __builtin_nontemporal_load(ad.at(a, cc, base, r, ld_col, PAGED ? pg[slot][j] : 0));   // streamed once
         }
     };
     auto stage_chunk = [&](int slot, unsigned char* buf) {
@@ -560,8 +569,12 @@ __global__ __launch_bounds__(kMfThreads, 2) void verify_mfma_pair_kernel(VerifyA
     const int n_chunks = (sq.r_end - sq.r_begin + kChunk - 1) / kChunk;
     const int n_iter = (n_chunks + n_phase - 1) / n_phase;   // the same for every wavefront of the workgroup
     const int first = sq.r_begin + kChunk * phase;
+    lookup_pages(first, 0);
+    lookup_pages(first + step, 1);
     issue_loads(first, 0);
     issue_loads(first + step, 1);
+    lookup_pages(first + 2 * step, 0);
+    lookup_pages(first + 3 * step, 1);
     // two chunks are in flight; now the tree masks and the Q fragments
     tree_masks(a, b, sq.T, tid, s_parent, s_anc);
     WaveState<DH> w;
@@ -574,6 +587,7 @@ __global__ __launch_bounds__(kMfThreads, 2) void verify_mfma_pair_kernel(VerifyA
             unsigned char* buf = stage + half * Cf::kStage;
             stage_chunk(half, buf);
             issue_loads(base + 2 * step, half);
+            lookup_pages(base + 4 * step, half);
             __syncthreads();   // the partner's half of the chunk is staged; the other buffer is free again
             if (active && it + half < n_iter && base < sq.r_end)
                 process_chunk<DH>(w, buf, buf + kChunk * Cf::kKStride, base, sq.C, sq.n_rows, sl2, g, li);

@@ -15,6 +15,7 @@ struct KvDev {
     const int32_t* page_table;
     int64_t pool_rows;
     int32_t max_pages, page_rows;
+    int32_t page_shift;   // log2(page_rows) when that is a power of two, else -1
     int32_t H, d_h;
 };
 
@@ -26,6 +27,9 @@ inline KvDev to_dev(const tw_kv_view& v) {
     d.pool_rows = v.pool_rows;
     d.max_pages = v.max_pages;
     d.page_rows = v.page_rows > 0 ? v.page_rows : 1;
+    d.page_shift = -1;
+    for (int sh = 0; sh < 31; ++sh)
+        if (d.page_rows == (1 << sh)) d.page_shift = sh;
     d.H = v.H;
     d.d_h = v.d_h;
     return d;
