@@ -39,9 +39,10 @@ inline KvDev to_dev(const tw_kv_view& v) {
 __device__ __forceinline__ int64_t pool_row(const KvDev& kv, int b, int r) {
     int64_t row;
     if (kv.page_table) {
-        int pi = r / kv.page_rows;
+        int pi = kv.page_shift >= 0 ? r >> kv.page_shift : r / kv.page_rows;
+        const int slot = kv.page_shift >= 0 ? r & (kv.page_rows - 1) : r % kv.page_rows;
         pi = pi < kv.max_pages ? pi : kv.max_pages - 1;
-        row = (int64_t)kv.page_table[(int64_t)b * kv.max_pages + pi] * kv.page_rows + (r % kv.page_rows);
+        row = (int64_t)kv.page_table[(int64_t)b * kv.max_pages + pi] * kv.page_rows + slot;
     } else {
         row = (int64_t)kv.row_off[b] + r;
     }

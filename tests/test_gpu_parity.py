@@ -200,6 +200,20 @@ def test_verify_paged_pool(tw):
                  page_table=w.page_table, page_rows=pr)
 
 
+@pytest.mark.parametrize("page_rows", [1, 12, 64])
+@pytest.mark.parametrize("T", [20, 50])
+def test_verify_page_sizes(tw, page_rows, T):
+    # page sizes that are and are not powers of two (the row -> (page, slot) split is a shift and a
+    # mask for the former, a division for the latter), on the matrix-core and the fp32 kernels
+    for dtype, d_h in ((torch.bfloat16, 128), (torch.float32, 64)):
+        cfg = W.Config(**{**W.CONFIGS["cfg3"].__dict__, "name": "pages", "seed": 90 + page_rows + T, "B": 3, "H": 4,
+                          "d_h": d_h, "hidden": 4 * d_h, "T": T, "P": (0, 150), "tree": ("random", 6),
+                          "page_rows": page_rows, "dtype": "bf16" if dtype == torch.bfloat16 else "f32"})
+        w = W.make_workload(cfg, with_compact=False, with_score=False)
+        check_verify(tw, w.q_tree, w.k_pool, w.v_pool, w.ctx_len, w.n_nodes, w.parent, cfg.scale,
+                     tol=ATTN_TOL if dtype == torch.bfloat16 else 2e-5, page_table=w.page_table, page_rows=page_rows)
+
+
 @pytest.mark.parametrize("seed", range(8))
 def test_verify_random_shapes(tw, seed):
     # ragged everything, contiguous and paged pools, both head sizes, trees up to 64 nodes
