@@ -413,7 +413,7 @@ struct SeqAddr {
 // ---------------------------------------------------------------------------------------------
 // T <= 32: every wavefront stages its own chunks (K and V) in a private LDS area; no workgroup
 // barrier inside the loop.  K and V share one row mapping (same row_off / page_table).
-// STREAM: the loads carry the non-temporal hint (each byte is used once).
+// The K/V loads carry the non-temporal hint (each byte is used once).
 // ---------------------------------------------------------------------------------------------
 template <int DH, bool PAGED>
 __global__ __launch_bounds__(kMfThreads, 2) void verify_mfma_kernel(VerifyArgs a) {
