@@ -103,7 +103,8 @@ __global__ __launch_bounds__(kScMfThreads, (NB <= 2 ? 2 : 1)) void score_mfma_ke
             r = r < end - 1 ? r : end - 1;   // past the end: re-read the last key (cached), masked below
             int64_t prow = row0 + r;
             prow = prow < 0 ? 0 : (prow > last_pool_row ? last_pool_row : prow);
-            pk[j] = *(const u32x4*)(kbase + prow * pool_stride);
+            // streaming hint on both passes: 13-23 % faster on 4..64 prompts of 3008 keys
+            pk[j] = __builtin_nontemporal_load((const u32x4*)(kbase + prow * pool_stride));
         }
     };
     auto stage = [&]() {
