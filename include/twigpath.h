@@ -165,7 +165,9 @@ int32_t tw_ttp_compact(const int32_t* kept, int32_t R, int32_t v_start, int32_t 
  * src_row_off[b] .. +n_tot[b] and destination rows dst_row_off[b] ..
  * +n_tot[b]-M+R of every (src[t], dst[t]) pair; kept is [dev] [B][R];
  * n_tot, src_row_off, dst_row_off are [dev] [B]; n_tot_max is a host upper bound
- * of n_tot.  Precondition on device contents: v_start + M <= n_tot[b] <= n_tot_max.
+ * of n_tot.  Precondition on device contents: v_start + M <= n_tot[b] <= n_tot_max
+ * (a length outside that range is moved into it; the row offsets say where the
+ * caller's rows are and are taken as they come).
  * Errors as tw_ttp_compact, plus UNSUPPORTED for B > 65535.
  */
 int32_t tw_ttp_compact_batched(const int32_t* kept, int32_t R, int32_t v_start, int32_t M,

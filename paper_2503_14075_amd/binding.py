@@ -115,8 +115,10 @@ def kv_view(pool: torch.Tensor, row_off: Optional[torch.Tensor] = None,
             page_table: Optional[torch.Tensor] = None, page_rows: int = 0) -> KvView:
     """pool [rows][H][d_h]; row_off int32 [B] (contiguous) or page_table int32 [B][max_pages]."""
     rows, H, d_h = pool.shape
-    return KvView(_ptr(pool), _dtype_code(pool), H, d_h, rows, _ptr(row_off), _ptr(page_table),
+    view = KvView(_ptr(pool), _dtype_code(pool), H, d_h, rows, _ptr(row_off), _ptr(page_table),
                   0 if page_table is None else page_table.shape[1], page_rows)
+    view._keep = (pool, row_off, page_table)   # the struct holds raw pointers: keep their tensors alive with it
+    return view
 
 
 def version() -> int:

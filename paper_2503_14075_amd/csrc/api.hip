@@ -188,7 +188,7 @@ int32_t tw_ttp_compact_batched(const int32_t* kept, int32_t R, int32_t v_start, 
         return TW_ERR_INVALID_ARG;
     for (int t = 0; t < n_tensors; ++t)
         if (!src[t] || !dst[t]) return TW_ERR_INVALID_ARG;
-    const CompactBatch cb = {kept, n_tot, src_row_off, dst_row_off, 0, R, v_start, M};
+    const CompactBatch cb = {kept, n_tot, src_row_off, dst_row_off, n_tot_max, R, v_start, M};
     return compact_tables(cb, B, n_tot_max - M + R, src, dst, n_tensors, row_bytes, (hipStream_t)stream);
 }
 

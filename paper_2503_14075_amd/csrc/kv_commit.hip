@@ -25,7 +25,8 @@ __global__ __launch_bounds__(kCommitThreads) void kv_commit_kernel(CommitArgs a)
     const size_t col = ((size_t)blockIdx.x * kCommitThreads + threadIdx.x) * 16;
     int n = a.n_acc[b];
     n = n < 0 ? 0 : (n > a.T_max - 1 ? a.T_max - 1 : n);
-    const int C = a.ctx_len[b] < 0 ? 0 : a.ctx_len[b];
+    // held where C + T_max cannot wrap; rows past the pool are clamped by pool_row
+    const int C = a.ctx_len[b] < 0 ? 0 : (a.ctx_len[b] > (1 << 30) ? (1 << 30) : a.ctx_len[b]);
     if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0 && a.new_ctx_len) a.new_ctx_len[b] = C + 1 + n;
     if (col >= row_bytes) return;
     char* base = (char*)kv.base;

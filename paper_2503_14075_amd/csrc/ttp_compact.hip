@@ -26,7 +26,13 @@ template <bool kVec16>
 __global__ __launch_bounds__(kCompactMaxThreads) void compact_kernel(CompactBatch cb, CompactTable tab,
                                                                   size_t row_bytes) {
     const int r = blockIdx.x, b = blockIdx.z;
-    const int n_tot = cb.n_tot ? cb.n_tot[b] : cb.n_tot_all;
+    // a sequence length from device memory is held between the end of the visual span and the host's
+    // upper bound, so every row index below stays inside [0, n_tot_all) of the sequence
+    int n_tot = cb.n_tot_all;
+    if (cb.n_tot) {
+        n_tot = cb.n_tot[b];
+        n_tot = n_tot < cb.v_start + cb.M ? cb.v_start + cb.M : (n_tot > cb.n_tot_all ? cb.n_tot_all : n_tot);
+    }
     if (r >= n_tot - cb.M + cb.R) return;
     const int64_t s0 = cb.src_off ? cb.src_off[b] : 0, d0 = cb.dst_off ? cb.dst_off[b] : 0;
     int sr = compact_src_row(cb.kept + (int64_t)b * cb.R, cb.R, cb.v_start, cb.M, r);

@@ -37,6 +37,7 @@ inline KvDev to_dev(const tw_kv_view& v) {
 
 // Pool row of cache row r of sequence b, clamped into the pool.
 __device__ __forceinline__ int64_t pool_row(const KvDev& kv, int b, int r) {
+    r = r < 0 ? 0 : r;   // a row index made from unchecked device contents may have wrapped
     int64_t row;
     if (kv.page_table) {
         int pi = kv.page_shift >= 0 ? r >> kv.page_shift : r / kv.page_rows;
@@ -191,7 +192,7 @@ struct CompactBatch {
     const int32_t* n_tot;    // [B] or null
     const int32_t* src_off;  // [B] first source row of sequence b, or null
     const int32_t* dst_off;  // [B] first destination row, or null
-    int32_t n_tot_all, R, v_start, M;
+    int32_t n_tot_all, R, v_start, M;   // n_tot_all: the length (n_tot null) or its upper bound
 };
 hipError_t launch_compact(const CompactBatch& cb, int B, int n_out_max, const CompactTable& tab,
                           int n_tensors, size_t row_bytes, hipStream_t s);

@@ -540,6 +540,107 @@ def test_compact_batched_ragged_pools(tw):
             assert torch.equal(got.view(torch.int32), want.view(torch.int32))
 
 
+def test_violated_device_preconditions_stay_in_bounds(tw):
+    # Lengths, offsets, parents, page ids, kept indices and paths that break the documented
+    # preconditions: the kernels move every index into the buffers the arguments describe, so the
+    # calls complete, nothing outside the outputs is written, and a well-formed sequence in the
+    # same batch still gets the exact result.  (Results of the malformed sequences are unspecified.)
+    H, d_h, T, pr = 4, 128, 20, 16
+    scale = 1 / math.sqrt(d_h)
+    ctx = [40, 70, 90]
+    trees = [W.random_parent_tree(W.HostRng(81, b), T, 5) for b in range(3)]
+    q, k, v, off = make_case(82, 3, H, d_h, ctx, T, torch.bfloat16, trees)
+    want = oracle.tree_verify_attn(q, k, v, ctx, [T] * 3, trees, scale, row_off=off)
+    big, neg = 2 ** 31 - 1, -(2 ** 31)
+    bad_parent = [[big, neg, 7, -3] * 5, [5] * T, trees[2]]
+    kd, vd, qd = k.to(DEV), v.to(DEV), q.to(DEV)
+    out = torch.full((3, T + 2, H, d_h), float("nan"), dtype=torch.float32, device=DEV)   # two guard rows each
+    for n_nodes, ctx_len, row_off in (([0, 100, T], [-7, 10 ** 9, ctx[2]], [-3, big, off[2]]),
+                                      ([neg, big, T], [big, neg, ctx[2]], [neg, 12345678, off[2]])):
+        o = torch.full((3, T, H, d_h), float("nan"), dtype=torch.float32, device=DEV)
+        ro = _i32(row_off)
+        tw.tree_verify_attn(qd, tw.kv_view(kd, ro), tw.kv_view(vd, ro), _i32(ctx_len), max(ctx), _i32(bad_parent),
+                            _i32(n_nodes), scale, o, None)
+        torch.cuda.synchronize()
+        assert float((o[2].cpu().double() - want[2]).abs().max()) <= ATTN_TOL
+    del out
+    # paged: page ids from nowhere for the first two sequences
+    n_pages = [(c + T + pr - 1) // pr for c in ctx]
+    pk = torch.zeros((sum(n_pages) * pr, H, d_h), dtype=torch.bfloat16)
+    pv = torch.zeros_like(pk)
+    pt, nxt = [], 0
+    for b in range(3):
+        ids = list(range(nxt, nxt + n_pages[b]))
+        nxt += n_pages[b]
+        for j, pg in enumerate(ids):
+            r0, r1 = j * pr, min((j + 1) * pr, ctx[b] + T)
+            pk[pg * pr:pg * pr + r1 - r0] = k[off[b] + r0:off[b] + r1]
+            pv[pg * pr:pg * pr + r1 - r0] = v[off[b] + r0:off[b] + r1]
+        pt.append(ids + [0] * (max(n_pages) - len(ids)))
+    pt[0] = [big, neg, -1, 10 ** 6][:max(n_pages)] + [big] * (max(n_pages) - 4)
+    pt[1] = [neg] * max(n_pages)
+    pkd, pvd, ptd = pk.to(DEV), pv.to(DEV), _i32(pt)
+    o = torch.full((3, T, H, d_h), float("nan"), dtype=torch.float32, device=DEV)
+    tw.tree_verify_attn(qd, tw.kv_view(pkd, None, ptd, pr), tw.kv_view(pvd, None, ptd, pr), _i32([big, 5, ctx[2]]),
+                        max(ctx), _i32(bad_parent), _i32([T, T, T]), scale, o, None)
+    torch.cuda.synchronize()
+    assert float((o[2].cpu().double() - want[2]).abs().max()) <= ATTN_TOL
+
+    # pruning score: lengths, row counts, positions and offsets from nowhere
+    n_tot = [c + T for c in ctx]
+    v0, M = 3, 30
+    n_q = [9, 9, 9]
+    qs = W.normal(83, 1, (3, 9, H, d_h), 1.0, torch.bfloat16)
+    pos0 = [nt - 9 for nt in n_tot]
+    want_s = oracle.ttp_score(qs, k, n_q, pos0, n_tot, off, v0, M, scale, True)
+    ws = torch.empty(tw.workspace_bytes(tw.TW_CALL_TTP_SCORE, 3, 9, H, d_h, max(n_tot)) // 4, dtype=torch.float32,
+                     device=DEV)
+    sc = torch.full((3, M), float("nan"), dtype=torch.float32, device=DEV)
+    ro = _i32([neg, big, off[2]])          # a view only holds pointers: the tensors must stay alive
+    tw.ttp_score(qs.to(DEV), tw.kv_view(kd, row_off=ro), _i32([0, 1000, 9]),
+                 _i32([big, neg, pos0[2]]), _i32([-1, 10 ** 9, n_tot[2]]), max(n_tot), v0, M, scale, True, sc, ws)
+    torch.cuda.synchronize()
+    assert float((sc[2].cpu().double() - want_s[2]).abs().max()) <= score_tol(H, 9)
+
+    # compaction: kept indices and lengths from nowhere (the row offsets are the caller's own)
+    R = 5
+    src = torch.arange(3 * 120 * 8, dtype=torch.float32).view(3 * 120, 8)
+    n_tot_c = [100, 100, 100]
+    dst = torch.full((3 * 80 + 4, 8), -1.0, dtype=torch.float32, device=DEV)       # four guard rows at the end
+    kept = torch.tensor([[big, neg, -1, 10 ** 6, 3], [0, 0, 0, 0, 0], [1, 4, 9, 16, 25]], dtype=torch.int32)
+    tw.ttp_compact_batched(kept.to(DEV), R, v0, M, _i32([neg, big, 100]), 100, _i32([0, 120, 240]),
+                           _i32([0, 80, 160]), [src.to(DEV)], [dst], 32)
+    torch.cuda.synchronize()
+    want_c = oracle.ttp_compact(kept[2], v0, M, src[240:340])
+    assert torch.equal(dst[160:160 + 75].cpu(), want_c)
+    assert bool((dst[240:] == -1).all())
+
+    # acceptance walk and commit: node counts, parents, accepted counts and paths from nowhere
+    rng = W.HostRng(84, 0)
+    toks = [W.plant_tokens(rng, t, vocab=3, p_match=0.9) for t in trees]
+    w_acc, w_path, w_bonus = oracle.tree_accept([x[0] for x in toks], [x[1] for x in toks], trees, [T] * 3)
+    n_acc = torch.zeros(3, dtype=torch.int32, device=DEV)
+    path = torch.zeros((3, T), dtype=torch.int32, device=DEV)
+    bonus = torch.zeros(3, dtype=torch.int32, device=DEV)
+    tw.tree_accept(_i32([x[0] for x in toks]), _i32([x[1] for x in toks]), _i32(bad_parent), _i32([neg, big, T]),
+                   n_acc, path, bonus)
+    torch.cuda.synchronize()
+    assert int(n_acc[2]) == int(w_acc[2]) and int(bonus[2]) == int(w_bonus[2])
+    assert torch.equal(path[2].cpu(), w_path[2])
+    pool = k.clone()
+    pd = pool.to(DEV)
+    new_len = torch.zeros(3, dtype=torch.int32, device=DEV)
+    bad_path = w_path.clone()
+    bad_path[0] = torch.tensor([big, neg] * (T // 2), dtype=torch.int32)
+    bad_path[1] = torch.full((T,), -1, dtype=torch.int32)
+    bad_acc = torch.tensor([1000, -3, int(w_acc[2])], dtype=torch.int32)
+    tw.kv_commit(bad_path.to(DEV), bad_acc.to(DEV), [tw.kv_view(pd, ro)], _i32([big, -5, ctx[2]]), new_len)
+    torch.cuda.synchronize()
+    oracle.kv_commit(pool, [ctx[2]], [T], w_path[2:3], [int(w_acc[2])], row_off=[off[2]])
+    lo, hi = off[2], off[2] + ctx[2] + T
+    assert torch.equal(pd[lo:hi].cpu().view(torch.int16), pool[lo:hi].view(torch.int16))
+
+
 def test_pools_larger_than_4_gib(tw):
     # Sequences parked at the far end of two 4.7 GiB pools: byte offsets past 2^32 (row * stride past
     # 2^31 already) in every kernel that addresses a pool.  The pools are left uninitialised except
