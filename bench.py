@@ -45,6 +45,8 @@ def main():
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the CPU oracle leg (0 = skip)")
     ap.add_argument("--other-configs", type=int, default=1,
                     help="also time tree_verify_attn on cfg2 (three prefix lengths), cfg3 and cfg4 (0 = skip)")
+    ap.add_argument("--next-rows", type=int, default=1,
+                    help="also time the calls around the hot path (P-Head score, commit, draft side; 0 = skip)")
     ap.add_argument("--bf16-out-iters", type=int, default=25,
                     help="launches of the bf16-output leg of tree_verify_attn (0 = skip)")
     ap.add_argument("--graph-iters", type=int, default=50,
@@ -248,6 +250,61 @@ def main():
             del do, wo
         del flush_a, flush_b
 
+    # the calls around the timed step, on the same batch: the P-Head form of the pruning score (an
+    # HBM stream over the keys and their gates), the commit of the accepted paths, and the draft
+    # side (top-E of a 32000-wide distribution per expanded node, pruning of the drafted tree)
+    next_rows = {}
+    if args.next_rows:
+        from paper_2503_14075_amd import binding as twb
+
+        def med_us(fn, n=12):
+            ev = []
+            for _ in range(n):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                fn()
+                e1.record()
+                ev.append((e0, e1))
+            torch.cuda.synchronize()
+            ts = sorted(x.elapsed_time(y) for x, y in ev[2:])
+            return ts[len(ts) // 2] * 1e3
+
+        Bn = args.batch
+        gk = torch.empty_like(dw.k_score).normal_()
+        qp = dw.q_sel[:, -1].contiguous()
+        gq = torch.empty_like(qp).normal_()
+        gview = twb.kv_view(gk, row_off=dw.score_row_off)
+        t_ph = med_us(lambda: twb.ttp_score_phead(qp, gq, dw.k_score_view, gview, 0, cfg.M, cfg.scale, dw.scores,
+                                                  dw.score_ws))
+        b_ph = 2 * Bn * cfg.M * cfg.H * cfg.d_h * 2
+        next_rows["ttp_score_phead"] = {"us_median": t_ph, "algorithmic_MB": b_ph / 1e6, "GBps": b_ph / t_ph / 1e3,
+                                        "frac_of_8TBps": b_ph / t_ph / 1e3 / HBM_PEAK_GBS}
+        del gk, gview
+        dw.run_score()   # the scores of the timed configuration back in place
+        new_len = torch.empty(Bn, dtype=torch.int32, device=dev)
+        ctx_seq = dw.ctx_len[:Bn].contiguous()
+        kc, vc = dw.k_pool.clone(), dw.v_pool.clone()      # the commit moves rows in place: not on the timed caches
+        cviews = [twb.kv_view(kc, dw.row_off, dw.page_table, cfg.page_rows),
+                  twb.kv_view(vc, dw.row_off, dw.page_table, cfg.page_rows)]
+        next_rows["kv_commit_us_median"] = med_us(lambda: twb.kv_commit(dw.path, dw.n_acc, cviews, ctx_seq, new_len))
+        del kc, vc, cviews
+        probs = torch.rand(Bn * 10, 32000, device=dev)
+        ids = torch.empty((Bn * 10, 10), dtype=torch.int32, device=dev)
+        vals = torch.empty((Bn * 10, 10), dtype=torch.float32, device=dev)
+        next_rows["draft_topk_us_median"] = med_us(lambda: twb.draft_topk(probs, 10, ids, vals))
+        del probs
+        N = 310                                     # 10 expanded nodes x 10 tokens on each of 3 levels + 10
+        cp = (torch.arange(N, device=dev, dtype=torch.int32) // 10 - 1).clamp(min=-1).repeat(Bn, 1).contiguous()
+        ct = torch.randint(0, 32000, (Bn, N), device=dev, dtype=torch.int32)
+        pb = torch.rand(Bn, N, device=dev)
+        nc = torch.full((Bn,), N, dtype=torch.int32, device=dev)
+        root = torch.zeros(Bn, dtype=torch.int32, device=dev)
+        outs = [torch.empty((Bn, 61), dtype=torch.int32, device=dev) for _ in range(3)]
+        nn = torch.empty(Bn, dtype=torch.int32, device=dev)
+        tws = torch.empty(twb.tree_build_workspace_bytes(Bn, N, 61) // 4 + 1, dtype=torch.float32, device=dev)
+        next_rows["tree_build_us_median"] = med_us(lambda: twb.tree_build(cp, ct, pb, nc, root, 61, outs[0], outs[1],
+                                                                          outs[2], nn, tws))
+
     # what plain library kernels reach on this machine in this run (context for the roofline fraction):
     # a 1 GiB device-to-device copy (read + write) and a 1 GiB reduction (read only)
     ctx_a = torch.empty(1 << 29, dtype=torch.bfloat16, device=dev).normal_()
@@ -354,7 +411,8 @@ def main():
                    "verify_tokens_per_s_kernel_only": tokens / (ker_avg * 1e-3),
                    "verify_single_sequence_latency_us": single_us,
                    "verify_single_sequence_latency_us_hip_graph": single_graph_us,
-                   "verify_other_configs": others},
+                   "verify_other_configs": others,
+                   "next_rows": next_rows},
     }
     print(json.dumps(out))
 

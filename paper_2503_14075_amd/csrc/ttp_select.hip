@@ -5,7 +5,6 @@
 
 namespace tw {
 
-constexpr int kSelThreads = 256;
 
 // Larger float <=> larger key.  -0.0 is folded into +0.0 first so the two tie.
 __device__ __forceinline__ uint32_t order_key(float x) {
@@ -14,14 +13,15 @@ __device__ __forceinline__ uint32_t order_key(float x) {
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
-// Keys of one sequence are loaded once into registers (KPT per lane) when the
+// Keys of one sequence are loaded once into registers (KPT per lane, THREADS lanes) when the
 // row fits, otherwise (KPT == 0) every pass re-reads them from memory.
-template <int KPT>
-__global__ __launch_bounds__(kSelThreads) void select_kernel(const float* __restrict__ scores, int M,
-                                                             int R, int32_t* __restrict__ kept) {
+template <int KPT, int THREADS>
+__global__ __launch_bounds__(THREADS) void select_kernel(const float* __restrict__ scores, int M, int R,
+                                                         int32_t* __restrict__ kept) {
+    constexpr int kWaves = THREADS / 64;
     __shared__ uint32_t s_hist[256];
     __shared__ uint32_t s_prefix, s_need;
-    __shared__ uint32_t s_wave_a[kSelThreads / 64];
+    __shared__ uint32_t s_wave_a[4];   // the bucket scan is done by the first 256 lanes
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const float* sc = scores + (int64_t)blockIdx.x * M;
     int32_t* out = kept + (int64_t)blockIdx.x * R;
@@ -30,10 +30,10 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const float* __rest
     uint32_t keys[KPT > 0 ? KPT : 1];
 #pragma unroll
     for (int u = 0; u < KPT; ++u) {
-        const int m = tid + u * kSelThreads;
+        const int m = tid + u * THREADS;
         keys[u] = m < M ? order_key(sc[m]) : 0u;
     }
-    const int n_iter = (M + kSelThreads - 1) / kSelThreads;
+    const int n_iter = (M + THREADS - 1) / THREADS;
 
     if (tid == 0) {
         s_prefix = 0u;
@@ -43,7 +43,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const float* __rest
     // the R-th largest element is known down to that byte, and s_need is its
     // rank among the elements sharing the prefix.
     for (int shift = 24; shift >= 0; shift -= 8) {
-        s_hist[tid] = 0u;
+        if (tid < 256) s_hist[tid] = 0u;
         __syncthreads();
         const uint32_t prefix = s_prefix, need = s_need;
         const uint32_t hi_mask = shift == 24 ? 0u : (0xFFFFFFFFu << (shift + 8));
@@ -63,58 +63,61 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const float* __rest
         if (KPT > 0) {
 #pragma unroll
             for (int u = 0; u < KPT; ++u) {
-                const int m = tid + u * kSelThreads;
+                const int m = tid + u * THREADS;
                 count(m < M && (keys[u] & hi_mask) == prefix, keys[u]);
             }
         } else {
             for (int u = 0; u < n_iter; ++u) {
-                const int m = tid + u * kSelThreads;
+                const int m = tid + u * THREADS;
                 const uint32_t key = m < M ? order_key(sc[m]) : 0u;
                 count(m < M && (key & hi_mask) == prefix, key);
             }
         }
         __syncthreads();
-        // lane tid owns bucket 255 - tid; inclusive scan from the largest bucket down
-        const uint32_t mine = s_hist[255 - tid];
-        uint32_t incl = mine;
+        // lane tid < 256 owns bucket 255 - tid; inclusive scan from the largest bucket down
+        uint32_t mine = 0u, incl = 0u;
+        if (tid < 256) {
+            mine = s_hist[255 - tid];
+            incl = mine;
 #pragma unroll
-        for (int off = 1; off < 64; off <<= 1) {
-            const uint32_t up = __shfl_up(incl, off, 64);
-            if (lane >= off) incl += up;
+            for (int off = 1; off < 64; off <<= 1) {
+                const uint32_t up = __shfl_up(incl, off, 64);
+                if (lane >= off) incl += up;
+            }
+            if (lane == 63) s_wave_a[wave] = incl;
         }
-        if (lane == 63) s_wave_a[wave] = incl;
         __syncthreads();
-        for (int w = 0; w < wave; ++w) incl += s_wave_a[w];
-        // exactly one bucket has  (count above it) < need <= (count above it) + (its own count)
-        if (incl >= need && incl - mine < need) {
-            s_prefix = prefix | ((uint32_t)(255 - tid) << shift);
-            s_need = need - (incl - mine);
+        if (tid < 256) {
+            for (int w = 0; w < wave; ++w) incl += s_wave_a[w];
+            // exactly one bucket has  (count above it) < need <= (count above it) + (its own count)
+            if (incl >= need && incl - mine < need) {
+                s_prefix = prefix | ((uint32_t)(255 - tid) << shift);
+                s_need = need - (incl - mine);
+            }
         }
         __syncthreads();
     }
     const uint32_t thr = s_prefix;   // key of the R-th largest score
     const uint32_t need = s_need;    // how many elements equal to it are kept (lowest indices)
-    // Output in ascending index order.  Element m = u * 256 + tid belongs to (round u, wavefront):
-    // rounds, and wavefronts inside a round, are in index order, so an element's rank among the
-    // equal keys and its output position are a count inside its wavefront (ballot) plus the totals
-    // of all earlier (round, wavefront) cells, which every wavefront scans for itself.  A row held
-    // in registers (KPT rounds) is one sweep; a longer one takes sweeps of 16 rounds, the running
-    // totals carried over.
-    constexpr int kWaves = kSelThreads / 64, kMaxCells = 64;
-    constexpr int kSweep = KPT > 0 ? KPT : kMaxCells / kWaves;
-    static_assert(kSweep * kWaves <= kMaxCells, "one lane per cell");
-    __shared__ uint32_t s_cell[kMaxCells];
+    // Output in ascending index order.  Element m = u * THREADS + tid belongs to (round u,
+    // wavefront): rounds, and wavefronts inside a round, are in index order, so an element's rank
+    // among the equal keys and its output position are a count inside its wavefront (ballot) plus
+    // the totals of all earlier (round, wavefront) cells, which every wavefront scans for itself,
+    // one lane per cell.  A sweep covers as many rounds as 64 cells hold; the running totals are
+    // carried from sweep to sweep.
+    constexpr int kSweep = 64 / kWaves;
+    __shared__ uint32_t s_cell[64];
     const uint64_t below = (1ull << lane) - 1ull;
     uint32_t run_eq = 0u, run_sel = 0u;   // totals of the sweeps before this one (same in every thread)
-    for (int u0 = 0; u0 < n_iter; u0 += kSweep) {
+    auto sweep = [&](int u0, auto key_of) {
         const int nu = min(kSweep, n_iter - u0);
         uint64_t eq_b[kSweep], gt_b[kSweep];
 #pragma unroll
         for (int du = 0; du < kSweep; ++du) {
-            const int u = u0 + du, m = u * kSelThreads + tid;
+            const int m = (u0 + du) * THREADS + tid;
             bool eq = false, gt = false;
             if (du < nu && m < M) {
-                const uint32_t key = KPT > 0 ? keys[KPT > 0 ? du : 0] : order_key(sc[m]);   // KPT > 0: u0 == 0
+                const uint32_t key = key_of(du, m);
                 eq = key == thr;
                 gt = key > thr;
             }
@@ -123,7 +126,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const float* __rest
             if (lane == 0) s_cell[du * kWaves + wave] = (uint32_t)__popcll(eq_b[du]);
         }
         __syncthreads();
-        // exclusive scan of the equal-key counts over the cells, by every wavefront for itself
+        // exclusive scan of the equal-key counts over the cells
         uint32_t c = lane < nu * kWaves ? s_cell[lane] : 0u, incl = c;
 #pragma unroll
         for (int off = 1; off < 64; off <<= 1) {
@@ -156,22 +159,36 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const float* __rest
         for (int du = 0; du < kSweep; ++du) {
             const uint32_t pos = run_sel + __shfl(sel_excl, du * kWaves + wave, 64) +
                                  (uint32_t)__popcll(sel_b[du] & below);
-            if (((sel_b[du] >> lane) & 1ull) && pos < (uint32_t)R) out[pos] = (u0 + du) * kSelThreads + tid;
+            if (((sel_b[du] >> lane) & 1ull) && pos < (uint32_t)R) out[pos] = (u0 + du) * THREADS + tid;
         }
         run_eq += eq_total;
         run_sel += sel_total;
         __syncthreads();   // the cells are rewritten by the next sweep
+    };
+    if (KPT > 0) {
+        // register-held keys: the sweeps are unrolled so that keys[] is indexed by constants
+#pragma unroll
+        for (int u0 = 0; u0 < KPT; u0 += kSweep) {
+            if (u0 < n_iter)
+                sweep(u0, [&](int du, int) { return keys[(u0 + du) < KPT ? (u0 + du) : 0]; });
+        }
+    } else {
+        for (int u0 = 0; u0 < n_iter; u0 += kSweep) sweep(u0, [&](int, int m) { return order_key(sc[m]); });
     }
 }
 
 hipError_t launch_select(const float* scores, int B, int M, int R, int32_t* kept, hipStream_t s) {
     if (B == 0 || R == 0) return hipSuccess;
-    if (M <= 4 * kSelThreads)
-        hipLaunchKernelGGL(select_kernel<4>, dim3(B), dim3(kSelThreads), 0, s, scores, M, R, kept);
-    else if (M <= 12 * kSelThreads)
-        hipLaunchKernelGGL(select_kernel<12>, dim3(B), dim3(kSelThreads), 0, s, scores, M, R, kept);
+    // rows up to 32768 scores (a vocabulary) are held in registers: 4 or 12 per lane of 256, or 32
+    // per lane of 1024 (one row of 32000: 147 us with a re-read per pass, measured, against this)
+    if (M <= 4 * 256)
+        hipLaunchKernelGGL((select_kernel<4, 256>), dim3(B), dim3(256), 0, s, scores, M, R, kept);
+    else if (M <= 12 * 256)
+        hipLaunchKernelGGL((select_kernel<12, 256>), dim3(B), dim3(256), 0, s, scores, M, R, kept);
+    else if (M <= 32 * 1024)
+        hipLaunchKernelGGL((select_kernel<32, 1024>), dim3(B), dim3(1024), 0, s, scores, M, R, kept);
     else
-        hipLaunchKernelGGL(select_kernel<0>, dim3(B), dim3(kSelThreads), 0, s, scores, M, R, kept);
+        hipLaunchKernelGGL((select_kernel<0, 256>), dim3(B), dim3(256), 0, s, scores, M, R, kept);
     return hipGetLastError();
 }
 

@@ -461,7 +461,7 @@ def _check_select(tw, scores, R):
     assert torch.equal(kept.cpu(), oracle.ttp_select(scores, R))
 
 
-@pytest.mark.parametrize("M", [1, 63, 576, 2880, 32000])
+@pytest.mark.parametrize("M", [1, 63, 576, 1024, 1025, 2880, 3072, 3073, 32000, 32768, 32769])
 def test_select_adversarial(tw, M):
     g = torch.Generator().manual_seed(M)
     vals = torch.tensor([-3.5, -0.0, 0.0, 1e-38, 1e-38, 0.25, 0.25, 7.0])
