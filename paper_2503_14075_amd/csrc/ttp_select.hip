@@ -20,7 +20,7 @@ __global__ __launch_bounds__(THREADS) void select_kernel(const float* __restrict
                                                          int32_t* __restrict__ kept) {
     constexpr int kWaves = THREADS / 64;
     __shared__ uint32_t s_hist[256];
-    __shared__ uint32_t s_prefix, s_need;
+    __shared__ uint32_t s_prefix, s_need, s_eq_total;
     __shared__ uint32_t s_wave_a[4];   // the bucket scan is done by the first 256 lanes
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const float* sc = scores + (int64_t)blockIdx.x * M;
@@ -55,7 +55,7 @@ __global__ __launch_bounds__(THREADS) void select_kernel(const float* __restrict
             const uint64_t vmask = __ballot(valid);
             if (vmask == 0ull) return;
             const int leader = __ffsll((unsigned long long)vmask) - 1;
-            const uint32_t b0 = __shfl(bucket, leader, 64);
+            const uint32_t b0 = __builtin_amdgcn_readlane(bucket, leader);   // leader is wavefront-uniform
             const uint64_t same = __ballot(valid && bucket == b0);
             if (lane == leader) atomicAdd(&s_hist[b0], (uint32_t)__popcll(same));
             if (valid && bucket != b0) atomicAdd(&s_hist[bucket], 1u);
@@ -93,6 +93,7 @@ __global__ __launch_bounds__(THREADS) void select_kernel(const float* __restrict
             if (incl >= need && incl - mine < need) {
                 s_prefix = prefix | ((uint32_t)(255 - tid) << shift);
                 s_need = need - (incl - mine);
+                s_eq_total = mine;   // after the last pass: how many keys equal the R-th largest
             }
         }
         __syncthreads();
@@ -107,6 +108,68 @@ __global__ __launch_bounds__(THREADS) void select_kernel(const float* __restrict
     // carried from sweep to sweep.
     constexpr int kSweep = 64 / kWaves;
     __shared__ uint32_t s_cell[64];
+    // Long rows with few survivors (the top few of a vocabulary): instead of sweeping every round,
+    // the survivors and the keys equal to the threshold are appended to a short list in any order
+    // and ranked by index there.  Taken when the row needs several sweeps and the list fits.
+    constexpr int kListCap = 1024;
+    constexpr bool kManySweeps = KPT == 0 || KPT > kSweep;
+    __shared__ uint32_t s_list[kManySweeps ? kListCap : 1];
+    __shared__ uint32_t s_n_list;
+    if (kManySweeps && (uint32_t)R - need + s_eq_total <= (uint32_t)kListCap) {
+        if (tid == 0) s_n_list = 0u;
+        __syncthreads();
+        auto append = [&](uint32_t key, int m) {
+            if (m < M && key >= thr) s_list[atomicAdd(&s_n_list, 1u)] = (uint32_t)m | (key == thr ? 0x80000000u : 0u);
+        };
+        if (KPT > 0) {
+#pragma unroll
+            for (int u = 0; u < KPT; ++u) append(keys[u], tid + u * THREADS);
+        } else {
+            for (int u = 0; u < n_iter; ++u) {
+                const int m = tid + u * THREADS;
+                append(m < M ? order_key(sc[m]) : 0u, m);
+            }
+        }
+        __syncthreads();
+        const int L = (int)s_n_list;
+        constexpr uint32_t kEq = 0x80000000u, kKeep = 0x40000000u, kIdx = 0x3FFFFFFFu;   // indices are below 2^20
+        // kept: every key above the threshold, and the `need` lowest indices among the equal ones.
+        // The decisions are made on the list as appended, then written as a flag after a barrier.
+        bool keep[(kListCap + THREADS - 1) / THREADS];
+#pragma unroll
+        for (int k = 0; k < (kListCap + THREADS - 1) / THREADS; ++k) {
+            const int e = tid + k * THREADS;
+            keep[k] = false;
+            if (e < L) {
+                const uint32_t me = s_list[e], idx = me & kIdx;
+                keep[k] = true;
+                if (me & kEq) {
+                    uint32_t eq_rank = 0u;
+                    for (int j = 0; j < L; ++j) eq_rank += (s_list[j] & kEq) && (s_list[j] & kIdx) < idx;
+                    keep[k] = eq_rank < need;
+                }
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < (kListCap + THREADS - 1) / THREADS; ++k) {
+            const int e = tid + k * THREADS;
+            if (e < L && keep[k]) s_list[e] |= kKeep;
+        }
+        __syncthreads();
+        // output position of a kept entry: the kept entries with a lower index
+#pragma unroll
+        for (int k = 0; k < (kListCap + THREADS - 1) / THREADS; ++k) {
+            const int e = tid + k * THREADS;
+            if (e < L && keep[k]) {
+                const uint32_t idx = s_list[e] & kIdx;
+                uint32_t pos = 0u;
+                for (int j = 0; j < L; ++j) pos += (s_list[j] & kKeep) && (s_list[j] & kIdx) < idx;
+                if (pos < (uint32_t)R) out[pos] = (int32_t)idx;
+            }
+        }
+        return;
+    }
     const uint64_t below = (1ull << lane) - 1ull;
     uint32_t run_eq = 0u, run_sel = 0u;   // totals of the sweeps before this one (same in every thread)
     auto sweep = [&](int u0, auto key_of) {

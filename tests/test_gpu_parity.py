@@ -473,8 +473,12 @@ def test_select_adversarial(tw, M):
         -torch.rand(M, generator=g),                                          # all negative
         torch.randn(M, generator=g) * 1e-41,                                  # denormals of both signs
     ]
+    few = torch.rand(M, generator=g)                                          # distinct values, except that the
+    few[torch.randperm(M, generator=g)[:7]] = 2.0                             # largest one occurs 7 times and the
+    few[torch.randperm(M, generator=g)[:5]] = 1.5                             # next one 5 times: short tie runs
+    rows.append(few)
     sc = torch.stack(rows).float()
-    for R in sorted({0, 1, min(2, M), M // 9, M // 2, max(M - 1, 0), M}):
+    for R in sorted({0, 1, min(2, M), min(9, M), M // 9, M // 2, max(M - 1, 0), M}):
         _check_select(tw, sc, R)
 
 
