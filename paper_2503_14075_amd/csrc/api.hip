@@ -325,8 +325,8 @@ int32_t tw_draft_topk(const float* probs, int32_t n, int32_t V, int32_t E, int32
     if (n == 0 || E == 0) return TW_OK;
     if (!probs || !ids || !vals) return TW_ERR_INVALID_ARG;
     hipStream_t s = (hipStream_t)stream;
-    if (launch_select(probs, n, V, E, ids, s) != hipSuccess) return TW_ERR_LAUNCH;   // survivors, ascending index
-    return launch_rank_sort(probs, n, V, E, ids, vals, s) == hipSuccess ? TW_OK : TW_ERR_LAUNCH;
+    // one launch: radix select of the survivors, then their rank order inside the same workgroup
+    return launch_select(probs, n, V, E, ids, s, vals) == hipSuccess ? TW_OK : TW_ERR_LAUNCH;
 }
 
 size_t tw_tree_build_workspace_bytes(int32_t B, int32_t N, int32_t T_max) {

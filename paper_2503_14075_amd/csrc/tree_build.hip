@@ -1,47 +1,14 @@
 // Draft-side tree construction of tree-based self-speculative decoding
-// (Sec. 5.4, App. A): per-node top-E tokens in rank order, cumulative path
-// confidence of every drafted candidate, and the final pruning of the drafted
-// tree to its N_max most confident candidates with a topological renumbering
-// that the verification calls take as parent[].
+// (Sec. 5.4, App. A): cumulative path confidence of every drafted candidate,
+// and the final pruning of the drafted tree to its N_max most confident
+// candidates with a topological renumbering that the verification calls take
+// as parent[].  (The per-node top-E tokens in rank order come from the select
+// kernel.)
 #include "twig_internal.h"
 
 namespace tw {
 
 constexpr int kTbThreads = 256;
-
-__device__ __forceinline__ uint32_t tb_order_key(float x) {
-    uint32_t u = __float_as_uint(x);
-    if (u == 0x80000000u) u = 0u;
-    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
-}
-
-// Rank order of the E survivors of a row: larger value first, equal values lower index first.
-// kept [n][E] holds the survivors' indices in ascending order (output of the radix select).
-__global__ __launch_bounds__(kTbThreads) void rank_sort_kernel(const float* __restrict__ vals, int V, int E,
-                                                               int32_t* __restrict__ ids,
-                                                               float* __restrict__ out_vals) {
-    __shared__ uint32_t s_key[kTbThreads];
-    __shared__ int32_t s_idx[kTbThreads];
-    const int row = blockIdx.x, i = threadIdx.x;
-    int32_t idx = 0;
-    uint32_t key = 0u;
-    float v = 0.f;
-    if (i < E) {
-        idx = ids[(int64_t)row * E + i];
-        idx = idx < 0 ? 0 : (idx >= V ? V - 1 : idx);
-        v = vals[(int64_t)row * V + idx];
-        key = tb_order_key(v);
-    }
-    s_key[i] = key;
-    s_idx[i] = idx;
-    __syncthreads();
-    if (i < E) {
-        int rank = 0;
-        for (int j = 0; j < E; ++j) rank += (s_key[j] > key) || (s_key[j] == key && s_idx[j] < idx);
-        ids[(int64_t)row * E + rank] = idx;   // every slot is written exactly once: the order is total
-        out_vals[(int64_t)row * E + rank] = v;
-    }
-}
 
 // conf[b][i] = product of prob along the path root -> candidate i; -1 for slots past n_cand[b].
 __global__ __launch_bounds__(kTbThreads) void tree_conf_kernel(const int32_t* __restrict__ cand_parent,
@@ -101,13 +68,6 @@ __global__ __launch_bounds__(kTbThreads) void tree_emit_kernel(TreeBuildArgs a) 
         a.src_out[o + t] = src;
     }
     if (tid == 0) a.n_nodes_out[b] = 1 + n_keep;
-}
-
-hipError_t launch_rank_sort(const float* vals, int n, int V, int E, int32_t* ids, float* out_vals,
-                            hipStream_t s) {
-    if (n == 0 || E == 0) return hipSuccess;
-    hipLaunchKernelGGL(rank_sort_kernel, dim3(n), dim3(kTbThreads), 0, s, vals, V, E, ids, out_vals);
-    return hipGetLastError();
 }
 
 hipError_t launch_tree_conf(const int32_t* cand_parent, const float* cand_prob, const int32_t* n_cand, int B,

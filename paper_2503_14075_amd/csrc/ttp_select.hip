@@ -17,7 +17,7 @@ __device__ __forceinline__ uint32_t order_key(float x) {
 // row fits, otherwise (KPT == 0) every pass re-reads them from memory.
 template <int KPT, int THREADS>
 __global__ __launch_bounds__(THREADS) void select_kernel(const float* __restrict__ scores, int M, int R,
-                                                         int32_t* __restrict__ kept) {
+                                                         int32_t* __restrict__ kept, float* __restrict__ ranked_vals) {
     constexpr int kWaves = THREADS / 64;
     __shared__ uint32_t s_hist[256];
     __shared__ uint32_t s_prefix, s_need, s_eq_total;
@@ -168,8 +168,7 @@ __global__ __launch_bounds__(THREADS) void select_kernel(const float* __restrict
                 if (pos < (uint32_t)R) out[pos] = (int32_t)idx;
             }
         }
-        return;
-    }
+    } else {
     const uint64_t below = (1ull << lane) - 1ull;
     uint32_t run_eq = 0u, run_sel = 0u;   // totals of the sweeps before this one (same in every thread)
     auto sweep = [&](int u0, auto key_of) {
@@ -238,20 +237,49 @@ __global__ __launch_bounds__(THREADS) void select_kernel(const float* __restrict
     } else {
         for (int u0 = 0; u0 < n_iter; u0 += kSweep) sweep(u0, [&](int, int m) { return order_key(sc[m]); });
     }
+    }
+    // Rank order on request (R <= 256): larger value first, equal values lower index first, with
+    // the values beside the indices.  The survivors were just written in index order by this
+    // workgroup; the order is total, so every output slot is written exactly once.
+    if (ranked_vals) {
+        __shared__ uint32_t s_rk_key[256];
+        __shared__ int32_t s_rk_idx[256];
+        __syncthreads();   // the survivors are in `out`
+        int32_t idx = 0;
+        uint32_t key = 0u;
+        float v = 0.f;
+        if (tid < R) {
+            idx = out[tid];
+            idx = idx < 0 ? 0 : (idx >= M ? M - 1 : idx);
+            v = sc[idx];
+            key = order_key(v);
+            s_rk_key[tid] = key;
+            s_rk_idx[tid] = idx;
+        }
+        __syncthreads();
+        if (tid < R) {
+            int rank = 0;
+            for (int j = 0; j < R; ++j) rank += (s_rk_key[j] > key) || (s_rk_key[j] == key && s_rk_idx[j] < idx);
+            out[rank] = idx;
+            ranked_vals[(int64_t)blockIdx.x * R + rank] = v;
+        }
+    }
 }
 
-hipError_t launch_select(const float* scores, int B, int M, int R, int32_t* kept, hipStream_t s) {
+hipError_t launch_select(const float* scores, int B, int M, int R, int32_t* kept, hipStream_t s,
+                         float* ranked_vals) {
     if (B == 0 || R == 0) return hipSuccess;
+    if (ranked_vals && R > 256) return hipErrorInvalidValue;
     // rows up to 32768 scores (a vocabulary) are held in registers: 4 or 12 per lane of 256, or 32
     // per lane of 1024 (one row of 32000: 147 us with a re-read per pass, measured, against this)
     if (M <= 4 * 256)
-        hipLaunchKernelGGL((select_kernel<4, 256>), dim3(B), dim3(256), 0, s, scores, M, R, kept);
+        hipLaunchKernelGGL((select_kernel<4, 256>), dim3(B), dim3(256), 0, s, scores, M, R, kept, ranked_vals);
     else if (M <= 12 * 256)
-        hipLaunchKernelGGL((select_kernel<12, 256>), dim3(B), dim3(256), 0, s, scores, M, R, kept);
+        hipLaunchKernelGGL((select_kernel<12, 256>), dim3(B), dim3(256), 0, s, scores, M, R, kept, ranked_vals);
     else if (M <= 32 * 1024)
-        hipLaunchKernelGGL((select_kernel<32, 1024>), dim3(B), dim3(1024), 0, s, scores, M, R, kept);
+        hipLaunchKernelGGL((select_kernel<32, 1024>), dim3(B), dim3(1024), 0, s, scores, M, R, kept, ranked_vals);
     else
-        hipLaunchKernelGGL((select_kernel<0, 256>), dim3(B), dim3(256), 0, s, scores, M, R, kept);
+        hipLaunchKernelGGL((select_kernel<0, 256>), dim3(B), dim3(256), 0, s, scores, M, R, kept, ranked_vals);
     return hipGetLastError();
 }
 

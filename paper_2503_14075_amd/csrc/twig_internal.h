@@ -179,7 +179,10 @@ struct PheadArgs {
 hipError_t launch_phead(const PheadArgs& a, int dtype, hipStream_t s);
 
 // --- select / compact / tree -------------------------------------------------
-hipError_t launch_select(const float* scores, int B, int M, int R, int32_t* kept, hipStream_t s);
+// ranked_vals non-null (R <= 256): kept comes out in rank order (larger value first, equal values
+// lower index first) with the values beside it; null: ascending index order.
+hipError_t launch_select(const float* scores, int B, int M, int R, int32_t* kept, hipStream_t s,
+                         float* ranked_vals = nullptr);
 
 constexpr int kCompactMaxTensors = 64;
 struct CompactTable {
@@ -210,8 +213,6 @@ struct TreeBuildArgs {
     int32_t* n_nodes_out;        // [B]
     int32_t N, R, T_max;
 };
-hipError_t launch_rank_sort(const float* vals, int n, int V, int E, int32_t* ids, float* out_vals,
-                            hipStream_t s);
 hipError_t launch_tree_conf(const int32_t* cand_parent, const float* cand_prob, const int32_t* n_cand, int B,
                             int N, float* conf, hipStream_t s);
 hipError_t launch_tree_emit(const TreeBuildArgs& a, int B, hipStream_t s);
