@@ -106,7 +106,7 @@ __global__ __launch_bounds__(THREADS) void select_kernel(const float* __restrict
     // the totals of all earlier (round, wavefront) cells, which every wavefront scans for itself,
     // one lane per cell.  A sweep covers as many rounds as 64 cells hold; the running totals are
     // carried from sweep to sweep.
-    constexpr int kSweep = 64 / kWaves;
+    constexpr int kSweep = (KPT > 0 && KPT < 64 / kWaves) ? KPT : 64 / kWaves;   // rounds per sweep
     __shared__ uint32_t s_cell[64];
     // Long rows with few survivors (the top few of a vocabulary): instead of sweeping every round,
     // the survivors and the keys equal to the threshold are appended to a short list in any order
