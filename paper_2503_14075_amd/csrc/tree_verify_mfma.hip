@@ -608,8 +608,13 @@ static hipError_t launch_one(const VerifyArgs& a, hipStream_t s) {
     const size_t lds = MfCfg<DH>::kLds;
     const void* fn = a.n_blk == 1 ? (const void*)verify_mfma_kernel<DH, PAGED>
                                   : (const void*)verify_mfma_pair_kernel<DH, PAGED>;
-    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
+    // the kernels' LDS need is a constant: raise the limit once per kernel, not on every launch
+    static bool raised[2] = {false, false};
+    if (!raised[a.n_blk - 1]) {
+        const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        raised[a.n_blk - 1] = true;
+    }
     if (a.n_blk == 1)
         hipLaunchKernelGGL((verify_mfma_kernel<DH, PAGED>), grid, dim3(kMfThreads), lds, s, a);
     else

@@ -389,9 +389,14 @@ static hipError_t launch_rs(const ScoreArgs& a, hipStream_t s) {
     using Cf = RsCfg<DH, NB>;
     const int span_chunks = (a.v_start + a.M - 1) / kRsChunk - a.v_start / kRsChunk + 1;
     const size_t lds = Cf::kOffEs + (size_t)span_chunks * Cf::kEsChunk;
-    hipError_t e = hipFuncSetAttribute((const void*)score_resident_kernel<DH, NB>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
+    // the table grows with the visual span: raise the limit to a compute unit's LDS once per kernel
+    static bool raised = false;
+    if (!raised) {
+        const hipError_t e = hipFuncSetAttribute((const void*)score_resident_kernel<DH, NB>,
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, kRsLdsBytes);
+        if (e != hipSuccess) return e;
+        raised = true;
+    }
     hipLaunchKernelGGL((score_resident_kernel<DH, NB>), dim3(resident_grid(n_pairs)), dim3(kRsThreads), lds, s, a,
                        n_pairs);
     return hipGetLastError();
