@@ -351,10 +351,6 @@ int32_t tw_tree_build(const int32_t* cand_parent, const int32_t* cand_token, con
     hipStream_t s = (hipStream_t)stream;
     float* conf = (float*)ws;
     int32_t* kept = (int32_t*)((char*)ws + (size_t)B * N * sizeof(float));
-    if (R > 0) {
-        if (launch_tree_conf(cand_parent, cand_prob, n_cand, B, N, conf, s) != hipSuccess) return TW_ERR_LAUNCH;
-        if (launch_select(conf, B, N, R, kept, s) != hipSuccess) return TW_ERR_LAUNCH;
-    }
     TreeBuildArgs a;
     a.cand_parent = cand_parent;
     a.cand_token = cand_token;
@@ -368,6 +364,12 @@ int32_t tw_tree_build(const int32_t* cand_parent, const int32_t* cand_token, con
     a.N = N;
     a.R = R;
     a.T_max = T_max;
+    hipError_t e = hipSuccess;
+    if (R > 0 && launch_tree_build_fused(a, cand_prob, conf, B, s, &e)) return e == hipSuccess ? TW_OK : TW_ERR_LAUNCH;
+    if (R > 0) {
+        if (launch_tree_conf(cand_parent, cand_prob, n_cand, B, N, conf, s) != hipSuccess) return TW_ERR_LAUNCH;
+        if (launch_select(conf, B, N, R, kept, s) != hipSuccess) return TW_ERR_LAUNCH;
+    }
     return launch_tree_emit(a, B, s) == hipSuccess ? TW_OK : TW_ERR_LAUNCH;
 }
 

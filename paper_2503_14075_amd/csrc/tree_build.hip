@@ -4,13 +4,29 @@
 // candidates with a topological renumbering that the verification calls take
 // as parent[].  (The per-node top-E tokens in rank order come from the select
 // kernel.)
-#include "twig_internal.h"
+#include "select_block.h"
 
 namespace tw {
 
 constexpr int kTbThreads = 256;
 
-// conf[b][i] = product of prob along the path root -> candidate i; -1 for slots past n_cand[b].
+// Confidence of candidate i of sequence b: product of prob along the path root -> candidate;
+// -1 for slots past n (the number of valid candidates).
+__device__ __forceinline__ float path_confidence(const int32_t* __restrict__ cand_parent,
+                                                 const float* __restrict__ cand_prob, int64_t row, int i, int n,
+                                                 int N) {
+    if (i >= n) return -1.f;
+    // multiply from the node up to the root; parents precede children so the walk ends
+    float c = 1.f;
+    int u = i;
+    for (int step = 0; step < N && u >= 0; ++step) {
+        c *= cand_prob[row + u];
+        const int p = cand_parent[row + u];
+        u = p < u ? p : -1;
+    }
+    return c;
+}
+
 __global__ __launch_bounds__(kTbThreads) void tree_conf_kernel(const int32_t* __restrict__ cand_parent,
                                                                const float* __restrict__ cand_prob,
                                                                const int32_t* __restrict__ n_cand, int N,
@@ -19,25 +35,14 @@ __global__ __launch_bounds__(kTbThreads) void tree_conf_kernel(const int32_t* __
     if (i >= N) return;
     int n = n_cand[b];
     n = n < 0 ? 0 : (n > N ? N : n);
-    float c = -1.f;
-    if (i < n) {
-        // multiply from the node up to the root; parents precede children so the walk ends
-        c = 1.f;
-        int u = i;
-        for (int step = 0; step < N && u >= 0; ++step) {
-            c *= cand_prob[(int64_t)b * N + u];
-            int p = cand_parent[(int64_t)b * N + u];
-            u = p < u ? p : -1;
-        }
-    }
-    conf[(int64_t)b * N + i] = c;
+    conf[(int64_t)b * N + i] = path_confidence(cand_parent, cand_prob, (int64_t)b * N, i, n, N);
 }
 
 // kept [B][R] ascending candidate indices (radix select on conf).  Node 0 is the root; kept
 // candidate number r becomes node 1 + r (valid candidates precede the -1 padding slots).
-__global__ __launch_bounds__(kTbThreads) void tree_emit_kernel(TreeBuildArgs a) {
-    extern __shared__ int32_t s_inv[];   // candidate index -> node id, 0 = not kept
-    const int b = blockIdx.x, tid = threadIdx.x;
+// s_inv: N ints of LDS, candidate index -> node id, 0 = not kept.
+__device__ __forceinline__ void emit_tree(const TreeBuildArgs& a, int b, int32_t* s_inv) {
+    const int tid = threadIdx.x;
     int n = a.n_cand[b];
     n = n < 0 ? 0 : (n > a.N ? a.N : n);
     const int n_keep = n < a.R ? n : a.R;
@@ -70,6 +75,30 @@ __global__ __launch_bounds__(kTbThreads) void tree_emit_kernel(TreeBuildArgs a) 
     if (tid == 0) a.n_nodes_out[b] = 1 + n_keep;
 }
 
+__global__ __launch_bounds__(kTbThreads) void tree_emit_kernel(TreeBuildArgs a) {
+    extern __shared__ int32_t s_inv[];
+    emit_tree(a, blockIdx.x, s_inv);
+}
+
+// The three steps in one launch, one workgroup per sequence, when the candidates of a sequence
+// fit the registers of the select (N <= 256 * KPT): confidences to the workspace, select from
+// them in place, emit.  Each step reads what the same workgroup wrote before a barrier.
+template <int KPT>
+__global__ __launch_bounds__(kTbThreads) void tree_build_fused_kernel(TreeBuildArgs a, const float* cand_prob,
+                                                                      float* conf) {
+    extern __shared__ int32_t s_inv[];
+    const int b = blockIdx.x;
+    int n = a.n_cand[b];
+    n = n < 0 ? 0 : (n > a.N ? a.N : n);
+    const int64_t row = (int64_t)b * a.N;
+    for (int i = threadIdx.x; i < a.N; i += kTbThreads)
+        conf[row + i] = path_confidence(a.cand_parent, cand_prob, row, i, n, a.N);
+    __syncthreads();
+    select_block<KPT, kTbThreads>(conf + row, a.N, a.R, const_cast<int32_t*>(a.kept) + (int64_t)b * a.R, nullptr);
+    __syncthreads();
+    emit_tree(a, b, s_inv);
+}
+
 hipError_t launch_tree_conf(const int32_t* cand_parent, const float* cand_prob, const int32_t* n_cand, int B,
                             int N, float* conf, hipStream_t s) {
     if (B == 0 || N == 0) return hipSuccess;
@@ -82,6 +111,19 @@ hipError_t launch_tree_emit(const TreeBuildArgs& a, int B, hipStream_t s) {
     if (B == 0) return hipSuccess;
     hipLaunchKernelGGL(tree_emit_kernel, dim3(B), dim3(kTbThreads), (size_t)a.N * sizeof(int32_t), s, a);
     return hipGetLastError();
+}
+
+// false: the candidates do not fit the fused kernel, the caller launches the three steps
+bool launch_tree_build_fused(const TreeBuildArgs& a, const float* cand_prob, float* conf, int B, hipStream_t s,
+                             hipError_t* err) {
+    if (a.N > 12 * kTbThreads || B == 0) return false;
+    const size_t lds = (size_t)a.N * sizeof(int32_t);
+    if (a.N <= 4 * kTbThreads)
+        hipLaunchKernelGGL(tree_build_fused_kernel<4>, dim3(B), dim3(kTbThreads), lds, s, a, cand_prob, conf);
+    else
+        hipLaunchKernelGGL(tree_build_fused_kernel<12>, dim3(B), dim3(kTbThreads), lds, s, a, cand_prob, conf);
+    *err = hipGetLastError();
+    return true;
 }
 
 }  // namespace tw

@@ -215,6 +215,8 @@ struct TreeBuildArgs {
 };
 hipError_t launch_tree_conf(const int32_t* cand_parent, const float* cand_prob, const int32_t* n_cand, int B,
                             int N, float* conf, hipStream_t s);
+bool launch_tree_build_fused(const TreeBuildArgs& a, const float* cand_prob, float* conf, int B, hipStream_t s,
+                             hipError_t* err);
 hipError_t launch_tree_emit(const TreeBuildArgs& a, int B, hipStream_t s);
 
 // --- commit of the accepted path ------------------------------------------------

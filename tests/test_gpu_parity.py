@@ -909,8 +909,11 @@ def test_draft_topk_bit_exact(tw, V, E):
     assert torch.equal(ids.cpu(), wi) and torch.equal(vals.cpu(), wv)
 
 
-def test_tree_build_bit_exact_and_feeds_verification(tw):
-    B, E, K, D, T_max = 7, 10, 10, 4, 61          # the paper's defaults: N_max = 60 candidates + root
+@pytest.mark.parametrize("E,K", [(10, 10), (20, 20), (40, 30)])
+def test_tree_build_bit_exact_and_feeds_verification(tw, E, K):
+    # E = K = 10 are the paper's defaults (310 candidates); 1220 and 3640 candidates take the wider
+    # one-launch kernel and the three-launch path
+    B, D, T_max = 7, 4, 61                        # N_max = 60 candidates + root
     rng = W.HostRng(91, 0)
     cands = []
     for b in range(B):
