@@ -1063,6 +1063,32 @@ def test_bench_launch_configuration_sampled(runner):
         assert float((out[b].double() - want_o).abs().max()) <= ATTN_TOL
 
 
+def test_two_streams_at_once(runner):
+    # no state is shared between calls: two workloads stepping concurrently on two streams (each with
+    # its own workspace) give what they give alone
+    cfgs = [W.replicate(W.CONFIGS["cfg1"], 3), W.CONFIGS["cfg4"]]
+    dws = [runner.DeviceWorkload(W.make_workload(c), DEV) for c in cfgs]
+    outs = lambda dw: [dw.scores, dw.kept, dw.out, dw.n_acc, dw.path, dw.bonus] + list(dw.compact_dst)
+    refs = []
+    for dw in dws:
+        dw.step()
+        torch.cuda.synchronize()
+        refs.append([t.clone() for t in outs(dw)])
+        for t in outs(dw):
+            t.fill_(-1 if t.dtype in (torch.int32, torch.int64) else float("nan"))
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    for s_ in streams:
+        s_.wait_stream(torch.cuda.current_stream())
+    for _ in range(3):
+        for dw, s_ in zip(dws, streams):
+            with torch.cuda.stream(s_):
+                dw.step()
+    torch.cuda.synchronize()
+    for dw, ref in zip(dws, refs):
+        for got, want in zip(outs(dw), ref):
+            assert torch.equal(got.view(torch.uint8), want.view(torch.uint8))
+
+
 @pytest.mark.parametrize("name", ["cfg1", "cfg4"])
 def test_step_replays_from_a_hip_graph(runner, name):
     # the library only enqueues kernels on the caller's stream (no allocation, no synchronisation, no
