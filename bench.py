@@ -291,7 +291,11 @@ def main():
         probs = torch.rand(Bn * 10, 32000, device=dev)
         ids = torch.empty((Bn * 10, 10), dtype=torch.int32, device=dev)
         vals = torch.empty((Bn * 10, 10), dtype=torch.float32, device=dev)
-        next_rows["draft_topk_us_median"] = med_us(lambda: twb.draft_topk(probs, 10, ids, vals))
+        t_tk = med_us(lambda: twb.draft_topk(probs, 10, ids, vals))
+        next_rows["draft_topk_us_median"] = t_tk
+        tk_bytes = probs.numel() * 4 + ids.numel() * 8       # the rows read once, ids and values written
+        next_rows["draft_topk"] = {"rows": Bn * 10, "V": 32000, "E": 10, "algorithmic_MB": tk_bytes / 1e6,
+                                   "GBps": tk_bytes / t_tk / 1e3, "frac_of_8TBps": tk_bytes / t_tk / 1e3 / 8000.0}
         del probs
         N = 310                                     # 10 expanded nodes x 10 tokens on each of 3 levels + 10
         cp = (torch.arange(N, device=dev, dtype=torch.int32) // 10 - 1).clamp(min=-1).repeat(Bn, 1).contiguous()

@@ -325,7 +325,10 @@ int32_t tw_draft_topk(const float* probs, int32_t n, int32_t V, int32_t E, int32
     if (n == 0 || E == 0) return TW_OK;
     if (!probs || !ids || !vals) return TW_ERR_INVALID_ARG;
     hipStream_t s = (hipStream_t)stream;
-    // one launch: radix select of the survivors, then their rank order inside the same workgroup
+    // vocabulary-sized rows with a small E: one read of the row and a short candidate list
+    hipError_t err = hipSuccess;
+    if (launch_topk_rows(probs, n, V, E, ids, vals, s, &err)) return err == hipSuccess ? TW_OK : TW_ERR_LAUNCH;
+    // otherwise: radix select of the survivors, then their rank order inside the same workgroup
     return launch_select(probs, n, V, E, ids, s, vals) == hipSuccess ? TW_OK : TW_ERR_LAUNCH;
 }
 

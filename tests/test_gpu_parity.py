@@ -894,13 +894,24 @@ def test_score_generic_path(tw):
 # ----------------------------------------------------------------------------
 # draft-side tree build
 # ----------------------------------------------------------------------------
-@pytest.mark.parametrize("V,E", [(32000, 10), (301, 64), (50, 50), (7, 1)])
+@pytest.mark.parametrize("V,E", [(32000, 10), (301, 64), (50, 50), (7, 1), (32768, 32), (32000, 33), (1024, 1),
+                                 (4096, 5), (8192, 32), (8196, 10), (20000, 7), (32766, 10), (3076, 3)])
 def test_draft_topk_bit_exact(tw, V, E):
+    # rows of 3073 to 32768 values (a multiple of four) with E <= 32 take the one-read kernel,
+    # whose rows with many ties at its bound fall back to the radix select inside the kernel
     g = torch.Generator().manual_seed(V)
     probs = torch.softmax(torch.randn(9, V, generator=g) * 4, dim=1)
     probs[1, : V // 2] = probs[1, 0]          # plateau of ties
     probs[2] = 1.0 / V
     probs[3] = torch.round(probs[3] * 64) / 64  # few distinct values
+    probs[4] = torch.randn(V, generator=g)      # negative values, and zeros of both signs
+    probs[4, ::7] = 0.0
+    probs[4, 3::7] = -0.0
+    few = torch.randperm(V, generator=g)[: max(1, E // 2)]
+    probs[5] = 0.0                              # fewer non-zero values than E
+    probs[5, few] = torch.rand(few.numel(), generator=g) + 0.1
+    probs[6, -1] = probs[6].max() * 2           # the winner in the last slot
+    probs[7, 0] = probs[7].max()                # a tie of the two largest
     ids = torch.full((9, E), -7, dtype=torch.int32, device=DEV)
     vals = torch.full((9, E), -7.0, dtype=torch.float32, device=DEV)
     tw.draft_topk(probs.to(DEV), E, ids, vals)
