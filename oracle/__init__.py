@@ -221,6 +221,18 @@ def draft_topk(probs: torch.Tensor, E: int):
     return ids, vals
 
 
+def draft_topk_logits(logits: torch.Tensor, E: int):
+    """(ids [n][E] int32, probs [n][E] fp64) of softmax(logits) per row: larger logit first, ties
+    lower index first."""
+    assert logits.dtype == torch.float32 and logits.dim() == 2
+    n, V = logits.shape
+    ids = torch.empty(n, E, dtype=torch.int32)
+    probs = torch.empty(n, E, dtype=torch.float64)
+    _check(lib().orc_draft_topk_logits(_p(logits.contiguous()), n, V, int(E), _p(ids), _p(probs)),
+           "draft_topk_logits")
+    return ids, probs
+
+
 def tree_build(cand_parent: Sequence[int], cand_token: Sequence[int], cand_prob: Sequence[float],
                root_token: int, T_max: int):
     """(n_nodes, parent [T_max], token [T_max], src [T_max]) for one sequence."""

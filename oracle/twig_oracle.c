@@ -402,6 +402,38 @@ int orc_draft_topk(const float* probs, int n, int V, int E, int32_t* ids, float*
 }
 
 /*
+ * The same expansion taken from the logits of the draft head (Sec. 5.4 / App. A):
+ * the E most probable tokens of softmax(logits[r]) and their probabilities.  The
+ * order is decided on the logits themselves (softmax is monotone): larger logit
+ * first, equal logits lower index first.  The probabilities are fp64,
+ * exp(l - max) / sum over the whole row.
+ */
+int orc_draft_topk_logits(const float* logits, int n, int V, int E, int32_t* ids, double* probs) {
+    if (n < 0 || V < 0 || E < 0 || E > V) return -1;
+    if (n > 0 && E > 0 && (!logits || !ids || !probs)) return -1;
+    orc_pair* pr = (orc_pair*)malloc(sizeof(orc_pair) * (size_t)(V > 0 ? V : 1));
+    if (!pr) return -3;
+    for (int r = 0; r < n; ++r) {
+        const float* row = logits + (size_t)r * V;
+        double mx = -INFINITY, sum = 0.0;
+        for (int m = 0; m < V; ++m)
+            if ((double)row[m] > mx) mx = (double)row[m];
+        for (int m = 0; m < V; ++m) sum += exp((double)row[m] - mx);
+        for (int m = 0; m < V; ++m) {
+            pr[m].s = row[m];
+            pr[m].m = m;
+        }
+        qsort(pr, (size_t)V, sizeof(orc_pair), pair_cmp);
+        for (int e = 0; e < E; ++e) {
+            ids[(size_t)r * E + e] = pr[e].m;
+            probs[(size_t)r * E + e] = exp((double)pr[e].s - mx) / sum;
+        }
+    }
+    free(pr);
+    return 0;
+}
+
+/*
  * Pruning of a drafted tree to its most confident candidates (App. A).  The
  * confidence of candidate i is the product of cand_prob along its path from the
  * root (computed in fp32 from the node upwards, the order the GPU uses, so that

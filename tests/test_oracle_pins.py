@@ -562,6 +562,56 @@ def test_draft_topk_vs_stable_argsort():
         oracle.draft_topk(probs, 302)
 
 
+def test_draft_topk_logits_closed_forms():
+    # (a) logits = log of a known distribution with distinct rational probabilities, at a shift:
+    #     the winners are the known largest entries and their probabilities come back
+    V, E = 200, 7
+    w = np.arange(1, V + 1, dtype=np.float64)
+    rng = np.random.default_rng(5)
+    perm = rng.permutation(V)
+    p0 = (w / w.sum())[perm]                              # p0[i] = (perm[i] + 1) / sum
+    logits = torch.tensor(np.log(p0) + 3.25, dtype=torch.float32)[None]
+    ids, pr = oracle.draft_topk_logits(logits, E)
+    want_ids = [int(np.where(perm == V - 1 - e)[0][0]) for e in range(E)]
+    assert ids[0].tolist() == want_ids
+    assert np.allclose(pr[0].numpy(), [(V - e) / w.sum() for e in range(E)], rtol=3e-6, atol=0)  # fp32 logits
+    # (b) one raised logit among equal ones: p = e^a / (e^a + V - 1) and (V-1) equal shares, ties by index
+    a, V = 2.5, 50
+    lg = torch.zeros(1, V)
+    lg[0, 31] = a
+    ids, pr = oracle.draft_topk_logits(lg, 4)
+    assert ids[0].tolist() == [31, 0, 1, 2]
+    z = np.exp(a) + V - 1
+    assert np.allclose(pr[0].numpy(), [np.exp(a) / z, 1 / z, 1 / z, 1 / z], rtol=1e-14, atol=0)
+    # (c) E = V: a permutation, descending, summing to one
+    g = torch.Generator().manual_seed(9)
+    lg = torch.randn(3, 64, generator=g) * 5
+    ids, pr = oracle.draft_topk_logits(lg, 64)
+    for r in range(3):
+        assert sorted(ids[r].tolist()) == list(range(64))
+        assert abs(float(pr[r].sum()) - 1.0) < 1e-13
+        assert bool((pr[r][1:] <= pr[r][:-1]).all())
+        order = np.argsort(-lg[r].numpy(), kind="stable")
+        assert ids[r].tolist() == order.tolist()
+    # adding a constant changes nothing; checked where the shift is exact, on a grid of 1/8
+    grid = torch.round(lg * 8) / 8
+    i1, p1 = oracle.draft_topk_logits(grid, 10)
+    i2, p2 = oracle.draft_topk_logits(grid + 16.0, 10)
+    assert torch.equal(i1, i2) and torch.allclose(p1, p2, rtol=1e-14, atol=0)
+    # (d) it agrees with the probability form on a library softmax (fp64), where no two probabilities tie
+    sm = torch.softmax(lg.double(), dim=1)
+    ia, _ = oracle.draft_topk(sm.float(), 10)
+    ib, pb = oracle.draft_topk_logits(lg, 10)
+    assert torch.equal(ia, ib)
+    assert torch.allclose(pb, torch.gather(sm, 1, ib.long()), rtol=1e-13, atol=0)
+    # (e) very large logits do not overflow
+    big = torch.tensor([[1e30, -1e30, 1e30, 0.0]])
+    ids, pr = oracle.draft_topk_logits(big, 3)
+    assert ids[0].tolist() == [0, 2, 3] and np.allclose(pr[0].numpy(), [0.5, 0.5, 0.0])
+    with pytest.raises(ValueError):
+        oracle.draft_topk_logits(lg, 65)
+
+
 def _drafted_candidates(rng, E, K, D):
     """Level-wise expansion as in App. A with seeded probabilities: level 1 = E children of the
     root, each later level expands K nodes of the previous level into E children."""
