@@ -296,6 +296,11 @@ def main():
         tk_bytes = probs.numel() * 4 + ids.numel() * 8       # the rows read once, ids and values written
         next_rows["draft_topk"] = {"rows": Bn * 10, "V": 32000, "E": 10, "algorithmic_MB": tk_bytes / 1e6,
                                    "GBps": tk_bytes / t_tk / 1e3, "frac_of_8TBps": tk_bytes / t_tk / 1e3 / 8000.0}
+        # the same expansion from logits (softmax on the way): the rows read once, ids and probabilities written
+        t_tl = med_us(lambda: twb.draft_topk_logits(probs, 10, ids, vals))
+        next_rows["draft_topk_logits"] = {"rows": Bn * 10, "V": 32000, "E": 10, "us_median": t_tl,
+                                          "algorithmic_MB": tk_bytes / 1e6, "GBps": tk_bytes / t_tl / 1e3,
+                                          "frac_of_8TBps": tk_bytes / t_tl / 1e3 / 8000.0}
         del probs
         N = 310                                     # 10 expanded nodes x 10 tokens on each of 3 levels + 10
         cp = (torch.arange(N, device=dev, dtype=torch.int32) // 10 - 1).clamp(min=-1).repeat(Bn, 1).contiguous()

@@ -255,6 +255,20 @@ int32_t tw_draft_topk(const float* probs, int32_t n, int32_t V, int32_t E, int32
                       void* stream);
 
 /*
+ * The same expansion taken straight from the logits of the draft head (Sec. 5.4
+ * / App. A): ids[r] receives the E most probable tokens of softmax(logits[r][0..V)),
+ * larger logit first, equal logits lower index first; probs[r] their
+ * probabilities exp(l - max) / sum over the whole row, computed in fp32 in the
+ * same single read of the row (relative error below 2e-5).
+ *   logits [dev] [n][V] fp32 finite; ids [dev] [n][E] int32; probs [dev] [n][E] fp32.
+ * Rows that are 16-byte aligned and a multiple of four long are read with
+ * 16-byte loads; any other shape is accepted and read element by element.
+ * Errors: INVALID_ARG (E > V, null pointers), UNSUPPORTED (E > 32, V > 2^20).
+ */
+int32_t tw_draft_topk_logits(const float* logits, int32_t n, int32_t V, int32_t E, int32_t* ids, float* probs,
+                             void* stream);
+
+/*
  * Pruning of a drafted token tree to its most confident candidates (App. A:
  * the completed tree keeps at most N_max candidate nodes, highest confidence
  * first, together with their ancestors).  Candidates 0..n_cand[b)-1 of sequence

@@ -29,7 +29,7 @@ _STATUS = {0: "TW_OK", -1: "TW_ERR_INVALID_ARG", -2: "TW_ERR_UNSUPPORTED", -3: "
 
 EXPORTS = ["tw_version", "tw_workspace_bytes", "tw_ttp_score", "tw_ttp_score_phead", "tw_ttp_select", "tw_ttp_compact",
            "tw_ttp_compact_batched",
-           "tw_tree_ancestor_masks", "tw_tree_verify_attn", "tw_tree_accept", "tw_kv_commit", "tw_draft_topk",
+           "tw_tree_ancestor_masks", "tw_tree_verify_attn", "tw_tree_accept", "tw_kv_commit", "tw_draft_topk", "tw_draft_topk_logits",
            "tw_tree_build_workspace_bytes", "tw_tree_build", "tw_validate_tree",
            "tw_rbar"]
 
@@ -70,6 +70,8 @@ _lib.tw_kv_commit.restype = _i32
 _lib.tw_kv_commit.argtypes = [_vp, _vp, _i32, ctypes.POINTER(KvView), _i32, _vp, _i32, _vp, _vp]
 _lib.tw_draft_topk.restype = _i32
 _lib.tw_draft_topk.argtypes = [_vp, _i32, _i32, _i32, _vp, _vp, _vp]
+_lib.tw_draft_topk_logits.restype = _i32
+_lib.tw_draft_topk_logits.argtypes = [_vp, _i32, _i32, _i32, _vp, _vp, _vp]
 _lib.tw_tree_build_workspace_bytes.restype = _sz
 _lib.tw_tree_build_workspace_bytes.argtypes = [_i32, _i32, _i32]
 _lib.tw_tree_build.restype = _i32
@@ -206,6 +208,12 @@ def kv_commit(path: torch.Tensor, n_acc: torch.Tensor, views: Sequence[KvView], 
 def draft_topk(probs: torch.Tensor, E: int, ids: torch.Tensor, vals: torch.Tensor) -> None:
     n, V = probs.shape
     _check("tw_draft_topk", _lib.tw_draft_topk(_ptr(probs), n, V, E, _ptr(ids), _ptr(vals), _stream()))
+
+
+def draft_topk_logits(logits: torch.Tensor, E: int, ids: torch.Tensor, probs: torch.Tensor) -> None:
+    n, V = logits.shape
+    _check("tw_draft_topk_logits",
+           _lib.tw_draft_topk_logits(_ptr(logits), n, V, E, _ptr(ids), _ptr(probs), _stream()))
 
 
 def tree_build_workspace_bytes(B: int, N: int, T_max: int) -> int:

@@ -327,9 +327,20 @@ int32_t tw_draft_topk(const float* probs, int32_t n, int32_t V, int32_t E, int32
     hipStream_t s = (hipStream_t)stream;
     // vocabulary-sized rows with a small E: one read of the row and a short candidate list
     hipError_t err = hipSuccess;
-    if (launch_topk_rows(probs, n, V, E, ids, vals, s, &err)) return err == hipSuccess ? TW_OK : TW_ERR_LAUNCH;
+    if (launch_topk_rows(probs, n, V, E, ids, vals, false, s, &err)) return err == hipSuccess ? TW_OK : TW_ERR_LAUNCH;
     // otherwise: radix select of the survivors, then their rank order inside the same workgroup
     return launch_select(probs, n, V, E, ids, s, vals) == hipSuccess ? TW_OK : TW_ERR_LAUNCH;
+}
+
+int32_t tw_draft_topk_logits(const float* logits, int32_t n, int32_t V, int32_t E, int32_t* ids, float* probs,
+                             void* stream) {
+    if (n < 0 || V < 0 || E < 0 || E > V) return TW_ERR_INVALID_ARG;
+    if (E > 32 || V > (1 << 20)) return TW_ERR_UNSUPPORTED;
+    if (n == 0 || E == 0) return TW_OK;
+    if (!logits || !ids || !probs) return TW_ERR_INVALID_ARG;
+    hipError_t err = hipSuccess;
+    if (!launch_topk_rows(logits, n, V, E, ids, probs, true, (hipStream_t)stream, &err)) return TW_ERR_UNSUPPORTED;
+    return err == hipSuccess ? TW_OK : TW_ERR_LAUNCH;
 }
 
 size_t tw_tree_build_workspace_bytes(int32_t B, int32_t N, int32_t T_max) {

@@ -1,13 +1,18 @@
 // Rank-ordered top-E of vocabulary-sized rows for small E (the per-node expansion of the draft
-// tree by its E most probable tokens, Sec. 5.4 / App. A).  One workgroup per row, the row read
-// once with 16-byte loads and held in registers.
+// tree by its E most probable tokens, Sec. 5.4 / App. A), from probabilities or from logits.  One
+// workgroup per row; the row is read once, in chunks of 32768 values held in registers.
 //
 // The lanes form 64 groups that partition the row.  The E-th largest of the 64 group maxima is a
 // lower bound of the E-th largest value of the row (E groups hold a value at least that large), so
 // every winner, and every value tied with the last winner, is among the values not below that
 // bound.  For a row without massive ties those are about E values; they go to a short list in LDS
-// and are ranked there (larger value first, equal values lower index first).  A row whose list
-// overflows (many values tied at the bound) is handed to the general radix select.
+// and are ranked there (larger value first, equal values lower index first).  With several chunks
+// the group maxima run on from chunk to chunk, so the bound only rises and the list stays a
+// superset of the winners.  A row whose list overflows (many values tied at the bound) is handed
+// to the general radix select.
+//
+// From logits, the row maximum and the sum of exp(l - max) are carried along the same single read
+// (rescaled when a later chunk raises the maximum), and the winners leave as probabilities.
 #include "select_block.h"
 
 namespace tw {
@@ -15,71 +20,115 @@ namespace tw {
 constexpr int kTkCap = 1024;   // list entries
 typedef __attribute__((ext_vector_type(4))) float f32x4t;
 
-template <int NV, int THREADS>   // 16-byte pieces per lane, lanes per row
-__global__ __launch_bounds__(THREADS) void topk_rows_kernel(const float* __restrict__ probs, int V, int E,
+// NV 16-byte pieces per lane and chunk, THREADS lanes per row; kLogits: softmax of the row on the
+// way; kVec: rows are 16-byte aligned and a multiple of four long
+template <int NV, int THREADS, bool kLogits, bool kVec>
+__global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(4))) void topk_rows_kernel(const float* __restrict__ x, int V, int E,
                                                             int32_t* __restrict__ ids, float* __restrict__ vals) {
     constexpr int kWaves = THREADS / 64;
+    constexpr int kChunk = THREADS * NV * 4;
     __shared__ float s_max[THREADS];
     __shared__ uint32_t s_key[kTkCap];
     __shared__ uint32_t s_idx[kTkCap];
+    __shared__ float s_sum[kWaves];
     __shared__ uint32_t s_n;
     const int tid = threadIdx.x, lane = tid & 63;
-    const float* row = probs + (int64_t)blockIdx.x * V;
+    const float* row = x + (int64_t)blockIdx.x * V;
     int32_t* out = ids + (int64_t)blockIdx.x * E;
     float* out_v = vals + (int64_t)blockIdx.x * E;
-    const int n_pieces = V >> 2;   // V is a multiple of four here
 
-    // slots past the row hold -inf: below every finite value, and kept off the list by index too
-    f32x4t raw[NV];
-#pragma unroll
-    for (int u = 0; u < NV; ++u) {
-        const int piece = tid + u * THREADS;
-        raw[u] = f32x4t{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
-        if (piece < n_pieces) raw[u] = __builtin_nontemporal_load((const f32x4t*)row + piece);
-    }
-    float mx = -INFINITY;
-#pragma unroll
-    for (int u = 0; u < NV; ++u) mx = fmaxf(fmaxf(mx, fmaxf(raw[u][0], raw[u][1])), fmaxf(raw[u][2], raw[u][3]));
-    s_max[tid] = mx;
+    float G = -INFINITY;                        // group maximum over the chunks so far (lane l: group l)
+    float run_m = -INFINITY, lane_sum = 0.f;    // kLogits: row maximum so far, this lane's sum of exp(l - run_m)
     if (tid == 0) s_n = 0u;
-    __syncthreads();
-    // Lane l of every wavefront takes the maximum of the lanes l, l + 64, ... (64 groups that
-    // partition the row) and counts the group maxima above and not below its own: the E-th largest
-    // group maximum is the one with (above) < E <= (not below).  Every wavefront finds it for itself.
-    float gmax = s_max[lane];
+    for (int c0 = 0; c0 < V; c0 += kChunk) {
+        // slots past the row hold -inf: below every finite value, and kept off the list by index too
+        f32x4t raw[NV];
 #pragma unroll
-    for (int w = 1; w < kWaves; ++w) gmax = fmaxf(gmax, s_max[lane + 64 * w]);
-    int above = 0, not_below = 0;
+        for (int u = 0; u < NV; ++u) {
+            const int first = c0 + (tid + u * THREADS) * 4;
+            raw[u] = f32x4t{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+            if (kVec) {
+                if (first < V) raw[u] = __builtin_nontemporal_load((const f32x4t*)(row + first));
+            } else {
 #pragma unroll
-    for (int j = 0; j < 64; ++j) {
-        const float o = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(gmax), j));
-        above += o > gmax;
-        not_below += o >= gmax;
-    }
-    const uint64_t is_bound = __ballot(above < E && E <= not_below);
-    // finite input always has such a lane; lane 0 stands in otherwise, which only lengthens the list
-    const int src = is_bound ? __ffsll((unsigned long long)is_bound) - 1 : 0;
-    const float tau = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(gmax), src));
+                for (int c = 0; c < 4; ++c)
+                    if (first + c < V) raw[u][c] = __builtin_nontemporal_load(row + first + c);
+            }
+        }
+        float mx = -INFINITY;
 #pragma unroll
-    for (int u = 0; u < NV; ++u) {
-        const float pm = fmaxf(fmaxf(raw[u][0], raw[u][1]), fmaxf(raw[u][2], raw[u][3]));
-        if (pm >= tau && tid + u * THREADS < n_pieces) {
+        for (int u = 0; u < NV; ++u)
+            mx = fmaxf(fmaxf(mx, fmaxf(raw[u][0], raw[u][1])), fmaxf(raw[u][2], raw[u][3]));
+        if (c0 > 0) __syncthreads();   // every wavefront has read the maxima of the chunk before
+        s_max[tid] = mx;
+        __syncthreads();
+        // Lane l of every wavefront folds the lanes l, l + 64, ... into its group maximum and counts
+        // the group maxima above and not below its own: the E-th largest group maximum is the one
+        // with (above) < E <= (not below).  Every wavefront finds it for itself.
+        float gmax = s_max[lane];
 #pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                if (raw[u][c] >= tau) {
-                    const uint32_t pos = atomicAdd(&s_n, 1u);
-                    if (pos < (uint32_t)kTkCap) {
-                        s_key[pos] = order_key(raw[u][c]);
-                        s_idx[pos] = (uint32_t)((tid + u * THREADS) * 4 + c);
+        for (int w = 1; w < kWaves; ++w) gmax = fmaxf(gmax, s_max[lane + 64 * w]);
+        G = fmaxf(G, gmax);
+        int above = 0, not_below = 0;
+#pragma unroll
+        for (int j = 0; j < 64; ++j) {
+            const float o = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(G), j));
+            above += o > G;
+            not_below += o >= G;
+        }
+        const uint64_t is_bound = __ballot(above < E && E <= not_below);
+        // finite input always has such a lane; lane 0 stands in otherwise, which only lengthens the list
+        const int src = is_bound ? __ffsll((unsigned long long)is_bound) - 1 : 0;
+        const float tau = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(G), src));
+#pragma unroll
+        for (int u = 0; u < NV; ++u) {
+            const float pm = fmaxf(fmaxf(raw[u][0], raw[u][1]), fmaxf(raw[u][2], raw[u][3]));
+            if (pm >= tau) {
+                const int first = c0 + (tid + u * THREADS) * 4;
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    if (raw[u][c] >= tau && first + c < V) {
+                        const uint32_t pos = atomicAdd(&s_n, 1u);
+                        if (pos < (uint32_t)kTkCap) {
+                            s_key[pos] = order_key(raw[u][c]);
+                            s_idx[pos] = (uint32_t)(first + c);
+                        }
                     }
                 }
             }
         }
+        if (kLogits) {
+            float m_new = G;   // the row maximum so far: the largest group maximum
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) m_new = fmaxf(m_new, __shfl_xor(m_new, off, 64));
+            const float rescale = run_m == m_new ? 1.f : __expf(run_m - m_new);
+            float acc = 0.f;
+#pragma unroll
+            for (int u = 0; u < NV; ++u)
+                acc += (__expf(raw[u][0] - m_new) + __expf(raw[u][1] - m_new)) +
+                       (__expf(raw[u][2] - m_new) + __expf(raw[u][3] - m_new));
+            lane_sum = lane_sum * rescale + acc;
+            run_m = m_new;
+        }
+    }
+    if (kLogits) {
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) lane_sum += __shfl_xor(lane_sum, off, 64);
+        if (lane == 0) s_sum[tid >> 6] = lane_sum;
     }
     __syncthreads();
+    float total = 0.f;
+    if (kLogits) {
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) total += s_sum[w];
+    }
     const int L = (int)s_n;
     if (L > kTkCap) {   // the same for every lane of the workgroup
         select_block<0, THREADS>(row, V, E, out, out_v);
+        if (kLogits) {
+            __syncthreads();   // the winners' logits are in out_v
+            if (tid < E) out_v[tid] = __expf(out_v[tid] - run_m) / total;
+        }
         return;
     }
     for (int e = tid; e < L; e += THREADS) {
@@ -88,20 +137,28 @@ __global__ __launch_bounds__(THREADS) void topk_rows_kernel(const float* __restr
         for (int j = 0; j < L; ++j) rank += (s_key[j] > key) || (s_key[j] == key && s_idx[j] < idx);
         if (rank < E) {
             out[rank] = (int32_t)idx;
-            out_v[rank] = row[idx];
+            const float v = row[idx];
+            out_v[rank] = kLogits ? __expf(v - run_m) / total : v;
         }
     }
 }
 
-bool launch_topk_rows(const float* probs, int n, int V, int E, int32_t* ids, float* vals, hipStream_t s,
+bool launch_topk_rows(const float* x, int n, int V, int E, int32_t* ids, float* vals, bool logits, hipStream_t s,
                       hipError_t* err) {
-    // rows shorter than this are served as fast by the radix select; every group of lanes must
-    // own a value, the row must fit the registers, and the bound is only tight while E is far
-    // below the number of groups
-    if (E < 1 || E > 32 || V <= 3072 || V > 32768 || (V & 3) || ((uintptr_t)probs & 15)) return false;
+    // the bound is only tight while E is far below the number of groups; probability rows shorter
+    // than this are served as fast by the radix select
+    if (E < 1 || E > 32 || (!logits && V <= 3072)) return false;
+    const bool vec = (V & 3) == 0 && ((uintptr_t)x & 15) == 0;
     // 512 lanes with 16 pieces each: measured against 256 x 32 and 1024 x 8 (30.7 / 33.0 / 34.3 us
     // for 1280 rows of 32000)
-    hipLaunchKernelGGL((topk_rows_kernel<16, 512>), dim3(n), dim3(512), 0, s, probs, V, E, ids, vals);
+    const dim3 grid(n), block(512);
+    if (logits) {
+        if (vec) hipLaunchKernelGGL((topk_rows_kernel<16, 512, true, true>), grid, block, 0, s, x, V, E, ids, vals);
+        else hipLaunchKernelGGL((topk_rows_kernel<16, 512, true, false>), grid, block, 0, s, x, V, E, ids, vals);
+    } else {
+        if (vec) hipLaunchKernelGGL((topk_rows_kernel<16, 512, false, true>), grid, block, 0, s, x, V, E, ids, vals);
+        else hipLaunchKernelGGL((topk_rows_kernel<16, 512, false, false>), grid, block, 0, s, x, V, E, ids, vals);
+    }
     *err = hipGetLastError();
     return true;
 }

@@ -185,7 +185,8 @@ hipError_t launch_select(const float* scores, int B, int M, int R, int32_t* kept
                          float* ranked_vals = nullptr);
 // Rank-ordered top-E of long rows for small E in one read of the row; false when the shape is
 // not one it covers (nothing launched), otherwise *err holds the launch status.
-bool launch_topk_rows(const float* probs, int n, int V, int E, int32_t* ids, float* vals, hipStream_t s,
+// With `logits` the rows are logits and vals receives the winners' softmax probabilities.
+bool launch_topk_rows(const float* x, int n, int V, int E, int32_t* ids, float* vals, bool logits, hipStream_t s,
                       hipError_t* err);
 
 constexpr int kCompactMaxTensors = 64;

@@ -105,6 +105,11 @@ def test_argument_validation_without_launch():
     assert lib.tw_draft_topk(P, 2, 32000, 300, P, P, None) == tw.TW_ERR_UNSUPPORTED
     assert lib.tw_draft_topk(None, 2, 100, 10, P, P, None) == tw.TW_ERR_INVALID_ARG
     assert lib.tw_draft_topk(P, 0, 100, 10, P, P, None) == tw.TW_OK
+    assert lib.tw_draft_topk_logits(P, 2, 100, 101, P, P, None) == tw.TW_ERR_INVALID_ARG
+    assert lib.tw_draft_topk_logits(P, 2, 32000, 33, P, P, None) == tw.TW_ERR_UNSUPPORTED
+    assert lib.tw_draft_topk_logits(P, 2, (1 << 20) + 1, 10, P, P, None) == tw.TW_ERR_UNSUPPORTED
+    assert lib.tw_draft_topk_logits(None, 2, 100, 10, P, P, None) == tw.TW_ERR_INVALID_ARG
+    assert lib.tw_draft_topk_logits(P, 0, 100, 10, P, P, None) == tw.TW_OK
     tb = lambda **kw: lib.tw_tree_build(kw.get("cp", P), P, P, P, P, kw.get("N", 310), kw.get("B", 1),
                                         kw.get("T", 61), P, P, P, P, kw.get("ws", None), kw.get("ws_bytes", 0), None)
     assert tb(T=65) == tw.TW_ERR_UNSUPPORTED

@@ -895,10 +895,12 @@ def test_score_generic_path(tw):
 # draft-side tree build
 # ----------------------------------------------------------------------------
 @pytest.mark.parametrize("V,E", [(32000, 10), (301, 64), (50, 50), (7, 1), (32768, 32), (32000, 33), (1024, 1),
-                                 (4096, 5), (8192, 32), (8196, 10), (20000, 7), (32766, 10), (3076, 3)])
+                                 (4096, 5), (8192, 32), (8196, 10), (20000, 7), (32766, 10), (3076, 3),
+                                 (32001, 10), (65540, 10), (100003, 5), (151936, 10)])
 def test_draft_topk_bit_exact(tw, V, E):
-    # rows of 3073 to 32768 values (a multiple of four) with E <= 32 take the one-read kernel,
-    # whose rows with many ties at its bound fall back to the radix select inside the kernel
+    # rows of more than 3072 values with E <= 32 take the one-read kernel (16-byte loads when the rows
+    # are a multiple of four long, several chunks beyond 32768 values), whose rows with many ties at
+    # its bound fall back to the radix select inside the kernel
     g = torch.Generator().manual_seed(V)
     probs = torch.softmax(torch.randn(9, V, generator=g) * 4, dim=1)
     probs[1, : V // 2] = probs[1, 0]          # plateau of ties
@@ -918,6 +920,37 @@ def test_draft_topk_bit_exact(tw, V, E):
     torch.cuda.synchronize()
     wi, wv = oracle.draft_topk(probs, E)
     assert torch.equal(ids.cpu(), wi) and torch.equal(vals.cpu(), wv)
+
+
+@pytest.mark.parametrize("V,E", [(32000, 10), (32000, 32), (7, 1), (7, 5), (50, 32), (301, 10), (1024, 1), (4099, 3),
+                                 (32768, 32), (32772, 10), (70001, 10), (151936, 10)])
+def test_draft_topk_logits(tw, V, E):
+    """Top-E of softmax(logits) in one read: ids bit-exact (the order is decided on the logits),
+    probabilities to 2e-5 relative (fp32 exponentials whose argument carries one rounding of
+    |l - max| <= ~90, and an fp32 sum of V non-negative terms in lane, wavefront and workgroup
+    order: a few 1e-6 together)."""
+    g = torch.Generator().manual_seed(1000 + V)
+    lg = torch.randn(9, V, generator=g) * 4
+    lg[1, : V // 2] = lg[1, 0]                  # plateau of ties
+    lg[2] = 0.75                                # all equal
+    lg[3] = torch.round(lg[3] * 2) / 2          # few distinct values
+    lg[4] += 3000.0                             # a large common offset
+    lg[5] = -30.0                               # a few tokens carry all the mass
+    few = torch.randperm(V, generator=g)[: max(1, E // 2)]
+    lg[5, few] = torch.rand(few.numel(), generator=g) * 5
+    lg[6, -1] = lg[6].max() + 9.0               # the winner in the last slot
+    lg[7, 0] = lg[7].max()                      # a tie of the two largest
+    lg[8] *= 5.0                                # a very peaked row
+    if V > 40000:
+        lg[8, 33000:] += 30.0                   # a later chunk raises the running maximum
+    ids = torch.full((9, E), -7, dtype=torch.int32, device=DEV)
+    pr = torch.full((9, E), -7.0, dtype=torch.float32, device=DEV)
+    tw.draft_topk_logits(lg.to(DEV), E, ids, pr)
+    torch.cuda.synchronize()
+    wi, wp = oracle.draft_topk_logits(lg, E)
+    assert torch.equal(ids.cpu(), wi)
+    err = ((pr.cpu().double() - wp).abs() / (2e-5 * wp + 1e-37)).max()
+    assert float(err) <= 1.0, f"probability error ratio {float(err):.3f}"
 
 
 @pytest.mark.parametrize("E,K", [(10, 10), (20, 20), (40, 30)])
