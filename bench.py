@@ -185,6 +185,21 @@ def main():
         torch.cuda.synchronize()
         graph_ms = (time.perf_counter() - tg) * 1e3 / args.graph_iters
 
+    # the same step with its two independent chains (verify -> accept, score -> select -> compact) on two
+    # streams; beside the serial figure, which stays the headline because the per-kernel durations of
+    # the roofline are only meaningful when the kernels run alone
+    two_streams_ms = None
+    if args.graph_iters > 0:
+        side2 = torch.cuda.Stream()
+        for _ in range(3):
+            dw.step_two_streams(side2)
+        torch.cuda.synchronize()
+        t2s = time.perf_counter()
+        for _ in range(args.graph_iters):
+            dw.step_two_streams(side2)
+        torch.cuda.synchronize()
+        two_streams_ms = (time.perf_counter() - t2s) * 1e3 / args.graph_iters
+
     # single-instance latency of the graded kernel (one sequence, one layer: what batch-1 decoding
     # issues 32 times per step), launched eagerly and as 32 back-to-back launches of a HIP graph
     single_us = single_graph_us = None
@@ -414,7 +429,7 @@ def main():
                      "algorithmic_bytes_per_launch": vbytes, "kernel_ms_avg": ker_avg,
                      "kernel_ms_min": ker_ms[0], "kernel_ms_median": ker_ms[len(ker_ms) // 2]},
         "cpu_baseline": cpu,
-        "extras": {"stages": stages, "ms_per_step_hip_graph": graph_ms,
+        "extras": {"stages": stages, "ms_per_step_hip_graph": graph_ms, "ms_per_step_two_streams": two_streams_ms,
                    "verify_bf16_output_us_median": verify_bf16_us,
                    "same_box_library_kernels": box,
                    "verify_tokens_per_s_kernel_only": tokens / (ker_avg * 1e-3),

@@ -107,3 +107,19 @@ class DeviceWorkload:
             self.run_compact()
         self.run_verify()
         self.run_accept()
+
+    def step_two_streams(self, side: torch.cuda.Stream) -> None:
+        """The same pass with its two independent chains on two streams: verify -> accept on `side`,
+        score -> select -> compact on the current stream, which waits for `side` at the end.  The
+        chains share no buffer (each has its own workspace)."""
+        cur = torch.cuda.current_stream()
+        side.wait_stream(cur)
+        with torch.cuda.stream(side):
+            self.run_verify()
+            self.run_accept()
+        if self.has_score:
+            self.run_score()
+        self.run_select()
+        if self.compact_src:
+            self.run_compact()
+        cur.wait_stream(side)

@@ -1133,6 +1133,24 @@ def test_two_streams_at_once(runner):
             assert torch.equal(got.view(torch.uint8), want.view(torch.uint8))
 
 
+def test_step_with_its_chains_on_two_streams(runner):
+    # verify -> accept and score -> select -> compact touch disjoint buffers: run side by side they
+    # give the serial results bit for bit
+    dw = runner.DeviceWorkload(W.make_workload(W.replicate(W.CONFIGS["cfg1"], 5)), DEV)
+    outs = [dw.scores, dw.kept, dw.out, dw.n_acc, dw.path, dw.bonus] + list(dw.compact_dst)
+    dw.step()
+    torch.cuda.synchronize()
+    ref = [t.clone() for t in outs]
+    side = torch.cuda.Stream()
+    for _ in range(3):
+        for t in outs:
+            t.fill_(-1 if t.dtype in (torch.int32, torch.int64) else float("nan"))
+        dw.step_two_streams(side)
+        torch.cuda.synchronize()
+        for got, want in zip(outs, ref):
+            assert torch.equal(got.view(torch.uint8), want.view(torch.uint8))
+
+
 @pytest.mark.parametrize("name", ["cfg1", "cfg4"])
 def test_step_replays_from_a_hip_graph(runner, name):
     # the library only enqueues kernels on the caller's stream (no allocation, no synchronisation, no
