@@ -263,7 +263,7 @@ int32_t tw_draft_topk(const float* probs, int32_t n, int32_t V, int32_t E, int32
  *   logits [dev] [n][V] fp32 finite; ids [dev] [n][E] int32; probs [dev] [n][E] fp32.
  * Rows that are 16-byte aligned and a multiple of four long are read with
  * 16-byte loads; any other shape is accepted and read element by element.
- * Errors: INVALID_ARG (E > V, null pointers), UNSUPPORTED (E > 32, V > 2^20).
+ * Errors: INVALID_ARG (E > V, null pointers), UNSUPPORTED (E > 256, V > 2^20).
  */
 int32_t tw_draft_topk_logits(const float* logits, int32_t n, int32_t V, int32_t E, int32_t* ids, float* probs,
                              void* stream);

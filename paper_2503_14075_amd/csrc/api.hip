@@ -335,7 +335,7 @@ int32_t tw_draft_topk(const float* probs, int32_t n, int32_t V, int32_t E, int32
 int32_t tw_draft_topk_logits(const float* logits, int32_t n, int32_t V, int32_t E, int32_t* ids, float* probs,
                              void* stream) {
     if (n < 0 || V < 0 || E < 0 || E > V) return TW_ERR_INVALID_ARG;
-    if (E > 32 || V > (1 << 20)) return TW_ERR_UNSUPPORTED;
+    if (E > 256 || V > (1 << 20)) return TW_ERR_UNSUPPORTED;
     if (n == 0 || E == 0) return TW_OK;
     if (!logits || !ids || !probs) return TW_ERR_INVALID_ARG;
     hipError_t err = hipSuccess;

@@ -9,7 +9,7 @@
 // and are ranked there (larger value first, equal values lower index first).  With several chunks
 // the group maxima run on from chunk to chunk, so the bound only rises and the list stays a
 // superset of the winners.  A row whose list overflows (many values tied at the bound) is handed
-// to the general radix select.
+// to the general radix select, and so is every row when E is above 32.
 //
 // From logits, the row maximum and the sum of exp(l - max) are carried along the same single read
 // (rescaled when a later chunk raises the maximum), and the winners leave as probabilities.
@@ -18,13 +18,15 @@
 namespace tw {
 
 constexpr int kTkCap = 1024;   // list entries
+constexpr int kTkListE = 32;   // the bound of the group maxima is used up to this E (far below the 64 groups)
 typedef __attribute__((ext_vector_type(4))) float f32x4t;
 
 // NV 16-byte pieces per lane and chunk, THREADS lanes per row; kLogits: softmax of the row on the
 // way; kVec: rows are 16-byte aligned and a multiple of four long
 template <int NV, int THREADS, bool kLogits, bool kVec>
-__global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(4))) void topk_rows_kernel(const float* __restrict__ x, int V, int E,
-                                                            int32_t* __restrict__ ids, float* __restrict__ vals) {
+// (held to 128 registers: two workgroups of 512 per compute unit)
+__global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(4))) void topk_rows_kernel(
+    const float* __restrict__ x, int V, int E, int32_t* __restrict__ ids, float* __restrict__ vals) {
     constexpr int kWaves = THREADS / 64;
     constexpr int kChunk = THREADS * NV * 4;
     __shared__ float s_max[THREADS];
@@ -69,29 +71,31 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(4))) vo
 #pragma unroll
         for (int w = 1; w < kWaves; ++w) gmax = fmaxf(gmax, s_max[lane + 64 * w]);
         G = fmaxf(G, gmax);
-        int above = 0, not_below = 0;
+        if (E <= kTkListE) {
+            int above = 0, not_below = 0;
 #pragma unroll
-        for (int j = 0; j < 64; ++j) {
-            const float o = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(G), j));
-            above += o > G;
-            not_below += o >= G;
-        }
-        const uint64_t is_bound = __ballot(above < E && E <= not_below);
-        // finite input always has such a lane; lane 0 stands in otherwise, which only lengthens the list
-        const int src = is_bound ? __ffsll((unsigned long long)is_bound) - 1 : 0;
-        const float tau = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(G), src));
+            for (int j = 0; j < 64; ++j) {
+                const float o = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(G), j));
+                above += o > G;
+                not_below += o >= G;
+            }
+            const uint64_t is_bound = __ballot(above < E && E <= not_below);
+            // finite input always has such a lane; lane 0 stands in otherwise, which only lengthens the list
+            const int src = is_bound ? __ffsll((unsigned long long)is_bound) - 1 : 0;
+            const float tau = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(G), src));
 #pragma unroll
-        for (int u = 0; u < NV; ++u) {
-            const float pm = fmaxf(fmaxf(raw[u][0], raw[u][1]), fmaxf(raw[u][2], raw[u][3]));
-            if (pm >= tau) {
-                const int first = c0 + (tid + u * THREADS) * 4;
+            for (int u = 0; u < NV; ++u) {
+                const float pm = fmaxf(fmaxf(raw[u][0], raw[u][1]), fmaxf(raw[u][2], raw[u][3]));
+                if (pm >= tau) {
+                    const int first = c0 + (tid + u * THREADS) * 4;
 #pragma unroll
-                for (int c = 0; c < 4; ++c) {
-                    if (raw[u][c] >= tau && first + c < V) {
-                        const uint32_t pos = atomicAdd(&s_n, 1u);
-                        if (pos < (uint32_t)kTkCap) {
-                            s_key[pos] = order_key(raw[u][c]);
-                            s_idx[pos] = (uint32_t)(first + c);
+                    for (int c = 0; c < 4; ++c) {
+                        if (raw[u][c] >= tau && first + c < V) {
+                            const uint32_t pos = atomicAdd(&s_n, 1u);
+                            if (pos < (uint32_t)kTkCap) {
+                                s_key[pos] = order_key(raw[u][c]);
+                                s_idx[pos] = (uint32_t)(first + c);
+                            }
                         }
                     }
                 }
@@ -123,7 +127,7 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(4))) vo
         for (int w = 0; w < kWaves; ++w) total += s_sum[w];
     }
     const int L = (int)s_n;
-    if (L > kTkCap) {   // the same for every lane of the workgroup
+    if (L > kTkCap || E > kTkListE) {   // the same for every lane of the workgroup
         select_block<0, THREADS>(row, V, E, out, out_v);
         if (kLogits) {
             __syncthreads();   // the winners' logits are in out_v
@@ -147,7 +151,8 @@ bool launch_topk_rows(const float* x, int n, int V, int E, int32_t* ids, float* 
                       hipError_t* err) {
     // the bound is only tight while E is far below the number of groups; probability rows shorter
     // than this are served as fast by the radix select
-    if (E < 1 || E > 32 || (!logits && V <= 3072)) return false;
+    // (a larger E from logits still takes this kernel for its softmax sums, with the radix select inside)
+    if (E < 1 || E > 256 || (!logits && (E > kTkListE || V <= 3072))) return false;
     const bool vec = (V & 3) == 0 && ((uintptr_t)x & 15) == 0;
     // 512 lanes with 16 pieces each: measured against 256 x 32 and 1024 x 8 (30.7 / 33.0 / 34.3 us
     // for 1280 rows of 32000)

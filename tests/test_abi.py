@@ -106,7 +106,7 @@ def test_argument_validation_without_launch():
     assert lib.tw_draft_topk(None, 2, 100, 10, P, P, None) == tw.TW_ERR_INVALID_ARG
     assert lib.tw_draft_topk(P, 0, 100, 10, P, P, None) == tw.TW_OK
     assert lib.tw_draft_topk_logits(P, 2, 100, 101, P, P, None) == tw.TW_ERR_INVALID_ARG
-    assert lib.tw_draft_topk_logits(P, 2, 32000, 33, P, P, None) == tw.TW_ERR_UNSUPPORTED
+    assert lib.tw_draft_topk_logits(P, 2, 32000, 257, P, P, None) == tw.TW_ERR_UNSUPPORTED
     assert lib.tw_draft_topk_logits(P, 2, (1 << 20) + 1, 10, P, P, None) == tw.TW_ERR_UNSUPPORTED
     assert lib.tw_draft_topk_logits(None, 2, 100, 10, P, P, None) == tw.TW_ERR_INVALID_ARG
     assert lib.tw_draft_topk_logits(P, 0, 100, 10, P, P, None) == tw.TW_OK

@@ -923,7 +923,8 @@ def test_draft_topk_bit_exact(tw, V, E):
 
 
 @pytest.mark.parametrize("V,E", [(32000, 10), (32000, 32), (7, 1), (7, 5), (50, 32), (301, 10), (1024, 1), (4099, 3),
-                                 (32768, 32), (32772, 10), (70001, 10), (151936, 10)])
+                                 (32768, 32), (32772, 10), (70001, 10), (151936, 10), (32000, 33), (300, 256),
+                                 (40000, 100)])
 def test_draft_topk_logits(tw, V, E):
     """Top-E of softmax(logits) in one read: ids bit-exact (the order is decided on the logits),
     probabilities to 2e-5 relative (fp32 exponentials whose argument carries one rounding of
