@@ -32,6 +32,7 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(4))) vo
     __shared__ float s_max[THREADS];
     __shared__ uint32_t s_key[kTkCap];
     __shared__ uint32_t s_idx[kTkCap];
+    __shared__ float s_val[kTkCap];
     __shared__ float s_sum[kWaves];
     __shared__ uint32_t s_n;
     const int tid = threadIdx.x, lane = tid & 63;
@@ -95,6 +96,7 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(4))) vo
                             if (pos < (uint32_t)kTkCap) {
                                 s_key[pos] = order_key(raw[u][c]);
                                 s_idx[pos] = (uint32_t)(first + c);
+                                s_val[pos] = raw[u][c];
                             }
                         }
                     }
@@ -135,13 +137,23 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(4))) vo
         }
         return;
     }
-    for (int e = tid; e < L; e += THREADS) {
-        const uint32_t key = s_key[e], idx = s_idx[e];
+    // rank of a list entry = the entries ahead of it; eight lanes share an entry, each counts every
+    // eighth of the list (the trip count is the same for every lane, the shuffles see all of them)
+    for (int e0 = 0; e0 < L; e0 += THREADS / 8) {
+        const int e = e0 + (tid >> 3);
+        uint32_t key = 0u, idx = 0u;
         int rank = 0;
-        for (int j = 0; j < L; ++j) rank += (s_key[j] > key) || (s_key[j] == key && s_idx[j] < idx);
-        if (rank < E) {
+        if (e < L) {
+            key = s_key[e];
+            idx = s_idx[e];
+            for (int j = tid & 7; j < L; j += 8) rank += (s_key[j] > key) || (s_key[j] == key && s_idx[j] < idx);
+        }
+        rank += __shfl_xor(rank, 1, 64);
+        rank += __shfl_xor(rank, 2, 64);
+        rank += __shfl_xor(rank, 4, 64);
+        if (e < L && (tid & 7) == 0 && rank < E) {
             out[rank] = (int32_t)idx;
-            const float v = row[idx];
+            const float v = s_val[e];
             out_v[rank] = kLogits ? __expf(v - run_m) / total : v;
         }
     }
