@@ -76,12 +76,14 @@ def _check(rc: int, what: str) -> None:
 def ttp_score(q_sel: torch.Tensor, k: torch.Tensor, n_q: Sequence[int], q_pos0: Sequence[int],
               n_tot: Sequence[int], k_row_off: Sequence[int], v_start: int, M: int, scale: float,
               causal: bool = True) -> torch.Tensor:
-    """scores [B][M] in fp64."""
+    """scores [B][M] in fp64.  k may hold fewer heads than q_sel (grouped-query attention: query
+    head h reads key head h // (H // H_kv))."""
     B, n_q_max, H, d_h = q_sel.shape
-    assert k.shape[1:] == (H, d_h) and k.dtype == q_sel.dtype
+    H_kv = k.shape[1]
+    assert k.shape[2] == d_h and H % H_kv == 0 and k.dtype == q_sel.dtype
     out = torch.zeros(B, M, dtype=torch.float64)
     a, b_, c, d = _i32(n_q), _i32(q_pos0), _i32(n_tot), _i64(k_row_off)
-    rc = lib().orc_ttp_score(_p(q_sel), _p(k), _dtype_code(k), B, H, d_h, n_q_max, _p(a), _p(b_),
+    rc = lib().orc_ttp_score(_p(q_sel), _p(k), _dtype_code(k), B, H, H_kv, d_h, n_q_max, _p(a), _p(b_),
                              _p(c), _p(d), int(v_start), int(M), ctypes.c_double(scale),
                              int(bool(causal)), _p(out))
     _check(rc, "ttp_score")
@@ -141,9 +143,11 @@ def tree_verify_attn(q: torch.Tensor, k_pool: torch.Tensor, v_pool: torch.Tensor
                      ctx_len: Sequence[int], n_nodes: Sequence[int], parent, scale: float,
                      row_off: Optional[Sequence[int]] = None, page_table=None,
                      page_rows: int = 16) -> torch.Tensor:
-    """out [B][T_max][H][d_h] fp64 (rows past n_nodes[b] are zero)."""
+    """out [B][T_max][H][d_h] fp64 (rows past n_nodes[b] are zero).  The pools may hold fewer heads
+    than q (grouped-query attention: query head h reads key/value head h // (H // H_kv))."""
     B, T_max, H, d_h = q.shape
-    assert k_pool.shape[1:] == (H, d_h) and v_pool.shape == k_pool.shape
+    H_kv = k_pool.shape[1]
+    assert k_pool.shape[2] == d_h and H % H_kv == 0 and v_pool.shape == k_pool.shape
     assert k_pool.dtype == q.dtype == v_pool.dtype
     rows, offs = cache_rows(ctx_len, n_nodes, row_off, page_table, page_rows)
     if rows.numel() and int(rows.max()) >= k_pool.shape[0]:
@@ -151,7 +155,7 @@ def tree_verify_attn(q: torch.Tensor, k_pool: torch.Tensor, v_pool: torch.Tensor
     par = _i32(parent).view(B, T_max)
     out = torch.zeros(B, T_max, H, d_h, dtype=torch.float64)
     a, c = _i32(n_nodes), _i32(ctx_len)
-    rc = lib().orc_tree_verify_attn(_p(q), _p(k_pool), _p(v_pool), _dtype_code(q), B, H, d_h, T_max,
+    rc = lib().orc_tree_verify_attn(_p(q), _p(k_pool), _p(v_pool), _dtype_code(q), B, H, H_kv, d_h, T_max,
                                     _p(a), _p(c), _p(rows), _p(offs), _p(par),
                                     ctypes.c_double(scale), _p(out))
     _check(rc, "tree_verify_attn")

@@ -57,14 +57,18 @@ int orc_max_threads(void) {
  * scoring rows of the attention weight on visual key v_start + m.
  *
  *   q_sel  [B][n_q_max][H][d_h]   rows beyond n_q[b] unused
- *   k      rows of sequence b start at row k_row_off[b]
+ *   k      rows of H_kv heads; rows of sequence b start at row k_row_off[b].  H_kv == H is
+ *          ordinary multi-head attention; H = g * H_kv is the grouped-query attention of the
+ *          Qwen2.5-VL base model among those of Sec. 6: query head h reads key head h / g.
  *   scores [B][M] fp64
  */
-int orc_ttp_score(const void* q_sel, const void* k, int dtype, int B, int H, int d_h, int n_q_max,
+int orc_ttp_score(const void* q_sel, const void* k, int dtype, int B, int H, int H_kv, int d_h, int n_q_max,
                   const int32_t* n_q, const int32_t* q_pos0, const int32_t* n_tot,
                   const int64_t* k_row_off, int v_start, int M, double scale, int causal,
                   double* scores) {
     if (!q_sel || !k || !scores || B < 0 || M < 0) return -1;
+    if (H < 1 || H_kv < 1 || H % H_kv) return -1;
+    const int group = H / H_kv;   /* grouped-query attention: query head h reads key head h / group */
     for (int b = 0; b < B; ++b) {
         if (v_start < 0 || v_start + M > n_tot[b] || n_q[b] < 1 || n_q[b] > n_q_max) return -1;
         if (q_pos0[b] < 0 || q_pos0[b] + n_q[b] > n_tot[b]) return -1;
@@ -91,7 +95,7 @@ int orc_ttp_score(const void* q_sel, const void* k, int dtype, int B, int H, int
                     int64_t qo = (((int64_t)b * n_q_max + i) * H + h) * d_h;
                     double mx = -INFINITY;
                     for (int j = 0; j < nvis; ++j) {
-                        int64_t ko = ((k_row_off[b] + j) * H + h) * (int64_t)d_h;
+                        int64_t ko = ((k_row_off[b] + j) * H_kv + h / group) * (int64_t)d_h;
                         double dot = 0.0;
                         for (int c = 0; c < d_h; ++c)
                             dot += widen(q_sel, dtype, qo + c) * widen(k, dtype, ko + c);
@@ -207,12 +211,15 @@ int orc_tree_ancestors(const int32_t* parent, int T, uint64_t* anc) {
  * ctx_len[b] + u.  Cache row r of instance b is pool row rows[rows_off[b] + r].
  *
  *   q   [B][T_max][H][d_h]       out [B][T_max][H][d_h] fp64 (rows >= n_nodes[b] untouched)
+ *   k_pool, v_pool  rows of H_kv heads (H_kv == H, or grouped-query attention as in orc_ttp_score)
  */
 int orc_tree_verify_attn(const void* q, const void* k_pool, const void* v_pool, int dtype, int B,
-                         int H, int d_h, int T_max, const int32_t* n_nodes, const int32_t* ctx_len,
+                         int H, int H_kv, int d_h, int T_max, const int32_t* n_nodes, const int32_t* ctx_len,
                          const int64_t* rows, const int64_t* rows_off, const int32_t* parent,
                          double scale, double* out) {
     if (!q || !k_pool || !v_pool || !out || !parent || T_max < 1 || T_max > 64) return -1;
+    if (H < 1 || H_kv < 1 || H % H_kv) return -1;
+    const int group = H / H_kv;   /* query head h reads key/value head h / group */
     for (int b = 0; b < B; ++b) {
         if (n_nodes[b] < 1 || n_nodes[b] > T_max || ctx_len[b] < 0) return -1;
         uint64_t tmp[64];
@@ -232,7 +239,7 @@ int orc_tree_verify_attn(const void* q, const void* k_pool, const void* v_pool, 
                 for (int j = 0; j < C + T; ++j) {
                     int vis = j < C || ((anc[t] >> (j - C)) & 1);
                     if (!vis) { s[j] = -INFINITY; continue; }
-                    int64_t ko = (rw[j] * H + h) * (int64_t)d_h;
+                    int64_t ko = (rw[j] * H_kv + h / group) * (int64_t)d_h;
                     double dot = 0.0;
                     for (int c = 0; c < d_h; ++c)
                         dot += widen(q, dtype, qo + c) * widen(k_pool, dtype, ko + c);
@@ -248,7 +255,7 @@ int orc_tree_verify_attn(const void* q, const void* k_pool, const void* v_pool, 
                 for (int c = 0; c < d_h; ++c) o[c] = 0.0;
                 for (int j = 0; j < C + T; ++j) {
                     if (s[j] == 0.0) continue;
-                    int64_t vo = (rw[j] * H + h) * (int64_t)d_h;
+                    int64_t vo = (rw[j] * H_kv + h / group) * (int64_t)d_h;
                     double w = s[j] / l;
                     for (int c = 0; c < d_h; ++c) o[c] += w * widen(v_pool, dtype, vo + c);
                 }

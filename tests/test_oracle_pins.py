@@ -282,6 +282,45 @@ def test_verify_tree_equals_per_branch_causal_runs(seed):
     assert seen == set(range(T))
 
 
+def test_grouped_query_attention_reads_key_head_h_div_g():
+    """Grouped-query attention (the Qwen2.5-VL base model among those of Sec. 6): query head h of
+    H = g * H_kv reads key/value head h // g.  Checked against the library routines run on the
+    key/value heads written out g times each (repeat_interleave; the interleaved order h % H_kv
+    would fail, the heads differ)."""
+    H, H_kv, d, C, T = 6, 2, 8, 11, 9
+    g = H // H_kv
+    par = W.random_parent_tree(W.HostRng(5, 1), T, 4)
+    q = _rand(21, 1, (1, T, H, d))
+    k = _rand(21, 2, (C + T, H_kv, d))
+    v = _rand(21, 3, (C + T, H_kv, d))
+    got = oracle.tree_verify_attn(q, k, v, [C], [T], [par], 0.4, row_off=[0])[0]
+    kx, vx = k.repeat_interleave(g, dim=1), v.repeat_interleave(g, dim=1)
+    for leaf in [i for i in range(T) if i not in par]:
+        chain = []
+        u = leaf
+        while u >= 0:
+            chain.append(u)
+            u = par[u]
+        chain.reverse()
+        rows = list(range(C)) + [C + u for u in chain]
+        want = _causal_library(q[0, chain], kx[rows], vx[rows], 0.4)
+        for pos, u in enumerate(chain):
+            assert torch.allclose(got[u], want[pos], atol=1e-12)
+    wrong = oracle.tree_verify_attn(q, k.repeat(1, g, 1), v.repeat(1, g, 1), [C], [T], [par], 0.4, row_off=[0])[0]
+    assert not torch.allclose(got, wrong, atol=1e-3)          # the two head orders are told apart
+    # the score: library attention map over the expanded keys
+    M, N, n_q, v0 = 21, 7, 4, 1
+    n_tot = v0 + M + N
+    qs = _rand(22, 1, (1, n_q, H, d))
+    ks = _rand(22, 2, (n_tot, H_kv, d))
+    pos0 = n_tot - n_q
+    sc = oracle.ttp_score(qs, ks, [n_q], [pos0], [n_tot], [0], v0, M, 0.3, True)[0]
+    A = _library_attention_map(qs[0], ks.repeat_interleave(g, dim=1), pos0, 0.3, True)
+    assert torch.allclose(sc, A[:, :, v0:v0 + M].sum(dim=(0, 1)) / (H * n_q), rtol=0, atol=1e-12)
+    with pytest.raises(AssertionError):
+        oracle.ttp_score(qs[:, :, :5].contiguous(), ks, [n_q], [pos0], [n_tot], [0], v0, M, 0.3, True)
+
+
 def test_verify_closed_forms_constant_v_constant_k_star_and_single():
     H, d, C, T = 2, 8, 9, 6
     par = [-1, 0, 0, 1, 1, 2]
