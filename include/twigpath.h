@@ -211,6 +211,21 @@ int32_t tw_tree_verify_attn(const void* q, const tw_kv_view* k, const tw_kv_view
                             void* out, int32_t out_dtype, void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * The same attention for a base model with grouped-query attention (Qwen2.5-VL
+ * among the base VLMs of Sec. 6): q and out hold H_q = q_heads_per_kv * k->H
+ * heads, the views' rows hold k->H key/value heads, and query head h reads
+ * key/value head h / q_heads_per_kv.  q_heads_per_kv = 1 is tw_tree_verify_attn.
+ * The workspace is sized by tw_workspace_bytes with H = H_q.
+ * Errors as tw_tree_verify_attn, plus INVALID_ARG (q_heads_per_kv < 1) and
+ * UNSUPPORTED (q_heads_per_kv > 64, H_q > 65535).
+ */
+int32_t tw_tree_verify_attn_gqa(const void* q, const tw_kv_view* k, const tw_kv_view* v,
+                                int32_t q_heads_per_kv, const int32_t* ctx_len, int32_t max_ctx_len,
+                                const int32_t* parent, const int32_t* n_nodes, int32_t T_max, int32_t B,
+                                float scale, void* out, int32_t out_dtype, void* ws, size_t ws_bytes,
+                                void* stream);
+
+/*
  * Greedy acceptance walk with bonus token (Sec. 5.4, App. A, last steps of
  * Alg. 2; a chain is the sequence case of Alg. 1).  argmax[b][i] is the target
  * model's prediction for the token after node i.  A non-root node is matched

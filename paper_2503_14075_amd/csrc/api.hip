@@ -207,7 +207,17 @@ int32_t tw_tree_verify_attn(const void* q, const tw_kv_view* k, const tw_kv_view
                             const int32_t* ctx_len, int32_t max_ctx_len, const int32_t* parent,
                             const int32_t* n_nodes, int32_t T_max, int32_t B, float scale,
                             void* out, int32_t out_dtype, void* ws, size_t ws_bytes, void* stream) {
-    if (B < 0 || T_max < 1 || max_ctx_len < 0) return TW_ERR_INVALID_ARG;
+    return tw_tree_verify_attn_gqa(q, k, v, 1, ctx_len, max_ctx_len, parent, n_nodes, T_max, B, scale, out,
+                                   out_dtype, ws, ws_bytes, stream);
+}
+
+int32_t tw_tree_verify_attn_gqa(const void* q, const tw_kv_view* k, const tw_kv_view* v,
+                                int32_t q_heads_per_kv, const int32_t* ctx_len, int32_t max_ctx_len,
+                                const int32_t* parent, const int32_t* n_nodes, int32_t T_max, int32_t B,
+                                float scale, void* out, int32_t out_dtype, void* ws, size_t ws_bytes,
+                                void* stream) {
+    if (B < 0 || T_max < 1 || max_ctx_len < 0 || q_heads_per_kv < 1) return TW_ERR_INVALID_ARG;
+    if (q_heads_per_kv > 64) return TW_ERR_UNSUPPORTED;
     if (T_max > TW_MAX_TREE) return TW_ERR_UNSUPPORTED;
     if (out_dtype != TW_F32 && out_dtype != TW_BF16) return TW_ERR_UNSUPPORTED;
     if (B == 0) return TW_OK;
@@ -233,7 +243,9 @@ int32_t tw_tree_verify_attn(const void* q, const tw_kv_view* k, const tw_kv_view
     a.n_nodes = n_nodes;
     a.T_max = T_max;
     a.B = B;
-    a.H = k->H;
+    if ((int64_t)k->H * q_heads_per_kv > 65535) return TW_ERR_UNSUPPORTED;
+    a.H = k->H * q_heads_per_kv;
+    a.group = q_heads_per_kv;
     a.d_h = k->d_h;
     a.max_rows = max_rows;
     a.scale = scale;

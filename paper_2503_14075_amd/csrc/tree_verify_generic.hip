@@ -40,6 +40,7 @@ __global__ __launch_bounds__(kGenThreads) void verify_generic_kernel(VerifyArgs 
     float* sV = sK + kGenTile * ld;          // [kGenTile][d_h]
     float* sP = sV + kGenTile * d_h;         // [64][kGenTile + 1]
     const int h = blockIdx.x, b = blockIdx.y, split = blockIdx.z;
+    const int h_kv = h / a.group;   // the key/value head this query head reads
     const int tid = threadIdx.x;
     int T = a.n_nodes[b];
     T = T < 1 ? 1 : (T > a.T_max ? a.T_max : T);
@@ -102,8 +103,8 @@ __global__ __launch_bounds__(kGenThreads) void verify_generic_kernel(VerifyArgs 
             kreg[u] = make_float4(0.f, 0.f, 0.f, 0.f);
             vreg[u] = make_float4(0.f, 0.f, 0.f, 0.f);
             if (r < kGenTile && base + r < r_end) {
-                kreg[u] = ld4<TIn>(kb + (pool_row(a.k, b, base + r) * a.H + h) * d_h + 4 * c4);
-                vreg[u] = ld4<TIn>(vb + (pool_row(a.v, b, base + r) * a.H + h) * d_h + 4 * c4);
+                kreg[u] = ld4<TIn>(kb + (pool_row(a.k, b, base + r) * a.k.H + h_kv) * d_h + 4 * c4);
+                vreg[u] = ld4<TIn>(vb + (pool_row(a.v, b, base + r) * a.k.H + h_kv) * d_h + 4 * c4);
             }
         }
     };

@@ -445,11 +445,11 @@ __global__ __launch_bounds__(kMfThreads, 2) void verify_mfma_kernel(VerifyArgs a
     // lane's share of a chunk load: row (lane / lanes_per_row) + rows_per_load * j,
     // 16-byte column lane % lanes_per_row of the head's segment
     const int ld_row = lane / Cf::kLanesPerRow, ld_col = lane % Cf::kLanesPerRow;
-    const uint32_t pool_stride = (uint32_t)(a.H * Cf::kRowB);
+    const uint32_t pool_stride = (uint32_t)(a.k.H * Cf::kRowB);   // a cache row holds the key/value heads
     // loads past the split re-read its last row (cached) and are masked
     const int last_row = sq.r_end > sq.r_begin ? sq.r_end - 1 : sq.r_begin;
     const int step = kChunk * n_phase;
-    const SeqAddr<PAGED> ad(a, b, hc, Cf::kRowB, pool_stride, last_row);
+    const SeqAddr<PAGED> ad(a, b, hc / a.group, Cf::kRowB, pool_stride, last_row);   // query head -> its key/value head
 
     // Paged caches: the page of every row this lane loads, looked up two chunks ahead
     // so the dependent data loads never wait on a table read.
@@ -535,10 +535,10 @@ __global__ __launch_bounds__(kMfThreads, 2) void verify_mfma_pair_kernel(VerifyA
     const int ld_row = lane / Cf::kLanesPerRow, ld_col = lane % Cf::kLanesPerRow;
     const int dst_off = blk == 0 ? 0 : kChunk * Cf::kKStride;
     const int dst_stride = blk == 0 ? Cf::kKStride : Cf::kVStride;
-    const uint32_t pool_stride = (uint32_t)(a.H * Cf::kRowB);
+    const uint32_t pool_stride = (uint32_t)(a.k.H * Cf::kRowB);   // a cache row holds the key/value heads
     const int last_row = sq.r_end > sq.r_begin ? sq.r_end - 1 : sq.r_begin;
     const int step = kChunk * n_phase;
-    const SeqAddr<PAGED> ad(a, b, hc, Cf::kRowB, pool_stride, last_row);
+    const SeqAddr<PAGED> ad(a, b, hc / a.group, Cf::kRowB, pool_stride, last_row);   // query head -> its key/value head
     // the even wavefront of a pair streams K, the odd one V
     const unsigned char* seq_base = blk == 0 ? ad.k_seq : ad.v_seq;
 

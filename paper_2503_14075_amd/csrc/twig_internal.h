@@ -119,7 +119,8 @@ struct VerifyArgs {
     const int32_t* n_nodes;
     float* part_o;   // [n_splits][B][H][T_max][d_h] unnormalised partial outputs
     float* part_ml;  // [n_splits][B][H][T_max][2] running max, running sum
-    int32_t T_max, B, H, d_h;
+    int32_t T_max, B, H, d_h;   // H: query heads = group * (heads of a cache row, k.H)
+    int32_t group;              // query heads per key/value head (1: multi-head attention)
     int32_t n_splits, max_rows;
     int32_t n_blk, n_phase, heads_per_wg;   // wavefront layout of the matrix-core kernel
     float scale;

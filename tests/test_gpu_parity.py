@@ -59,7 +59,11 @@ def gpu_verify(tw, q, k, v, ctx_len, n_nodes, parents, scale, row_off=None, page
     nbytes = tw.workspace_bytes(tw.TW_CALL_TREE_VERIFY_ATTN, B, T_max, H, d_h, max_ctx + T_max)
     ws = torch.empty(max(nbytes, 4) // 4, dtype=torch.float32, device=DEV) if nbytes else None
     out = torch.full((B, T_max, H, d_h), float("nan"), dtype=torch.float32, device=DEV)
-    tw.tree_verify_attn(qd, kv, vv, _i32(ctx_len), max_ctx, _i32(parents), _i32(n_nodes), scale, out, ws)
+    if k.shape[1] == H:
+        tw.tree_verify_attn(qd, kv, vv, _i32(ctx_len), max_ctx, _i32(parents), _i32(n_nodes), scale, out, ws)
+    else:   # fewer key/value heads than query heads: the grouped-query entry point
+        tw.tree_verify_attn_gqa(qd, kv, vv, H // k.shape[1], _i32(ctx_len), max_ctx, _i32(parents), _i32(n_nodes),
+                                scale, out, ws)
     torch.cuda.synchronize()
     return out.cpu()
 
@@ -78,7 +82,7 @@ def check_verify(tw, q, k, v, ctx_len, n_nodes, parents, scale, tol=ATTN_TOL, **
     return worst
 
 
-def make_case(seed, B, H, d_h, ctx_len, T_max, dtype, trees, kv_std=0.5, q_std=None, gap=3):
+def make_case(seed, B, H, d_h, ctx_len, T_max, dtype, trees, kv_std=0.5, q_std=None, gap=3, H_kv=None):
     q_std = 1.0 / math.sqrt(d_h) if q_std is None else q_std
     rows = [c + T_max for c in ctx_len]
     off, acc = [], gap
@@ -86,8 +90,8 @@ def make_case(seed, B, H, d_h, ctx_len, T_max, dtype, trees, kv_std=0.5, q_std=N
         off.append(acc)
         acc += r + gap
     q = W.normal(seed, 1, (B, T_max, H, d_h), q_std, dtype)
-    k = W.normal(seed, 2, (acc, H, d_h), kv_std, dtype)
-    v = W.normal(seed, 3, (acc, H, d_h), kv_std, dtype)
+    k = W.normal(seed, 2, (acc, H_kv or H, d_h), kv_std, dtype)
+    v = W.normal(seed, 3, (acc, H_kv or H, d_h), kv_std, dtype)
     return q, k, v, off
 
 
@@ -128,6 +132,41 @@ def test_verify_ragged_nodes_and_odd_head_count(tw):
     trees = [W.random_parent_tree(W.HostRng(11, b), n, 5) for b, n in enumerate(n_nodes)]
     q, k, v, off = make_case(12, B, H, d_h, ctx, T_max, torch.bfloat16, trees)
     check_verify(tw, q, k, v, ctx, n_nodes, padded(trees, T_max), 1 / math.sqrt(d_h), row_off=off)
+
+
+@pytest.mark.parametrize("B,H,H_kv,T,dtype,d_h", [
+    (2, 28, 4, 26, torch.bfloat16, 128),     # Qwen2.5-VL-7B heads; one head per workgroup, split cache
+    (30, 28, 4, 26, torch.bfloat16, 128),    # four query heads per workgroup, groups of seven straddle them
+    (14, 28, 4, 64, torch.bfloat16, 128),    # two node blocks
+    (3, 8, 2, 33, torch.bfloat16, 64),
+    (2, 12, 3, 20, torch.float32, 128),      # fp32 vector kernel
+    (2, 6, 1, 9, torch.bfloat16, 40),        # one key/value head for all query heads, odd head size
+])
+def test_verify_grouped_query_attention(tw, B, H, H_kv, T, dtype, d_h):
+    # q and out have H heads, the cache rows H_kv: query head h reads key/value head h // (H // H_kv)
+    ctx = [(97 * b + 300) % 700 for b in range(B)]
+    trees = [W.random_parent_tree(W.HostRng(T, b), T, 6) for b in range(B)]
+    q, k, v, off = make_case(300 + H, B, H, d_h, ctx, T, dtype, trees, H_kv=H_kv)
+    check_verify(tw, q, k, v, ctx, [T] * B, trees, 1 / math.sqrt(d_h), row_off=off,
+                 tol=ATTN_TOL if dtype == torch.bfloat16 else 1e-5)
+
+
+def test_verify_grouped_query_attention_paged(tw):
+    B, H, H_kv, T, d_h, page_rows = 5, 28, 4, 32, 128, 16
+    ctx = [33, 500, 0, 129, 260]
+    trees = [W.random_parent_tree(W.HostRng(8, b), T, 5) for b in range(B)]
+    n_pages = [(c + T + page_rows - 1) // page_rows for c in ctx]
+    max_pages = max(n_pages)
+    perm = torch.randperm(sum(n_pages) + 3, generator=torch.Generator().manual_seed(4)).tolist()
+    table, at = [], 0
+    for n in n_pages:
+        table.append(perm[at:at + n] + [0] * (max_pages - n))
+        at += n
+    pool_rows = (sum(n_pages) + 3) * page_rows
+    q = W.normal(41, 1, (B, T, H, d_h), 1 / math.sqrt(d_h), torch.bfloat16)
+    k = W.normal(41, 2, (pool_rows, H_kv, d_h), 0.5, torch.bfloat16)
+    v = W.normal(41, 3, (pool_rows, H_kv, d_h), 0.5, torch.bfloat16)
+    check_verify(tw, q, k, v, ctx, [T] * B, trees, 1 / math.sqrt(d_h), page_table=table, page_rows=page_rows)
 
 
 def test_verify_split_cache_single_sequence(tw):
