@@ -112,6 +112,20 @@ int32_t tw_ttp_score(const void* q_sel, int32_t n_q_max, const int32_t* n_q, con
                      void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * The same score for a base model with grouped-query attention (Qwen2.5-VL
+ * among the base VLMs of Sec. 6): q_sel holds H_q = q_heads_per_kv * k->H heads,
+ * the view's rows k->H key heads, query head h reads key head h / q_heads_per_kv,
+ * and the mean is over the H_q query heads.  q_heads_per_kv = 1 is tw_ttp_score.
+ * The workspace is sized by tw_workspace_bytes with H = H_q.
+ * Errors as tw_ttp_score, plus INVALID_ARG (q_heads_per_kv < 1) and UNSUPPORTED
+ * (q_heads_per_kv > 64, H_q > 65535).
+ */
+int32_t tw_ttp_score_gqa(const void* q_sel, int32_t n_q_max, const int32_t* n_q, const int32_t* q_pos0,
+                         const tw_kv_view* k, int32_t q_heads_per_kv, const int32_t* n_tot, int32_t n_tot_max,
+                         int32_t B, int32_t v_start, int32_t M, float scale, int32_t causal, float* scores,
+                         void* ws, size_t ws_bytes, void* stream);
+
+/*
  * Pruning score in the P-Head form (Sec. 5.1 Eq. 7).  One query per sequence
  * (the last text token).  For head h and visual key m the logit is
  *   scale * sum_c (gq[b][h][c] * q[b][h][c]) * (gk[key][h][c] * K[key][h][c]),   key = v_start + m,

@@ -78,13 +78,25 @@ int32_t tw_ttp_score(const void* q_sel, int32_t n_q_max, const int32_t* n_q, con
                      const tw_kv_view* k, const int32_t* n_tot, int32_t n_tot_max, int32_t B,
                      int32_t v_start, int32_t M, float scale, int32_t causal, float* scores,
                      void* ws, size_t ws_bytes, void* stream) {
-    if (B < 0 || M < 0 || n_q_max < 1 || n_tot_max < 1 || v_start < 0) return TW_ERR_INVALID_ARG;
+    return tw_ttp_score_gqa(q_sel, n_q_max, n_q, q_pos0, k, 1, n_tot, n_tot_max, B, v_start, M, scale, causal,
+                            scores, ws, ws_bytes, stream);
+}
+
+int32_t tw_ttp_score_gqa(const void* q_sel, int32_t n_q_max, const int32_t* n_q, const int32_t* q_pos0,
+                         const tw_kv_view* k, int32_t q_heads_per_kv, const int32_t* n_tot, int32_t n_tot_max,
+                         int32_t B, int32_t v_start, int32_t M, float scale, int32_t causal, float* scores,
+                         void* ws, size_t ws_bytes, void* stream) {
+    if (B < 0 || M < 0 || n_q_max < 1 || n_tot_max < 1 || v_start < 0 || q_heads_per_kv < 1)
+        return TW_ERR_INVALID_ARG;
+    if (q_heads_per_kv > 64) return TW_ERR_UNSUPPORTED;
     if (B == 0 || M == 0) return TW_OK;
     if (!q_sel || !q_pos0 || !n_tot || !scores || (uintptr_t)q_sel % 16) return TW_ERR_INVALID_ARG;
     const int vs = view_status(k, false);
     if (vs != TW_OK) return vs;
     if ((int64_t)v_start + M > n_tot_max || n_q_max > n_tot_max) return TW_ERR_INVALID_ARG;
-    const size_t need = score_workspace_bytes(B, k->H, n_q_max, n_tot_max);
+    if ((int64_t)k->H * q_heads_per_kv > 65535) return TW_ERR_UNSUPPORTED;
+    const int H_q = k->H * q_heads_per_kv;
+    const size_t need = score_workspace_bytes(B, H_q, n_q_max, n_tot_max);
     if (!ws || ws_bytes < need) return TW_ERR_WORKSPACE;
     if ((uintptr_t)ws % 16) return TW_ERR_INVALID_ARG;
     ScoreArgs a;
@@ -98,7 +110,8 @@ int32_t tw_ttp_score(const void* q_sel, int32_t n_q_max, const int32_t* n_q, con
     a.n_q_max = n_q_max;
     a.n_tot_max = n_tot_max;
     a.B = B;
-    a.H = k->H;
+    a.H = H_q;
+    a.group = q_heads_per_kv;
     a.d_h = k->d_h;
     a.v_start = v_start;
     a.M = M;

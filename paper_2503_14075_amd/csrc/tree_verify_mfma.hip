@@ -410,12 +410,20 @@ struct SeqAddr {
     }
 };
 
+// A 16-byte piece of a K/V row.  STREAM: with the non-temporal hint, for multi-head attention where
+// every byte is used once (the bench launch: 108 against 130 us).  With grouped-query attention the
+// query heads of a group read the same rows at about the same time, and the hint would push the lines
+// out of L2 before the next head of the group arrives (Qwen2.5-VL heads, 128 sequences: 51 against 68 us).
+template <bool STREAM>
+__device__ __forceinline__ u32x4 load_kv(const u32x4* p) {
+    return STREAM ? __builtin_nontemporal_load(p) : *p;
+}
+
 // ---------------------------------------------------------------------------------------------
 // T <= 32: every wavefront stages its own chunks (K and V) in a private LDS area; no workgroup
 // barrier inside the loop.  K and V share one row mapping (same row_off / page_table).
-// The K/V loads carry the non-temporal hint (each byte is used once).
 // ---------------------------------------------------------------------------------------------
-template <int DH, bool PAGED>
+template <int DH, bool PAGED, bool STREAM>
 __global__ __launch_bounds__(kMfThreads, 2) void verify_mfma_kernel(VerifyArgs a) {
     using Cf = MfCfg<DH>;
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
@@ -464,8 +472,8 @@ __global__ __launch_bounds__(kMfThreads, 2) void verify_mfma_kernel(VerifyArgs a
 #pragma unroll
         for (int j = 0; j < Cf::kLoads; ++j) {
             const int r = ld_row + Cf::kRowsPerLoad * j;
-            pk[j] = __builtin_nontemporal_load(ad.at(a, ck, base, r, ld_col, PAGED ? pg[j] : 0));   // streamed once
-            pv[j] = __builtin_nontemporal_load(ad.at(a, cv, base, r, ld_col, PAGED ? pg[j] : 0));
+            pk[j] = load_kv<STREAM>(ad.at(a, ck, base, r, ld_col, PAGED ? pg[j] : 0));
+            pv[j] = load_kv<STREAM>(ad.at(a, cv, base, r, ld_col, PAGED ? pg[j] : 0));
         }
     };
 
@@ -507,7 +515,7 @@ __global__ __launch_bounds__(kMfThreads, 2) void verify_mfma_kernel(VerifyArgs a
 // chunks ahead; one workgroup barrier per chunk makes the stage visible.  Every wavefront runs
 // the same number of iterations so the barriers match.
 // ---------------------------------------------------------------------------------------------
-template <int DH, bool PAGED>
+template <int DH, bool PAGED, bool STREAM>
 __global__ __launch_bounds__(kMfThreads, 2) void verify_mfma_pair_kernel(VerifyArgs a) {
     using Cf = MfCfg<DH>;
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
@@ -557,7 +565,7 @@ __global__ __launch_bounds__(kMfThreads, 2) void verify_mfma_pair_kernel(VerifyA
 #pragma unroll
         for (int j = 0; j < Cf::kLoads; ++j) {
             const int r = ld_row + Cf::kRowsPerLoad * j;
-            pld[slot][j] = __builtin_nontemporal_load(ad.at(a, cc, base, r, ld_col, PAGED ? pg[slot][j] : 0));   // streamed once
+            pld[slot][j] = load_kv<STREAM>(ad.at(a, cc, base, r, ld_col, PAGED ? pg[slot][j] : 0));
         }
     };
     auto stage_chunk = [&](int slot, unsigned char* buf) {
@@ -602,12 +610,12 @@ __global__ __launch_bounds__(kMfThreads, 2) void verify_mfma_pair_kernel(VerifyA
     }
 }
 
-template <int DH, bool PAGED>
+template <int DH, bool PAGED, bool STREAM>
 static hipError_t launch_one(const VerifyArgs& a, hipStream_t s) {
     const dim3 grid((a.H + a.heads_per_wg - 1) / a.heads_per_wg, a.B, a.n_splits);
     const size_t lds = MfCfg<DH>::kLds;
-    const void* fn = a.n_blk == 1 ? (const void*)verify_mfma_kernel<DH, PAGED>
-                                  : (const void*)verify_mfma_pair_kernel<DH, PAGED>;
+    const void* fn = a.n_blk == 1 ? (const void*)verify_mfma_kernel<DH, PAGED, STREAM>
+                                  : (const void*)verify_mfma_pair_kernel<DH, PAGED, STREAM>;
     // the kernels' LDS need is a constant: raise the limit once per kernel, not on every launch
     static bool raised[2] = {false, false};
     if (!raised[a.n_blk - 1]) {
@@ -616,10 +624,15 @@ static hipError_t launch_one(const VerifyArgs& a, hipStream_t s) {
         raised[a.n_blk - 1] = true;
     }
     if (a.n_blk == 1)
-        hipLaunchKernelGGL((verify_mfma_kernel<DH, PAGED>), grid, dim3(kMfThreads), lds, s, a);
+        hipLaunchKernelGGL((verify_mfma_kernel<DH, PAGED, STREAM>), grid, dim3(kMfThreads), lds, s, a);
     else
-        hipLaunchKernelGGL((verify_mfma_pair_kernel<DH, PAGED>), grid, dim3(kMfThreads), lds, s, a);
+        hipLaunchKernelGGL((verify_mfma_pair_kernel<DH, PAGED, STREAM>), grid, dim3(kMfThreads), lds, s, a);
     return hipGetLastError();
+}
+
+template <int DH, bool PAGED>
+static hipError_t launch_kv_policy(const VerifyArgs& a, hipStream_t s) {
+    return a.group == 1 ? launch_one<DH, PAGED, true>(a, s) : launch_one<DH, PAGED, false>(a, s);
 }
 
 bool verify_mfma_supported(const VerifyArgs& a, int dtype) {
@@ -630,8 +643,8 @@ bool verify_mfma_supported(const VerifyArgs& a, int dtype) {
 }
 
 hipError_t launch_verify_mfma(const VerifyArgs& a, hipStream_t s) {
-    if (a.d_h == 128) return a.k.page_table ? launch_one<128, true>(a, s) : launch_one<128, false>(a, s);
-    return a.k.page_table ? launch_one<64, true>(a, s) : launch_one<64, false>(a, s);
+    if (a.d_h == 128) return a.k.page_table ? launch_kv_policy<128, true>(a, s) : launch_kv_policy<128, false>(a, s);
+    return a.k.page_table ? launch_kv_policy<64, true>(a, s) : launch_kv_policy<64, false>(a, s);
 }
 
 }  // namespace tw

@@ -91,8 +91,9 @@ __global__ __launch_bounds__(kScMfThreads, (NB <= 2 ? 2 : 1)) void score_mfma_ke
     const float sl2 = a.scale * kLog2e;
 
     const int ld_row = lane / Cf::kLanesPerRow, ld_col = lane % Cf::kLanesPerRow;
-    const unsigned char* kbase = (const unsigned char*)a.k.base + (int64_t)h * Cf::kRowB + ld_col * 16;
-    const int64_t pool_stride = (int64_t)a.H * Cf::kRowB;
+    // a cache row holds the key heads; query head h reads key head h / group
+    const unsigned char* kbase = (const unsigned char*)a.k.base + (int64_t)(h / a.group) * Cf::kRowB + ld_col * 16;
+    const int64_t pool_stride = (int64_t)a.k.H * Cf::kRowB;
     const int64_t last_pool_row = a.k.pool_rows - 1;
     const int64_t row0 = (int64_t)a.k.row_off[b];
     u32x4 pk[Cf::kLoads];
@@ -325,7 +326,7 @@ __global__ __launch_bounds__(kScThreads) void score_generic_kernel(ScoreArgs a) 
             const int r = idx / c8n, c8 = idx % c8n;
             float v[8] = {0, 0, 0, 0, 0, 0, 0, 0};
             if (base + r < n_tot)
-                load8<TIn>(kbase + (pool_row(a.k, b, base + r) * a.H + h) * d_h + c8 * 8, v);
+                load8<TIn>(kbase + (pool_row(a.k, b, base + r) * a.k.H + h / a.group) * d_h + c8 * 8, v);
 #pragma unroll
             for (int e = 0; e < 8; ++e) sK[r * ld + c8 * 8 + e] = v[e];
         }

@@ -78,7 +78,7 @@ __global__ __launch_bounds__(kRsThreads, 2) void score_resident_kernel(ScoreArgs
     // [chunk of the span][key pair][kEsStride]: two 16-bit exponentials per scoring row
     uint32_t* s_es = (uint32_t*)(lds + Cf::kOffEs);
 
-    const uint32_t pool_stride = (uint32_t)(a.H * Cf::kRowB);
+    const uint32_t pool_stride = (uint32_t)(a.k.H * Cf::kRowB);   // a cache row holds the key heads
     const int64_t last_pool_row = a.k.pool_rows - 1;
     const float sl2 = a.scale * kLog2e;
     const int span_end = a.v_start + a.M;
@@ -117,7 +117,7 @@ __global__ __launch_bounds__(kRsThreads, 2) void score_resident_kernel(ScoreArgs
         // scalar part of the address: the sequence's first row (kept inside the pool) and the head
         const int64_t row0 = p.row0 < 0 ? 0 : (p.row0 > last_pool_row ? last_pool_row : p.row0);
         const unsigned char* sbase =
-            (const unsigned char*)a.k.base + (uint64_t)row0 * pool_stride + (int64_t)p.h * Cf::kRowB;
+            (const unsigned char*)a.k.base + (uint64_t)row0 * pool_stride + (int64_t)(p.h / a.group) * Cf::kRowB;
         // lane part, 32 bits: its key row, held below the sequence's end and the pool's end
         const int64_t room = last_pool_row - row0;
         int last = live ? p.n_tot - 1 : 0;   // past the end: the last key again (cached), masked later

@@ -77,8 +77,9 @@ __global__ __launch_bounds__(kStThreads, 2) void score_stream_kernel(ScoreArgs a
     const float sl2 = a.scale * kLog2e;
 
     const int ld_row = lane / Cf::kLanesPerRow, ld_col = lane % Cf::kLanesPerRow;
-    const unsigned char* kbase = (const unsigned char*)a.k.base + (int64_t)h * Cf::kRowB + ld_col * 16;
-    const int64_t pool_stride = (int64_t)a.H * Cf::kRowB;
+    // a cache row holds the key heads; query head h reads key head h / group
+    const unsigned char* kbase = (const unsigned char*)a.k.base + (int64_t)(h / a.group) * Cf::kRowB + ld_col * 16;
+    const int64_t pool_stride = (int64_t)a.k.H * Cf::kRowB;
     const int64_t last_pool_row = a.k.pool_rows - 1;
     const int64_t row0 = (int64_t)a.k.row_off[b];
     // this split's share of the keys, in whole chunks

@@ -154,7 +154,8 @@ struct ScoreArgs {
     // kernel: a launch covers rows row0 .. row0 + n_q_max - 1 of the q_stride rows that q_sel holds
     // per sequence (q_stride == 0: n_q_max), and n_halves partial planes are added at the end.
     int32_t row0 = 0, q_stride = 0, n_halves = 1;
-    int32_t n_q_max, n_tot_max, B, H, d_h, v_start, M, causal;
+    int32_t n_q_max, n_tot_max, B, H, d_h, v_start, M, causal;   // H: query heads = group * k.H
+    int32_t group = 1;   // query heads per key head (1: multi-head attention)
     float scale;
 };
 int score_key_splits(int B, int H, int n_tot_max);

@@ -151,6 +151,16 @@ def test_verify_grouped_query_attention(tw, B, H, H_kv, T, dtype, d_h):
                  tol=ATTN_TOL if dtype == torch.bfloat16 else 1e-5)
 
 
+@pytest.mark.parametrize("T", [26, 40])
+def test_verify_grouped_query_attention_split_cache(tw, T):
+    # one long sequence: the cache rows are split over workgroups and merged (ten splits here)
+    H, H_kv, d_h, ctx = 28, 4, 128, [3000]
+    trees = [W.random_parent_tree(W.HostRng(T, 0), T, 6)]
+    q, k, v, off = make_case(77, 1, H, d_h, ctx, T, torch.bfloat16, trees, H_kv=H_kv)
+    assert tw.workspace_bytes(tw.TW_CALL_TREE_VERIFY_ATTN, 1, T, H, d_h, ctx[0] + T) > 0
+    check_verify(tw, q, k, v, ctx, [T], trees, 1 / math.sqrt(d_h), row_off=off)
+
+
 def test_verify_grouped_query_attention_paged(tw):
     B, H, H_kv, T, d_h, page_rows = 5, 28, 4, 32, 128, 16
     ctx = [33, 500, 0, 129, 260]
@@ -788,7 +798,7 @@ def test_pools_larger_than_4_gib(tw):
 # ----------------------------------------------------------------------------
 # ttp_score
 # ----------------------------------------------------------------------------
-def _check_score(tw, dtype, H, d_h, M, v0, n_text, n_q, causal, q_std=1.0, seed=1, scale=None):
+def _check_score(tw, dtype, H, d_h, M, v0, n_text, n_q, causal, q_std=1.0, seed=1, scale=None, H_kv=None):
     B = len(n_text)
     n_tot = [v0 + M + n for n in n_text]
     off, acc = [], 2
@@ -797,7 +807,7 @@ def _check_score(tw, dtype, H, d_h, M, v0, n_text, n_q, causal, q_std=1.0, seed=
         acc += n + 1
     n_q_max = max(n_q)
     q = W.normal(seed, 1, (B, n_q_max, H, d_h), q_std, dtype)
-    k = W.normal(seed, 2, (acc, H, d_h), 1.0, dtype)
+    k = W.normal(seed, 2, (acc, H_kv or H, d_h), 1.0, dtype)   # fewer key heads: grouped-query attention
     pos0 = [nt - nq for nt, nq in zip(n_tot, n_q)]
     scale = 1 / math.sqrt(d_h) if scale is None else scale
     want = oracle.ttp_score(q, k, n_q, pos0, n_tot, off, v0, M, scale, causal)
@@ -806,8 +816,14 @@ def _check_score(tw, dtype, H, d_h, M, v0, n_text, n_q, causal, q_std=1.0, seed=
     nbytes = tw.workspace_bytes(tw.TW_CALL_TTP_SCORE, B, n_q_max, H, d_h, max(n_tot))
     ws = torch.empty(nbytes // 4, dtype=torch.float32, device=DEV)
     scores = torch.full((B, M), float("nan"), dtype=torch.float32, device=DEV)
-    tw.ttp_score(q.to(DEV), view, _i32(n_q), _i32(pos0), _i32(n_tot), max(n_tot), v0, M, scale, causal,
-                 scores, ws)
+    def run(dst):
+        if H_kv is None:
+            tw.ttp_score(q.to(DEV), view, _i32(n_q), _i32(pos0), _i32(n_tot), max(n_tot), v0, M, scale, causal,
+                         dst, ws)
+        else:
+            tw.ttp_score_gqa(q.to(DEV), view, H // H_kv, _i32(n_q), _i32(pos0), _i32(n_tot), max(n_tot), v0, M,
+                             scale, causal, dst, ws)
+    run(scores)
     torch.cuda.synchronize()
     got = scores.cpu().double()
     assert torch.isfinite(got).all()
@@ -823,8 +839,7 @@ def _check_score(tw, dtype, H, d_h, M, v0, n_text, n_q, causal, q_std=1.0, seed=
         tol = score_tol(H, n_q[b]) if one_pass else SCORE_TOL
         assert err <= tol, f"score error {err:.3e} in sequence {b} (bar {tol:.1e})"
     again = torch.empty_like(scores)
-    tw.ttp_score(q.to(DEV), view, _i32(n_q), _i32(pos0), _i32(n_tot), max(n_tot), v0, M, scale, causal,
-                 again, ws)
+    run(again)
     torch.cuda.synchronize()
     assert torch.equal(again, scores)          # fixed summation order
 
@@ -921,6 +936,19 @@ def test_score_phead_form(tw, dtype, H, d_h, M, v0, B):
     err = float(((got - want).abs() / (1e-6 + 2e-5 * want)).max())
     assert err <= 1.0, f"P-Head score error ratio {err:.3f}"
     assert float((got.sum(1) - 1).abs().max()) < 1e-5
+
+
+def test_score_grouped_query_attention(tw):
+    # q_sel has H heads, the key rows H_kv: query head h reads key head h // (H // H_kv); every kernel
+    # of the score is visited (Qwen2.5-VL-7B has 28 query heads over 4 key heads of 128)
+    bf = torch.bfloat16
+    _check_score(tw, bf, 28, 128, 576, 0, [64, 20], [64, 20], True, H_kv=4)             # one-pass, LDS table
+    _check_score(tw, bf, 28, 128, 576, 3, [30], [8], True, H_kv=4)                      # ... 32-row variant
+    _check_score(tw, bf, 28, 128, 500, 0, [110, 70], [110, 70], True, H_kv=4)           # 65-128 rows: two launches
+    _check_score(tw, bf, 28, 128, 2880, 0, [128, 40], [16, 16], True, H_kv=4)           # long prompt, streamed table
+    _check_score(tw, bf, 8, 64, 1500, 5, [100], [64], True, H_kv=2)                     # two-pass kernel
+    _check_score(tw, torch.float32, 6, 64, 90, 3, [20, 9], [8, 9], True, H_kv=3)        # fp32 vector kernel
+    _check_score(tw, bf, 6, 40, 70, 0, [17], [17], False, H_kv=1)                       # one key head, odd head size
 
 
 def test_score_generic_path(tw):
