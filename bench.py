@@ -329,6 +329,41 @@ def main():
         next_rows["tree_build_us_median"] = med_us(lambda: twb.tree_build(cp, ct, pb, nc, root, 61, outs[0], outs[1],
                                                                           outs[2], nn, tws))
 
+        # grouped-query attention at the head layout of Qwen2.5-VL-7B (28 query heads over 4 key/value
+        # heads of 128), cfg1's lengths, the same 128 sequences: the verification attention and the score
+        Hq, Hkv, dh = 28, 4, 128
+        n_txt, C_g = cfg.N[1], cfg.R + cfg.N[1] + cfg.P[1]     # cfg1: 64 text rows, 256 cache rows
+        rows_g, n_tot_g = C_g + cfg.T, cfg.M + n_txt
+        gen = torch.Generator(device=dev).manual_seed(7)
+        qg = (torch.randn(Bn, cfg.T, Hq, dh, device=dev, generator=gen) / dh ** 0.5).to(torch.bfloat16)
+        kg = (torch.randn(Bn * rows_g, Hkv, dh, device=dev, generator=gen) * 0.5).to(torch.bfloat16)
+        vg = (torch.randn(Bn * rows_g, Hkv, dh, device=dev, generator=gen) * 0.5).to(torch.bfloat16)
+        ro_g = torch.arange(Bn, device=dev, dtype=torch.int32) * rows_g
+        kvg, vvg = twb.kv_view(kg, ro_g, None, 16), twb.kv_view(vg, ro_g, None, 16)
+        ctx_g = torch.full((Bn,), C_g, dtype=torch.int32, device=dev)
+        out_g = torch.empty(Bn, cfg.T, Hq, dh, dtype=torch.float32, device=dev)
+        nb_g = twb.workspace_bytes(twb.TW_CALL_TREE_VERIFY_ATTN, Bn, cfg.T, Hq, dh, rows_g)
+        ws_g = torch.empty(max(nb_g, 4) // 4, dtype=torch.float32, device=dev) if nb_g else None
+        t_vg = med_us(lambda: twb.tree_verify_attn_gqa(qg, kvg, vvg, Hq // Hkv, ctx_g, C_g, dw.parent, dw.n_nodes,
+                                                       cfg.scale, out_g, ws_g))
+        b_vg = 2 * Bn * rows_g * Hkv * dh * 2 + Bn * cfg.T * Hq * dh * (2 + 4)
+        qs_g = torch.randn(Bn, n_txt, Hq, dh, device=dev, generator=gen).to(torch.bfloat16)
+        ks_g = torch.randn(Bn * n_tot_g, Hkv, dh, device=dev, generator=gen).to(torch.bfloat16)
+        ro_s = torch.arange(Bn, device=dev, dtype=torch.int32) * n_tot_g
+        ksv = twb.kv_view(ks_g, row_off=ro_s)
+        i32 = lambda v: torch.full((Bn,), v, dtype=torch.int32, device=dev)
+        nq_g, pos_g, nt_g = i32(n_txt), i32(n_tot_g - n_txt), i32(n_tot_g)
+        ws_s = torch.empty(twb.workspace_bytes(twb.TW_CALL_TTP_SCORE, Bn, n_txt, Hq, dh, n_tot_g) // 4,
+                           dtype=torch.float32, device=dev)
+        sc_g = torch.empty(Bn, cfg.M, dtype=torch.float32, device=dev)
+        t_sg = med_us(lambda: twb.ttp_score_gqa(qs_g, ksv, Hq // Hkv, nq_g, pos_g, nt_g, n_tot_g, 0, cfg.M,
+                                                cfg.scale, True, sc_g, ws_s))
+        b_sg = Bn * n_tot_g * Hkv * dh * 2 + Bn * n_txt * Hq * dh * 2 + Bn * cfg.M * 4
+        next_rows["grouped_query_28q_4kv_heads"] = {
+            "tree_verify_attn_gqa": {"us_median": t_vg, "algorithmic_MB": b_vg / 1e6, "GBps": b_vg / t_vg / 1e3},
+            "ttp_score_gqa": {"us_median": t_sg, "algorithmic_MB": b_sg / 1e6, "GBps": b_sg / t_sg / 1e3}}
+        del qg, kg, vg, out_g, qs_g, ks_g
+
     # what plain library kernels reach on this machine in this run (context for the roofline fraction):
     # a 1 GiB device-to-device copy (read + write) and a 1 GiB reduction (read only)
     ctx_a = torch.empty(1 << 29, dtype=torch.bfloat16, device=dev).normal_()
