@@ -75,7 +75,8 @@ int32_t tw_version(void);
  * Scratch bytes needed by a call.  `which` is a tw_call.  For
  * TW_CALL_TTP_SCORE: rows = n_q_max, max_rows = n_tot_max.  For
  * TW_CALL_TREE_VERIFY_ATTN: rows = T_max, max_rows = max_ctx_len + T_max.
- * Returns 0 for calls that need none or for invalid arguments.  The buffer
+ * H = heads of the query tensor (the view's H, times q_heads_per_kv for the
+ * grouped-query entry points).  Returns 0 for calls that need none or for invalid arguments.  The buffer
  * handed to the call is device memory, 16-byte aligned; its contents on entry
  * do not matter and are undefined on return.
  */

@@ -64,7 +64,7 @@ size_t verify_workspace_bytes(int B, int H, int T_max, int d_h, int max_rows) {
 
 extern "C" {
 
-int32_t tw_version(void) { return 1000; }
+int32_t tw_version(void) { return 1001; }
 
 size_t tw_workspace_bytes(int32_t which, int32_t B, int32_t rows, int32_t H, int32_t d_h,
                           int32_t max_rows) {

@@ -110,6 +110,19 @@ def test_argument_validation_without_launch():
     assert lib.tw_draft_topk_logits(P, 2, (1 << 20) + 1, 10, P, P, None) == tw.TW_ERR_UNSUPPORTED
     assert lib.tw_draft_topk_logits(None, 2, 100, 10, P, P, None) == tw.TW_ERR_INVALID_ARG
     assert lib.tw_draft_topk_logits(P, 0, 100, 10, P, P, None) == tw.TW_OK
+    # grouped-query entry points: the group size is checked before anything is dereferenced
+    v = _view()
+    gq = lib.tw_tree_verify_attn_gqa
+    assert gq(P, ctypes.byref(v), ctypes.byref(v), 0, P, 10, P, P, 8, 2, 0.1, P, tw.TW_F32, None, 0, None) \
+        == tw.TW_ERR_INVALID_ARG
+    assert gq(P, ctypes.byref(v), ctypes.byref(v), 65, P, 10, P, P, 8, 2, 0.1, P, tw.TW_F32, None, 0, None) \
+        == tw.TW_ERR_UNSUPPORTED
+    assert gq(P, ctypes.byref(v), ctypes.byref(v), 7, P, 10, P, P, 8, 0, 0.1, P, tw.TW_F32, None, 0, None) == tw.TW_OK
+    sg = lib.tw_ttp_score_gqa
+    assert sg(P, 8, P, P, ctypes.byref(v), 0, P, 700, 2, 0, 576, 0.1, 1, P, P, 1 << 30, None) == tw.TW_ERR_INVALID_ARG
+    assert sg(P, 8, P, P, ctypes.byref(v), 65, P, 700, 2, 0, 576, 0.1, 1, P, P, 1 << 30, None) == tw.TW_ERR_UNSUPPORTED
+    assert sg(P, 8, P, P, ctypes.byref(v), 7, P, 700, 2, 0, 576, 0.1, 1, P, P, 16, None) == tw.TW_ERR_WORKSPACE
+    assert sg(P, 8, P, P, ctypes.byref(v), 7, P, 700, 0, 0, 576, 0.1, 1, P, P, 0, None) == tw.TW_OK
     tb = lambda **kw: lib.tw_tree_build(kw.get("cp", P), P, P, P, P, kw.get("N", 310), kw.get("B", 1),
                                         kw.get("T", 61), P, P, P, P, kw.get("ws", None), kw.get("ws_bytes", 0), None)
     assert tb(T=65) == tw.TW_ERR_UNSUPPORTED
