@@ -616,13 +616,10 @@ static hipError_t launch_one(const VerifyArgs& a, hipStream_t s) {
     const size_t lds = MfCfg<DH>::kLds;
     const void* fn = a.n_blk == 1 ? (const void*)verify_mfma_kernel<DH, PAGED, STREAM>
                                   : (const void*)verify_mfma_pair_kernel<DH, PAGED, STREAM>;
-    // the kernels' LDS need is a constant: raise the limit once per kernel, not on every launch
-    static bool raised[2] = {false, false};
-    if (!raised[a.n_blk - 1]) {
-        const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        raised[a.n_blk - 1] = true;
-    }
+    // the kernels' LDS need is a constant: raise the limit once per kernel and device, not on every launch
+    static uint32_t raised[2] = {0u, 0u};
+    const hipError_t e = raise_lds_limit_once(fn, (int)lds, raised[a.n_blk - 1]);
+    if (e != hipSuccess) return e;
     if (a.n_blk == 1)
         hipLaunchKernelGGL((verify_mfma_kernel<DH, PAGED, STREAM>), grid, dim3(kMfThreads), lds, s, a);
     else

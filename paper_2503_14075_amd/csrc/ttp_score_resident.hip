@@ -389,14 +389,10 @@ static hipError_t launch_rs(const ScoreArgs& a, hipStream_t s) {
     using Cf = RsCfg<DH, NB>;
     const int span_chunks = (a.v_start + a.M - 1) / kRsChunk - a.v_start / kRsChunk + 1;
     const size_t lds = Cf::kOffEs + (size_t)span_chunks * Cf::kEsChunk;
-    // the table grows with the visual span: raise the limit to a compute unit's LDS once per kernel
-    static bool raised = false;
-    if (!raised) {
-        const hipError_t e = hipFuncSetAttribute((const void*)score_resident_kernel<DH, NB>,
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, kRsLdsBytes);
-        if (e != hipSuccess) return e;
-        raised = true;
-    }
+    // the table grows with the visual span: raise the limit to a compute unit's LDS once per kernel and device
+    static uint32_t raised = 0u;
+    const hipError_t e = raise_lds_limit_once((const void*)score_resident_kernel<DH, NB>, kRsLdsBytes, raised);
+    if (e != hipSuccess) return e;
     hipLaunchKernelGGL((score_resident_kernel<DH, NB>), dim3(resident_grid(n_pairs)), dim3(kRsThreads), lds, s, a,
                        n_pairs);
     return hipGetLastError();

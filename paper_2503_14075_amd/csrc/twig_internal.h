@@ -94,6 +94,18 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t raw_buffer(const void* base, u
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);
 }
 
+// Raises a kernel's dynamic LDS limit to `bytes`, once per device (bit d of `done` = device d has
+// it; the limit of a kernel is a per-device attribute).  Devices past 31 set it on every call.
+inline hipError_t raise_lds_limit_once(const void* kernel, int bytes, uint32_t& done) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev >= 0 && dev < 32 && ((done >> dev) & 1u)) return hipSuccess;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e == hipSuccess && dev >= 0 && dev < 32) done |= 1u << dev;
+    return e;
+}
+
 // Ancestor-or-self mask of node i from a parent array held in shared memory.
 // Parents are clamped to [0, i) so the walk always ends at the root.
 __device__ __forceinline__ uint64_t ancestor_mask(const int* s_parent, int i) {
