@@ -20,6 +20,11 @@
  *     clamped) but the result is unspecified.
  *   - Same inputs give bit-identical outputs from run to run (no
  *     order-dependent floating-point atomics anywhere).
+ *   - A call may be recorded into a HIP graph (stream capture): it consists of
+ *     kernel launches only, no memset or copy nodes.  The first launch of some
+ *     kernels on a device also raises that kernel's shared-memory limit (a
+ *     function attribute, not a stream operation); callers that want nothing
+ *     but launches inside a capture make one eager call of the same shape first.
  *
  * Tensor layout: token-major rows.  A row of a key, value or query tensor is H
  * heads of d_h contiguous elements (bf16 or fp32).  d_h must be a multiple of
