@@ -237,6 +237,15 @@ def draft_topk_logits(logits: torch.Tensor, E: int):
     return ids, probs
 
 
+def tree_confidence(cand_parent: Sequence[int], cand_prob: Sequence[float]) -> torch.Tensor:
+    """fp64 confidence (product of draft probabilities along the path) of every candidate."""
+    cp = _i32(cand_parent)
+    pb = torch.as_tensor(cand_prob, dtype=torch.float32).contiguous()
+    conf = torch.empty(cp.numel(), dtype=torch.float64)
+    _check(lib().orc_tree_confidence(_p(cp), _p(pb), int(cp.numel()), _p(conf)), "tree_confidence")
+    return conf
+
+
 def tree_build(cand_parent: Sequence[int], cand_token: Sequence[int], cand_prob: Sequence[float],
                root_token: int, T_max: int):
     """(n_nodes, parent [T_max], token [T_max], src [T_max]) for one sequence."""

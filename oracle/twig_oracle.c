@@ -441,12 +441,38 @@ int orc_draft_topk_logits(const float* logits, int n, int V, int E, int32_t* ids
 }
 
 /*
+ * Confidence of drafted candidates (App. A): the product of the draft
+ * probabilities along the path from the root to the candidate, in fp64.  A
+ * candidate's parent precedes it (cand_parent[i] < i, -1 for a child of the
+ * root), so one pass in generation order gives conf[i] = conf[parent] * prob[i].
+ * Returns 0, -1 on invalid arguments.
+ */
+int orc_tree_confidence(const int32_t* cand_parent, const float* cand_prob, int n_cand, double* conf) {
+    if (n_cand < 0 || (n_cand > 0 && (!cand_parent || !cand_prob || !conf))) return -1;
+    for (int i = 0; i < n_cand; ++i) {
+        if (cand_parent[i] < -1 || cand_parent[i] >= i) return -1;
+        conf[i] = (cand_parent[i] < 0 ? 1.0 : conf[cand_parent[i]]) * (double)cand_prob[i];
+    }
+    return 0;
+}
+
+typedef struct { double s; int32_t m; } orc_pair_d;
+
+static int pair_d_cmp(const void* a, const void* b) {
+    const orc_pair_d* x = (const orc_pair_d*)a;
+    const orc_pair_d* y = (const orc_pair_d*)b;
+    if (x->s > y->s) return -1;
+    if (x->s < y->s) return 1;
+    return (x->m > y->m) - (x->m < y->m);
+}
+
+/*
  * Pruning of a drafted tree to its most confident candidates (App. A).  The
- * confidence of candidate i is the product of cand_prob along its path from the
- * root (computed in fp32 from the node upwards, the order the GPU uses, so that
- * ties and the order of near-equal confidences are decided identically); the
- * T_max - 1 most confident candidates are kept, ties toward the lower index;
- * node 0 is the root, kept candidates follow in ascending candidate index.
+ * confidence of candidate i is orc_tree_confidence (fp64 product along the
+ * path); the T_max - 1 most confident candidates are kept, ties toward the
+ * lower index (a product with a factor <= 1 never exceeds its parent's, so the
+ * kept set holds every ancestor of a kept candidate); node 0 is the root, kept
+ * candidates follow in ascending candidate index.
  * One sequence per call.  Returns the number of nodes (root included), -1 on
  * invalid arguments.
  */
@@ -456,17 +482,18 @@ int orc_tree_build(const int32_t* cand_parent, const int32_t* cand_token, const 
     for (int i = 0; i < n_cand; ++i)
         if (cand_parent[i] < -1 || cand_parent[i] >= i) return -1;
     int n_keep = n_cand < T_max - 1 ? n_cand : T_max - 1;
-    orc_pair* pr = (orc_pair*)malloc(sizeof(orc_pair) * (size_t)(n_cand > 0 ? n_cand : 1));
+    orc_pair_d* pr = (orc_pair_d*)malloc(sizeof(orc_pair_d) * (size_t)(n_cand > 0 ? n_cand : 1));
     int32_t* node_of = (int32_t*)malloc(sizeof(int32_t) * (size_t)(n_cand > 0 ? n_cand : 1));
-    if (!pr || !node_of) return -3;
+    double* conf = (double*)malloc(sizeof(double) * (size_t)(n_cand > 0 ? n_cand : 1));
+    if (!pr || !node_of || !conf) return -3;
+    orc_tree_confidence(cand_parent, cand_prob, n_cand, conf);
     for (int i = 0; i < n_cand; ++i) {
-        float c = 1.0f;
-        for (int u = i; u >= 0; u = cand_parent[u]) c *= cand_prob[u];
-        pr[i].s = c;
+        pr[i].s = conf[i];
         pr[i].m = i;
         node_of[i] = 0;
     }
-    qsort(pr, (size_t)n_cand, sizeof(orc_pair), pair_cmp);
+    free(conf);
+    qsort(pr, (size_t)n_cand, sizeof(orc_pair_d), pair_d_cmp);
     int32_t keep[64];
     for (int r = 0; r < n_keep; ++r) keep[r] = pr[r].m;
     qsort(keep, (size_t)n_keep, sizeof(int32_t), int_cmp);

@@ -676,14 +676,21 @@ def test_tree_build_keeps_most_confident_ancestor_closed_set(seed):
     N, T_max = len(par), 17
     n, p_out, t_out, s_out = oracle.tree_build(par, tok, prob, 123, T_max)
     assert n == min(T_max, N + 1) and int(p_out[0]) == -1 and int(t_out[0]) == 123 and int(s_out[0]) == -1
-    # brute force: fp32 confidences, stable order (confidence desc, index asc), first T_max-1
+    # brute force: the product of the probabilities along each path in exact rational arithmetic
+    # (the fp32 inputs are dyadic rationals), walked from the node upwards; stable order
+    # (confidence desc, index asc), first T_max-1
+    from fractions import Fraction
+    p32 = [Fraction(float(np.float32(x))) for x in prob]
     conf = []
     for i in range(N):
-        c, u = np.float32(1.0), i
+        c, u = Fraction(1), i
         while u >= 0:
-            c = np.float32(c * np.float32(prob[u]))
+            c *= p32[u]
             u = par[u]
         conf.append(c)
+    # the oracle's fp64 confidences are the exact products to a few units in the last place
+    got = oracle.tree_confidence(par, prob)
+    assert all(abs(Fraction(float(g)) - c) <= c * Fraction(1, 2 ** 50) for g, c in zip(got.tolist(), conf))
     order = sorted(range(N), key=lambda i: (-conf[i], i))[:T_max - 1]
     keep = sorted(order)
     assert s_out[1:n].tolist() == keep
