@@ -343,7 +343,7 @@ def main():
         ctx_g = torch.full((Bn,), C_g, dtype=torch.int32, device=dev)
         out_g = torch.empty(Bn, cfg.T, Hq, dh, dtype=torch.float32, device=dev)
         nb_g = twb.workspace_bytes(twb.TW_CALL_TREE_VERIFY_ATTN, Bn, cfg.T, Hq, dh, rows_g)
-        ws_g = torch.empty(max(nb_g, 4) // 4, dtype=torch.float32, device=dev) if nb_g else None
+        ws_g = torch.zeros(max(nb_g, 4) // 4, dtype=torch.float32, device=dev) if nb_g else None
         t_vg = med_us(lambda: twb.tree_verify_attn_gqa(qg, kvg, vvg, Hq // Hkv, ctx_g, C_g, dw.parent, dw.n_nodes,
                                                        cfg.scale, out_g, ws_g))
         b_vg = 2 * Bn * rows_g * Hkv * dh * 2 + Bn * cfg.T * Hq * dh * (2 + 4)

@@ -7,9 +7,10 @@
  * Conventions for every call
  *   - Pointers marked [dev] are device memory owned by the caller; pointers
  *     marked [host] are read on the host during the call and not retained.
- *   - The library allocates no device memory and keeps no state between calls.
- *     Scratch space comes in through (ws, ws_bytes); tw_workspace_bytes() tells
- *     how much a call needs.
+ *   - The library allocates no device memory and keeps no results between calls
+ *     (it remembers only, per device, which kernels already had their
+ *     shared-memory limit raised).  Scratch space comes in through (ws,
+ *     ws_bytes); tw_workspace_bytes() tells how much a call needs.
  *   - A call only enqueues work on `stream` (a hipStream_t passed as void*;
  *     NULL = the default stream) and returns.  Nothing synchronises, nothing is
  *     read back.  Outputs are valid once the caller has synchronised the stream.
@@ -73,7 +74,7 @@ typedef struct tw_kv_view {
     int32_t max_pages, page_rows;
 } tw_kv_view;
 
-/* Library version, 1000*major + minor. */
+/* Library version, 1000*major + minor (2.0: the verification workspace carries counters that start at zero). */
 int32_t tw_version(void);
 
 /*
@@ -82,8 +83,14 @@ int32_t tw_version(void);
  * TW_CALL_TREE_VERIFY_ATTN: rows = T_max, max_rows = max_ctx_len + T_max.
  * H = heads of the query tensor (the view's H, times q_heads_per_kv for the
  * grouped-query entry points).  Returns 0 for calls that need none or for invalid arguments.  The buffer
- * handed to the call is device memory, 16-byte aligned; its contents on entry
- * do not matter and are undefined on return.
+ * handed to the call is device memory, 16-byte aligned, and not shared with a call that may run
+ * at the same time.
+ * TW_CALL_TTP_SCORE: its contents on entry do not matter and are undefined on return.
+ * TW_CALL_TREE_VERIFY_ATTN: the buffer starts with one arrival counter per (sequence, head), which
+ * a launch that cuts sequences into pieces needs at zero and puts back to zero as its last action.
+ * Zero the buffer once, after allocating it (hipMemset); from then on it serves any number of
+ * calls of any shape.  With counters that are not zero the output is unspecified (still memory-
+ * safe, and no kernel waits for another).  After TW_ERR_LAUNCH zero it again.
  */
 size_t tw_workspace_bytes(int32_t which, int32_t B, int32_t rows, int32_t H, int32_t d_h,
                           int32_t max_rows);

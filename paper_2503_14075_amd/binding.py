@@ -15,7 +15,8 @@ from typing import List, Optional, Sequence
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libtwigpath.so")
+# TWIGPATH_LIB names another build of the same library (the diagnostic build of build.py --trace)
+LIB_PATH = os.environ.get("TWIGPATH_LIB") or os.path.join(_HERE, "libtwigpath.so")
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2503_14075_amd.build`")

@@ -1,6 +1,7 @@
 """Build libtwigpath.so (HIP, gfx950 only) next to this file.
 
     python -m paper_2503_14075_amd.build [--force]
+    python -m paper_2503_14075_amd.build --trace    # diagnostic build libtwigpath_trace.so (-DTW_TRACE)
 """
 from __future__ import annotations
 
@@ -34,13 +35,17 @@ def is_stale() -> bool:
     return any(os.path.getmtime(d) > t for d in deps)
 
 
-def build(force: bool = True, extra=()) -> str:
-    if force or is_stale():
-        cmd = ["hipcc"] + [f for f in FLAGS if f] + list(extra) + ["-o", LIB] + sources()
+def build(force: bool = True, extra=(), out: str = LIB) -> str:
+    if force or out != LIB or is_stale():
+        cmd = ["hipcc"] + [f for f in FLAGS if f] + list(extra) + ["-o", out] + sources()
         subprocess.check_call(cmd)
-    return LIB
+    return out
 
 
 if __name__ == "__main__":
-    build(force=True, extra=[a for a in sys.argv[1:] if a != "--force"])
-    print(LIB)
+    args = [a for a in sys.argv[1:] if a != "--force"]
+    if "--trace" in args:
+        args.remove("--trace")
+        print(build(extra=["-DTW_TRACE"] + args, out=os.path.join(HERE, "libtwigpath_trace.so")))
+    else:
+        print(build(force=True, extra=args))

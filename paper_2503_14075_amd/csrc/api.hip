@@ -29,15 +29,16 @@ namespace tw {
 // least 768 (sequence, head, node block) units every wavefront takes its own unit (four heads,
 // or two heads x two blocks, per workgroup) and the cache is never split; with fewer, a workgroup
 // takes one head and its wavefronts share the head's rows round-robin.  Then the cache rows are
-// additionally split over several workgroups while the launch has fewer than 256 of them (one
-// per compute unit), never below 256 rows per split: a split costs a second prologue, a partial
-// output round trip and the merge launch, 15 to 20 us in all.  Thresholds from timing sweeps
-// over B = 1..96, 282..4160 rows, T = 26 and 64.
+// additionally cut into pieces of split_rows rows, one workgroup each, while the launch has fewer
+// than 256 workgroups (one per compute unit), never below 256 rows per piece.  The pieces have one
+// length for the whole launch (the host knows the longest sequence only): a shorter sequence
+// simply has fewer of them, and one that fits a single piece is finished by its workgroup alone.
 VerifyPlan verify_plan(int B, int H, int T_max, int max_rows) {
     VerifyPlan p;
     p.n_blk = T_max > 32 ? 2 : 1;
     const long units = (long)B * H * p.n_blk;
     p.n_splits = 1;
+    p.split_rows = (max_rows + 31) / 32 * 32;
     if (units >= 768) {
         p.heads_per_wg = 4 / p.n_blk;
         p.n_phase = 1;
@@ -50,21 +51,34 @@ VerifyPlan verify_plan(int B, int H, int T_max, int max_rows) {
     long cap = max_rows / 256;
     if (cap < 1) cap = 1;
     if (cap > 64) cap = 64;
-    p.n_splits = (int)(want < cap ? want : cap);
+    const int n = (int)(want < cap ? want : cap);
+    if (n > 1) {
+        // whole 32-row chunks per piece, then as few pieces as cover the longest sequence
+        const int per = (max_rows + n - 1) / n;
+        p.split_rows = (per + 31) / 32 * 32;
+        p.n_splits = (max_rows + p.split_rows - 1) / p.split_rows;
+    }
     return p;
 }
+
+size_t verify_counter_bytes(int B, int H) { return ((size_t)B * H * sizeof(int32_t) + 255) / 256 * 256; }
 
 size_t verify_workspace_bytes(int B, int H, int T_max, int d_h, int max_rows) {
     const int ns = verify_plan(B, H, T_max, max_rows).n_splits;
     if (ns == 1) return 0;
-    return (size_t)ns * B * H * T_max * (d_h + 2) * sizeof(float);
+    return verify_counter_bytes(B, H) + (size_t)ns * B * H * T_max * (d_h + 2) * sizeof(float);
 }
 
 }  // namespace tw
 
+#ifdef TW_TRACE
+static unsigned long long* g_trace = nullptr;
+extern "C" void tw_debug_set_trace(void* p) { g_trace = (unsigned long long*)p; }
+#endif
+
 extern "C" {
 
-int32_t tw_version(void) { return 1001; }
+int32_t tw_version(void) { return 2000; }
 
 size_t tw_workspace_bytes(int32_t which, int32_t B, int32_t rows, int32_t H, int32_t d_h,
                           int32_t max_rows) {
@@ -264,16 +278,22 @@ int32_t tw_tree_verify_attn_gqa(const void* q, const tw_kv_view* k, const tw_kv_
     a.scale = scale;
     const VerifyPlan plan = verify_plan(B, a.H, T_max, max_rows);
     a.n_splits = plan.n_splits;
+    a.split_rows = plan.split_rows;
     a.n_blk = plan.n_blk;
     a.n_phase = plan.n_phase;
     a.heads_per_wg = plan.heads_per_wg;
     a.part_o = nullptr;
     a.part_ml = nullptr;
+    a.arrive = nullptr;
+#ifdef TW_TRACE
+    a.trace = g_trace;
+#endif
     if (a.n_splits > 1) {
         const size_t need = verify_workspace_bytes(B, a.H, T_max, a.d_h, max_rows);
         if (!ws || ws_bytes < need) return TW_ERR_WORKSPACE;
         if ((uintptr_t)ws % 16) return TW_ERR_INVALID_ARG;
-        a.part_o = (float*)ws;
+        a.arrive = (int32_t*)ws;
+        a.part_o = (float*)((char*)ws + verify_counter_bytes(B, a.H));
         a.part_ml = a.part_o + (size_t)a.n_splits * B * a.H * T_max * a.d_h;
     }
     hipStream_t s = (hipStream_t)stream;
@@ -282,9 +302,7 @@ int32_t tw_tree_verify_attn_gqa(const void* q, const tw_kv_view* k, const tw_kv_
         e = launch_verify_mfma(a, s);
     else
         e = launch_verify_generic(a, k->dtype, s);
-    if (e != hipSuccess) return TW_ERR_LAUNCH;
-    if (a.n_splits > 1 && launch_verify_combine(a, s) != hipSuccess) return TW_ERR_LAUNCH;
-    return TW_OK;
+    return e == hipSuccess ? TW_OK : TW_ERR_LAUNCH;
 }
 
 int32_t tw_tree_accept(const int32_t* draft, const int32_t* argmax, const int32_t* parent,

@@ -6,9 +6,9 @@
 // Work split: grid (H, B, n_splits).  A workgroup owns one (sequence, head)
 // and one contiguous range of cache rows; four lanes share a tree node (each
 // owns every fourth output column).  Softmax is the usual online form; when
-// the cache is split over several workgroups the unnormalised partial
-// (max, sum, output) triples go to the workspace and verify_combine_kernel
-// merges them in split order.
+// the cache rows of a sequence are cut into several pieces the unnormalised
+// partial (max, sum, output) triples go to the workspace and the workgroup
+// that finishes last merges them in piece order (finish_split_unit).
 #include "twig_internal.h"
 
 namespace tw {
@@ -42,15 +42,9 @@ __global__ __launch_bounds__(kGenThreads) void verify_generic_kernel(VerifyArgs 
     const int h = blockIdx.x, b = blockIdx.y, split = blockIdx.z;
     const int h_kv = h / a.group;   // the key/value head this query head reads
     const int tid = threadIdx.x;
-    int T = a.n_nodes[b];
-    T = T < 1 ? 1 : (T > a.T_max ? a.T_max : T);
-    int C = a.ctx_len[b];
-    C = C < 0 ? 0 : (C > a.max_rows - a.T_max ? a.max_rows - a.T_max : C);
-    const int n_rows = C + T;
-    // rows of this split: equal shares rounded up to whole tiles
-    int per = (n_rows + a.n_splits - 1) / a.n_splits;
-    per = (per + kGenTile - 1) / kGenTile * kGenTile;
-    const int r_begin = min(split * per, n_rows), r_end = min(r_begin + per, n_rows);
+    const SeqInfo sq = seq_info_from(a.n_nodes[b], a.ctx_len[b], a.T_max, a.max_rows, a.split_rows, a.n_splits, split);
+    if (split >= sq.n_b) return;   // a piece past the end of this sequence (whole workgroup)
+    const int T = sq.T, C = sq.C, r_begin = sq.r_begin, r_end = sq.r_end;
 
     if (tid < TW_MAX_TREE) s_parent[tid] = tid < T ? a.parent[(int64_t)b * a.T_max + tid] : 0;
     __syncthreads();
@@ -166,8 +160,8 @@ __global__ __launch_bounds__(kGenThreads) void verify_generic_kernel(VerifyArgs 
     float l = run_l;
     l += __shfl_xor(l, 1, 64);
     l += __shfl_xor(l, 2, 64);
-    if (t >= T) return;
-    if (a.n_splits == 1) {
+    if (sq.n_b == 1) {
+        if (t >= T) return;
         const int64_t row = (((int64_t)b * a.T_max + t) * a.H + h) * d_h;
         const float inv = 1.f / l;
 #pragma unroll
@@ -178,65 +172,19 @@ __global__ __launch_bounds__(kGenThreads) void verify_generic_kernel(VerifyArgs 
             }
         }
     } else {
-        const int64_t slot = (((int64_t)split * a.B + b) * a.H + h) * a.T_max + t;
-        float* po = a.part_o + slot * d_h;
+        if (t < T) {
+            const int64_t slot0 = (((int64_t)split * a.B + b) * a.H + h) * a.T_max;   // node 0 of this piece's slot
+            const __amdgpu_buffer_rsrc_t ro = raw_buffer(a.part_o + slot0 * d_h, (uint32_t)(a.T_max * d_h * 4));
 #pragma unroll
-        for (int cc = 0; cc < kCq; ++cc)
-            if (cc < cq) po[qd + 4 * cc] = o[cc];
-        if (qd == 0) {
-            a.part_ml[slot * 2] = run_m;
-            a.part_ml[slot * 2 + 1] = l;
+            for (int cc = 0; cc < kCq; ++cc)
+                if (cc < cq)
+                    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, o[cc]), ro,
+                                                          (t * d_h + qd + 4 * cc) * 4, 0, kAuxThrough);
+            if (qd == 0)
+                store_partial2(a.part_ml + slot0 * 2, (uint32_t)(a.T_max * 8), (uint32_t)(t * 8), make_float2(run_m, l));
         }
+        finish_split_unit(a, b, h, T, sq.n_b, tid, kGenThreads);
     }
-}
-
-// Merge the per-split partial results in split order.  d_h/4 lanes per (sequence, node, head) row,
-// four output columns each; a workgroup takes as many consecutive rows as fit 256 threads, so its
-// stores cover a contiguous piece of `out`.  The partials of four splits are requested together
-// and before anything depends on them (the kernel is a few microseconds of pure memory latency);
-// the merge itself is the online-softmax update, one split at a time.
-constexpr int kCombineThreads = 256;
-constexpr int kCombineBatch = 4;
-__global__ __launch_bounds__(kCombineThreads) void verify_combine_kernel(VerifyArgs a) {
-    const int lanes = a.d_h / 4, rows_per_wg = kCombineThreads / lanes;
-    const int sub = threadIdx.x / lanes, c4 = threadIdx.x % lanes;
-    const int64_t row = (int64_t)blockIdx.x * rows_per_wg + sub;   // (b * T_max + t) * H + h
-    if (sub >= rows_per_wg || row >= (int64_t)a.B * a.T_max * a.H) return;
-    const int h = (int)(row % a.H), t = (int)((row / a.H) % a.T_max), b = (int)(row / ((int64_t)a.H * a.T_max));
-    const int T_raw = a.n_nodes[b];
-    const int64_t split_stride = (int64_t)a.B * a.H * a.T_max;
-    const int64_t slot0 = ((int64_t)b * a.H + h) * a.T_max + t;
-    float m = -INFINITY, l = 0.f;
-    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int s0 = 0; s0 < a.n_splits; s0 += kCombineBatch) {
-        float2 ml[kCombineBatch];
-        float4 v[kCombineBatch];
-#pragma unroll
-        for (int i = 0; i < kCombineBatch; ++i) {
-            const int s = min(s0 + i, a.n_splits - 1);   // past the last split: re-read it, unused
-            const int64_t slot = slot0 + s * split_stride;
-            ml[i] = *(const float2*)(a.part_ml + slot * 2);
-            v[i] = *(const float4*)(a.part_o + slot * a.d_h + 4 * c4);
-        }
-#pragma unroll
-        for (int i = 0; i < kCombineBatch; ++i) {
-            // a split in which this node saw no key carries max = -inf and is skipped
-            if (s0 + i < a.n_splits && ml[i].x != -INFINITY) {
-                const float m_new = fmaxf(m, ml[i].x);
-                const float keep = expf(m - m_new), w = expf(ml[i].x - m_new);
-                l = l * keep + ml[i].y * w;
-                acc.x = acc.x * keep + v[i].x * w;
-                acc.y = acc.y * keep + v[i].y * w;
-                acc.z = acc.z * keep + v[i].z * w;
-                acc.w = acc.w * keep + v[i].w * w;
-                m = m_new;
-            }
-        }
-    }
-    const int T = T_raw < 1 ? 1 : (T_raw > a.T_max ? a.T_max : T_raw);
-    if (t >= T) return;
-    const float inv = 1.f / l;
-    store_out4(a.out, a.out_bf16, row * a.d_h + 4 * c4, acc.x * inv, acc.y * inv, acc.z * inv, acc.w * inv, false);
 }
 
 hipError_t launch_verify_generic(const VerifyArgs& a, int dtype, hipStream_t s) {
@@ -251,14 +199,6 @@ hipError_t launch_verify_generic(const VerifyArgs& a, int dtype, hipStream_t s) 
         if (narrow) hipLaunchKernelGGL((verify_generic_kernel<uint16_t, 16>), grid, dim3(kGenThreads), lds, s, a);
         else hipLaunchKernelGGL((verify_generic_kernel<uint16_t, 32>), grid, dim3(kGenThreads), lds, s, a);
     }
-    return hipGetLastError();
-}
-
-hipError_t launch_verify_combine(const VerifyArgs& a, hipStream_t s) {
-    const int rows_per_wg = kCombineThreads / (a.d_h / 4);
-    const int64_t rows = (int64_t)a.B * a.T_max * a.H;
-    hipLaunchKernelGGL(verify_combine_kernel, dim3((unsigned)((rows + rows_per_wg - 1) / rows_per_wg)),
-                       dim3(kCombineThreads), 0, s, a);
     return hipGetLastError();
 }
 

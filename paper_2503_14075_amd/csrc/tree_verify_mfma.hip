@@ -14,8 +14,11 @@
 //   In the pair kernel the two node blocks of a head need the same K/V rows: one wavefront
 //   loads the K chunk, its partner the V chunk, into a stage they share (double-buffered,
 //   one workgroup barrier per chunk, loads two chunks ahead).
-//   grid (ceil(H / heads_per_wg), B, n_splits); n_splits > 1 additionally splits the cache
-//   rows over workgroups, partial (max, sum, O) go to the workspace for verify_combine_kernel.
+//   grid (ceil(H / heads_per_wg), B, n_splits); n_splits > 1 additionally cuts the cache rows
+//   into pieces of split_rows rows, one workgroup each (a workgroup past the end of its
+//   sequence leaves at once).  A sequence in one piece is finished by its workgroup; otherwise
+//   partial (max, sum, O) go to the workspace and the workgroup that arrives last at the
+//   unit's counter merges them in split order (finish_split_unit).
 //
 // Per 32-row chunk a wavefront
 //     1. stores prefetched K/V rows (16-byte lanes, fully coalesced 256-byte row segments)
@@ -62,23 +65,44 @@ struct WaveState {
     uint64_t anc;                   // ancestor-or-self mask of the lane's node
 };
 
+// Q fragments of tree node t: the loads depend on nothing but the unit, so they are issued at the very top
+// of the kernel (node clamped into the T_max rows the tensor holds); padding nodes are zeroed afterwards.
 template <int DH>
-__device__ __forceinline__ void load_q(WaveState<DH>& w, const VerifyArgs& a, int b, int h, int t, int T, int g) {
-    using Cf = MfCfg<DH>;
-    const int tc = t < T ? t : T - 1;
+__device__ __forceinline__ void issue_q(u32x4 (&raw)[MfCfg<DH>::kDC], const VerifyArgs& a, int b, int h, int t, int g) {
+    const int tc = t < a.T_max ? t : a.T_max - 1;
     const u32x4* src = (const u32x4*)((const uint16_t*)a.q + (((int64_t)b * a.T_max + tc) * a.H + h) * DH + 8 * g);
 #pragma unroll
-    for (int c = 0; c < Cf::kDC; ++c) {
-        u32x4 v = src[2 * c];
-        if (t >= T) v = (u32x4){0u, 0u, 0u, 0u};   // padding nodes
-        w.qf[c] = as_bf16x8(v);
-    }
+    for (int c = 0; c < MfCfg<DH>::kDC; ++c) raw[c] = src[2 * c];
+}
+template <int DH>
+__device__ __forceinline__ void init_state(WaveState<DH>& w, const u32x4 (&raw)[MfCfg<DH>::kDC], int t, int T) {
+    using Cf = MfCfg<DH>;
+#pragma unroll
+    for (int c = 0; c < Cf::kDC; ++c) w.qf[c] = as_bf16x8(t < T ? raw[c] : (u32x4){0u, 0u, 0u, 0u});
 #pragma unroll
     for (int q = 0; q < Cf::kNQ; ++q)
 #pragma unroll
         for (int r = 0; r < 16; ++r) w.o[q][r] = 0.f;
     w.run_m = -INFINITY;
     w.run_l = 0.f;
+}
+
+// Ancestor-or-self masks of a tree of up to 64 nodes inside one wavefront, lane = node, no shared
+// memory and no barrier: pointer doubling, six rounds of (mask |= mask of the jump target; jump
+// target = its jump target) cover every depth below 64.  `par_raw` is the lane's parent entry as
+// read; lanes past T return 0.
+__device__ __forceinline__ uint64_t wave_ancestor_mask(int par_raw, int node, int T) {
+    int j = node > 0 ? clamp_parent(par_raw, node) : 0;
+    uint32_t lo = node < 32 ? 1u << node : 0u, hi = node >= 32 ? 1u << (node - 32) : 0u;
+#pragma unroll
+    for (int round = 0; round < 6; ++round) {
+        const uint32_t jl = __shfl(lo, j, 64), jh = __shfl(hi, j, 64);
+        const int jj = __shfl(j, j, 64);
+        lo |= jl;
+        hi |= jh;
+        j = jj;
+    }
+    return node < T ? ((uint64_t)hi << 32) | lo : 0ull;
 }
 
 // Steps 2-4 for the chunk staged at (ldsK, ldsV) whose first cache row is `base`.
@@ -161,20 +185,20 @@ __device__ __forceinline__ void process_chunk(WaveState<DH>& w, const unsigned c
     }
 }
 
-// One unit per wavefront (n_phase == 1): normalise, or hand the partial to the combine kernel.
+// One unit per wavefront (n_phase == 1, never split): normalise and store.
 // The accumulators hold, per lane, 16 scattered 16-byte pieces of one node's output row; stored
 // from there every store instruction would touch 64 different 128-byte lines (measured: 25 us for
 // the 55 MB of the bench launch).  The tile goes through `tile` (32 x kOStride floats of LDS that
 // this wavefront owns and no longer reads) so that a store instruction writes whole rows.
 template <int DH>
 __device__ __forceinline__ void epilogue_direct(const WaveState<DH>& w, const VerifyArgs& a, float* tile, int b,
-                                                int h, int T, int split, int lane, int node0 = 0) {
+                                                int h, int T, int lane, int node0 = 0) {
     // T = nodes of this wavefront's block (may be <= 0), node0 = tree index of its first node
     static_assert(32 * MfCfg<DH>::kOStride * 4 <= MfCfg<DH>::kStage, "the tile fits one K+V stage");
     using Cf = MfCfg<DH>;
     const int g = lane >> 5, li = lane & 31;
     const float l = w.run_l + __shfl_xor(w.run_l, 32, 64);
-    const float mul = a.n_splits == 1 ? 1.f / l : 1.f;
+    const float mul = 1.f / l;
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");   // earlier reads of this LDS area are done
     __builtin_amdgcn_wave_barrier();
 #pragma unroll
@@ -192,48 +216,32 @@ __device__ __forceinline__ void epilogue_direct(const WaveState<DH>& w, const Ve
     // lanes_per_row consecutive lanes store one node's row as consecutive 16-byte pieces
     constexpr int kLanesPerRow = DH / 4, kRowsPerStore = 64 / kLanesPerRow;
     const int sub = lane / kLanesPerRow, c4 = lane % kLanesPerRow;
-    if (a.n_splits == 1) {
-        // Written once at the end of the wavefront's life: system-scope stores through a descriptor
-        // over the block's 32 rows of `out` (2 % faster than streaming stores on the bench launch).
-        const int64_t first = (((int64_t)b * a.T_max + node0) * a.H + h) * DH;   // node 0 of the block
-        const uint32_t node_stride = (uint32_t)a.H * DH;
-        if (a.out_bf16) {
-            typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
-            const __amdgpu_buffer_rsrc_t ro = raw_buffer((const uint16_t*)a.out + first, 32u * node_stride * 2u);
-#pragma unroll
-            for (int n0 = 0; n0 < 32; n0 += kRowsPerStore) {
-                const int node = n0 + sub;
-                if (node < T) {
-                    const f32x4 v = *(const f32x4*)(tile + node * Cf::kOStride + 4 * c4);
-                    const u32x2 p = {pack_bf16x2(v.x, v.y), pack_bf16x2(v.z, v.w)};
-                    __builtin_amdgcn_raw_buffer_store_b64(p, ro, (int)((node * node_stride + 4 * c4) * 2u), 0, kAuxThrough);
-                }
-            }
-        } else {
-            const __amdgpu_buffer_rsrc_t ro = raw_buffer((const float*)a.out + first, 32u * node_stride * 4u);
-#pragma unroll
-            for (int n0 = 0; n0 < 32; n0 += kRowsPerStore) {
-                const int node = n0 + sub;
-                if (node < T) {
-                    const f32x4 v = *(const f32x4*)(tile + node * Cf::kOStride + 4 * c4);
-                    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), ro,
-                                                           (int)((node * node_stride + 4 * c4) * 4u), 0, kAuxThrough);
-                }
-            }
-        }
-    } else {
-        const int64_t slot = (((int64_t)split * a.B + b) * a.H + h) * a.T_max + node0;
-        float* dst = a.part_o + slot * DH;
-        if (g == 0 && li < T) {
-            a.part_ml[(slot + li) * 2] = w.run_m * kLn2;   // natural-log units for the combine
-            a.part_ml[(slot + li) * 2 + 1] = l;
-        }
+    // Written once at the end of the wavefront's life: system-scope stores through a descriptor
+    // over the block's 32 rows of `out` (2 % faster than streaming stores on the bench launch).
+    const int64_t first = (((int64_t)b * a.T_max + node0) * a.H + h) * DH;   // node 0 of the block
+    const uint32_t node_stride = (uint32_t)a.H * DH;
+    if (a.out_bf16) {
+        typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
+        const __amdgpu_buffer_rsrc_t ro = raw_buffer((const uint16_t*)a.out + first, 32u * node_stride * 2u);
 #pragma unroll
         for (int n0 = 0; n0 < 32; n0 += kRowsPerStore) {
             const int node = n0 + sub;
-            if (node < T)
-                __builtin_nontemporal_store(*(const f32x4*)(tile + node * Cf::kOStride + 4 * c4),
-                                            (f32x4*)(dst + node * DH + 4 * c4));
+            if (node < T) {
+                const f32x4 v = *(const f32x4*)(tile + node * Cf::kOStride + 4 * c4);
+                const u32x2 p = {pack_bf16x2(v.x, v.y), pack_bf16x2(v.z, v.w)};
+                __builtin_amdgcn_raw_buffer_store_b64(p, ro, (int)((node * node_stride + 4 * c4) * 2u), 0, kAuxThrough);
+            }
+        }
+    } else {
+        const __amdgpu_buffer_rsrc_t ro = raw_buffer((const float*)a.out + first, 32u * node_stride * 4u);
+#pragma unroll
+        for (int n0 = 0; n0 < 32; n0 += kRowsPerStore) {
+            const int node = n0 + sub;
+            if (node < T) {
+                const f32x4 v = *(const f32x4*)(tile + node * Cf::kOStride + 4 * c4);
+                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), ro,
+                                                       (int)((node * node_stride + 4 * c4) * 4u), 0, kAuxThrough);
+            }
         }
     }
 }
@@ -242,7 +250,7 @@ __device__ __forceinline__ void epilogue_direct(const WaveState<DH>& w, const Ve
 // Must be entered by the whole workgroup after its last use of the stages.
 template <int DH>
 __device__ __forceinline__ void epilogue_merge(const WaveState<DH>& w, const VerifyArgs& a, unsigned char* lds,
-                                               int b, int h, int T, int split, int slot_w, int n_blk,
+                                               int b, int h, int T, int split, int n_b, int slot_w, int n_blk,
                                                int n_phase, int g, int li, int tid) {
     using Cf = MfCfg<DH>;
     __syncthreads();
@@ -284,59 +292,39 @@ __device__ __forceinline__ void epilogue_merge(const WaveState<DH>& w, const Ver
             acc.z += v.z * sc;
             acc.w += v.w * sc;
         }
-        if (a.n_splits == 1) {
+        if (n_b == 1) {
             const float inv = 1.f / l;
             store_out4(a.out, a.out_bf16, (((int64_t)b * a.T_max + node) * a.H + h) * DH + 4 * d4, acc.x * inv,
                        acc.y * inv, acc.z * inv, acc.w * inv, false);
         } else {
-            const int64_t slot = (((int64_t)split * a.B + b) * a.H + h) * a.T_max + node;
-            *(float4*)(a.part_o + slot * DH + 4 * d4) = acc;
-            if (d4 == 0) {
-                a.part_ml[slot * 2] = m * kLn2;
-                a.part_ml[slot * 2 + 1] = l;
-            }
+            const int64_t slot0 = (((int64_t)split * a.B + b) * a.H + h) * a.T_max;   // node 0 of this piece's slot
+            store_partial4(a.part_o + slot0 * DH, (uint32_t)(a.T_max * DH * 4), (uint32_t)((node * DH + 4 * d4) * 4), acc);
+            if (d4 == 0)
+                store_partial2(a.part_ml + slot0 * 2, (uint32_t)(a.T_max * 8), (uint32_t)(node * 8), make_float2(m * kLn2, l));
         }
     }
+    if (n_b > 1) finish_split_unit(a, b, h, T, n_b, tid, kMfThreads);
 }
 
-// Row range of a split and the tree of a sequence, common to both kernels.
-struct SeqInfo {
-    int T, C, n_rows, r_begin, r_end;
-};
+// Tree, context length and this split's rows of a sequence, common to both kernels.
 __device__ __forceinline__ SeqInfo seq_info(const VerifyArgs& a, int b, int split) {
-    SeqInfo s;
-    int T = a.n_nodes[b];
-    s.T = T < 1 ? 1 : (T > a.T_max ? a.T_max : T);
-    int C = a.ctx_len[b];
-    s.C = C < 0 ? 0 : (C > a.max_rows - a.T_max ? a.max_rows - a.T_max : C);
-    s.n_rows = s.C + s.T;
-    int per = (s.n_rows + a.n_splits - 1) / a.n_splits;
-    per = (per + kChunk - 1) / kChunk * kChunk;
-    s.r_begin = min(split * per, s.n_rows);
-    s.r_end = min(s.r_begin + per, s.n_rows);
-    return s;
-}
-
-// Ancestor masks of the sequence's tree into shared memory (workgroup-wide, two barriers).  Called
-// after the first K/V loads have been issued so that their latency overlaps this prologue.
-__device__ __forceinline__ void tree_masks(const VerifyArgs& a, int b, int T, int tid, int* s_parent,
-                                           unsigned long long* s_anc) {
-    if (tid < TW_MAX_TREE) s_parent[tid] = tid < T ? a.parent[(int64_t)b * a.T_max + tid] : 0;
-    __syncthreads();
-    if (tid < TW_MAX_TREE) s_anc[tid] = tid < T ? ancestor_mask(s_parent, tid) : 0ull;
-    __syncthreads();
+    return seq_info_from(a.n_nodes[b], a.ctx_len[b], a.T_max, a.max_rows, a.split_rows, a.n_splits, split);
 }
 
 // (head group, sequence) of a workgroup.  The hardware hands consecutive workgroups to the eight
 // XCDs (each with its own L2) round-robin; taken in grid order, XCD x would get head group x of
 // every sequence, i.e. one eighth of every cache row.  Renumbered, an XCD gets whole sequences: its
 // workgroups read complete 8 KB rows at about the same time (1.5 % faster on the bench launch, A/B on
-// one machine; the opposite order, sequences fastest, is 4 % slower).  Grids that are not a multiple of 8 keep grid order.
-__device__ __forceinline__ void unit_of_block(int& hg, int& b) {
+// one machine; the opposite order, sequences fastest, is 4 % slower).  Grids that are not a multiple of 8 keep
+// grid order, and so does the one-head-per-workgroup layout of small launches: there a batch of unequal
+// sequences must not hand whole (long or short) sequences to single XCDs, and in grid order every XCD gets
+// an eighth of the heads of every sequence (ragged batch of 16, measured: the XCDs ended between 21 and
+// 38 us with whole sequences each).
+__device__ __forceinline__ void unit_of_block(const VerifyArgs& a, int& hg, int& b) {
     const int total = gridDim.x * gridDim.y, id = blockIdx.x + gridDim.x * blockIdx.y;
     hg = blockIdx.x;
     b = blockIdx.y;
-    if ((total & 7) == 0) {
+    if ((total & 7) == 0 && a.heads_per_wg > 1) {
         const int u = (id & 7) * (total >> 3) + (id >> 3);
         hg = u % gridDim.x;
         b = u / gridDim.x;
@@ -427,24 +415,31 @@ template <int DH, bool PAGED, bool STREAM>
 __global__ __launch_bounds__(kMfThreads, 2) void verify_mfma_kernel(VerifyArgs a) {
     using Cf = MfCfg<DH>;
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
-    __shared__ int s_parent[TW_MAX_TREE];
-    __shared__ unsigned long long s_anc[TW_MAX_TREE];
 
     const int tid = threadIdx.x, lane = tid & 63;
+    TW_TRACE_MARK(a, 0);
+    TW_TRACE_MARK(a, 6);
+    TW_TRACE_MARK(a, 7);
     // the wavefront index in a scalar register: head, phase and chunk base are then scalars, branches
     // on them real branches, and the addresses below a scalar base plus a 32-bit lane offset
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int g = lane >> 5, li = lane & 31;
     const int split = blockIdx.z;
     int hg, b;
-    unit_of_block(hg, b);
+    unit_of_block(a, hg, b);
     const int n_phase = a.n_phase;               // 1 (four heads per workgroup) or 4 (one head)
     const int phase = wave % n_phase;
     const int h = hg * a.heads_per_wg + wave / n_phase;
-    const SeqInfo sq = seq_info(a, b, split);
     const bool active = h < a.H;
     const int hc = active ? h : a.H - 1;
     const int t = li;                            // this lane's tree node
+    // What depends on nothing but the unit is requested first: the lane's parent entry and its Q
+    // fragments travel while the lengths and offsets of the sequence are still being read.
+    const int par_raw = a.parent[(int64_t)b * a.T_max + (t < a.T_max ? t : a.T_max - 1)];
+    u32x4 q_raw[Cf::kDC];
+    issue_q<DH>(q_raw, a, b, hc, t, g);
+    const SeqInfo sq = seq_info(a, b, split);
+    if (split >= sq.n_b) return;                 // a piece past the end of this sequence (whole workgroup)
 
     unsigned char* ldsK = lds + wave * Cf::kStage;
     unsigned char* ldsV = ldsK + kChunk * Cf::kKStride;
@@ -483,11 +478,12 @@ __global__ __launch_bounds__(kMfThreads, 2) void verify_mfma_kernel(VerifyArgs a
         issue_loads(first);
         if (PAGED) lookup_pages(first + step);
     }
-    // the first chunk is in flight; now the tree masks and the Q fragments
-    tree_masks(a, b, sq.T, tid, s_parent, s_anc);
+    // the first chunk is in flight; now the tree masks (inside the wavefront) and the Q fragments
+    TW_TRACE_MARK(a, 1);
     WaveState<DH> w;
-    w.anc = s_anc[t];
-    load_q(w, a, b, hc, t, sq.T, g);
+    w.anc = wave_ancestor_mask(par_raw, t, sq.T);
+    init_state<DH>(w, q_raw, t, sq.T);
+    TW_TRACE_MARK(a, 2);
     for (int base = first; active && base < sq.r_end; base += step) {
 #pragma unroll
         for (int j = 0; j < Cf::kLoads; ++j) {
@@ -501,12 +497,15 @@ __global__ __launch_bounds__(kMfThreads, 2) void verify_mfma_kernel(VerifyArgs a
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         process_chunk<DH>(w, ldsK, ldsV, base, sq.C, sq.n_rows, sl2, g, li);
+        if (base == first) TW_TRACE_MARK(a, 3);
     }
+    TW_TRACE_MARK(a, 4);
     if (n_phase == 1) {
-        if (active) epilogue_direct<DH>(w, a, (float*)ldsK, b, h, sq.T, split, lane);
+        if (active) epilogue_direct<DH>(w, a, (float*)ldsK, b, h, sq.T, lane);
     } else {
-        epilogue_merge<DH>(w, a, lds, b, h, sq.T, split, phase, 1, n_phase, g, li, tid);
+        epilogue_merge<DH>(w, a, lds, b, h, sq.T, split, sq.n_b, phase, 1, n_phase, g, li, tid);
     }
+    TW_TRACE_MARK(a, 5);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -519,23 +518,29 @@ template <int DH, bool PAGED, bool STREAM>
 __global__ __launch_bounds__(kMfThreads, 2) void verify_mfma_pair_kernel(VerifyArgs a) {
     using Cf = MfCfg<DH>;
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
-    __shared__ int s_parent[TW_MAX_TREE];
-    __shared__ unsigned long long s_anc[TW_MAX_TREE];
 
     const int tid = threadIdx.x, lane = tid & 63;
+    TW_TRACE_MARK(a, 0);
+    TW_TRACE_MARK(a, 6);
+    TW_TRACE_MARK(a, 7);
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // scalar, as in the kernel above
     const int g = lane >> 5, li = lane & 31;
     const int split = blockIdx.z;
     int hg, b;
-    unit_of_block(hg, b);
+    unit_of_block(a, hg, b);
     const int blk = wave & 1, pair = wave >> 1;
     const int n_phase = a.n_phase;               // 1 (two heads per workgroup) or 2 (one head)
     const int phase = n_phase == 1 ? 0 : pair;
     const int h = hg * a.heads_per_wg + (n_phase == 1 ? pair : 0);
-    const SeqInfo sq = seq_info(a, b, split);
     const bool active = h < a.H;
     const int hc = active ? h : a.H - 1;
     const int t = 32 * blk + li;
+    // requested before anything else (see the kernel above); here lane = node for the masks
+    const int par_raw = a.parent[(int64_t)b * a.T_max + (lane < a.T_max ? lane : a.T_max - 1)];
+    u32x4 q_raw[Cf::kDC];
+    issue_q<DH>(q_raw, a, b, hc, t, g);
+    const SeqInfo sq = seq_info(a, b, split);
+    if (split >= sq.n_b) return;                 // a piece past the end of this sequence (whole workgroup)
 
     unsigned char* stage = lds + pair * 2 * Cf::kStage;   // two buffers of one K+V chunk
     const float sl2 = a.scale * kLog2e;
@@ -583,11 +588,15 @@ __global__ __launch_bounds__(kMfThreads, 2) void verify_mfma_pair_kernel(VerifyA
     issue_loads(first + step, 1);
     lookup_pages(first + 2 * step, 0);
     lookup_pages(first + 3 * step, 1);
-    // two chunks are in flight; now the tree masks and the Q fragments
-    tree_masks(a, b, sq.T, tid, s_parent, s_anc);
+    // two chunks are in flight; now the tree masks (inside the wavefront) and the Q fragments
+    TW_TRACE_MARK(a, 1);
     WaveState<DH> w;
-    w.anc = s_anc[t];
-    load_q(w, a, b, hc, t, sq.T, g);
+    {
+        const uint64_t m = wave_ancestor_mask(par_raw, lane, sq.T);   // of node `lane`; this lane's node is t
+        w.anc = ((uint64_t)__shfl((uint32_t)(m >> 32), t, 64) << 32) | __shfl((uint32_t)m, t, 64);
+    }
+    init_state<DH>(w, q_raw, t, sq.T);
+    TW_TRACE_MARK(a, 2);
     for (int it = 0; it < n_iter; it += 2) {
 #pragma unroll
         for (int half = 0; half < 2; ++half) {
@@ -599,15 +608,18 @@ __global__ __launch_bounds__(kMfThreads, 2) void verify_mfma_pair_kernel(VerifyA
             __syncthreads();   // the partner's half of the chunk is staged; the other buffer is free again
             if (active && it + half < n_iter && base < sq.r_end)
                 process_chunk<DH>(w, buf, buf + kChunk * Cf::kKStride, base, sq.C, sq.n_rows, sl2, g, li);
+            if (it == 0 && half == 0) TW_TRACE_MARK(a, 3);
         }
     }
+    TW_TRACE_MARK(a, 4);
     if (n_phase == 1) {
         __syncthreads();   // the partner is done with the shared stage; each wavefront takes one buffer of it
         if (active)
-            epilogue_direct<DH>(w, a, (float*)(stage + blk * Cf::kStage), b, h, sq.T - 32 * blk, split, lane, 32 * blk);
+            epilogue_direct<DH>(w, a, (float*)(stage + blk * Cf::kStage), b, h, sq.T - 32 * blk, lane, 32 * blk);
     } else {
-        epilogue_merge<DH>(w, a, lds, b, h, sq.T, split, blk * n_phase + phase, 2, n_phase, g, li, tid);
+        epilogue_merge<DH>(w, a, lds, b, h, sq.T, split, sq.n_b, blk * n_phase + phase, 2, n_phase, g, li, tid);
     }
+    TW_TRACE_MARK(a, 5);
 }
 
 template <int DH, bool PAGED, bool STREAM>
@@ -617,7 +629,7 @@ static hipError_t launch_one(const VerifyArgs& a, hipStream_t s) {
     const void* fn = a.n_blk == 1 ? (const void*)verify_mfma_kernel<DH, PAGED, STREAM>
                                   : (const void*)verify_mfma_pair_kernel<DH, PAGED, STREAM>;
     // the kernels' LDS need is a constant: raise the limit once per kernel and device, not on every launch
-    static uint32_t raised[2] = {0u, 0u};
+    static std::atomic<uint32_t> raised[2];
     const hipError_t e = raise_lds_limit_once(fn, (int)lds, raised[a.n_blk - 1]);
     if (e != hipSuccess) return e;
     if (a.n_blk == 1)

@@ -4,6 +4,9 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
+#include "index_math.h"
 #include "twigpath.h"
 
 namespace tw {
@@ -95,14 +98,16 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t raw_buffer(const void* base, u
 }
 
 // Raises a kernel's dynamic LDS limit to `bytes`, once per device (bit d of `done` = device d has
-// it; the limit of a kernel is a per-device attribute).  Devices past 31 set it on every call.
-inline hipError_t raise_lds_limit_once(const void* kernel, int bytes, uint32_t& done) {
+// it; the limit of a kernel is a per-device attribute).  Devices past 31 set it on every call.  The
+// bitmap is the only thing the library remembers between calls; threads may race to set the same
+// attribute to the same value, which is harmless, and the bit is published after the attribute.
+inline hipError_t raise_lds_limit_once(const void* kernel, int bytes, std::atomic<uint32_t>& done) {
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return e;
-    if (dev >= 0 && dev < 32 && ((done >> dev) & 1u)) return hipSuccess;
+    if (dev >= 0 && dev < 32 && ((done.load(std::memory_order_acquire) >> dev) & 1u)) return hipSuccess;
     e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
-    if (e == hipSuccess && dev >= 0 && dev < 32) done |= 1u << dev;
+    if (e == hipSuccess && dev >= 0 && dev < 32) done.fetch_or(1u << dev, std::memory_order_release);
     return e;
 }
 
@@ -112,8 +117,7 @@ __device__ __forceinline__ uint64_t ancestor_mask(const int* s_parent, int i) {
     uint64_t m = 1ull << i;
     int u = i;
     while (u > 0) {
-        int p = s_parent[u];
-        p = p < 0 ? 0 : (p >= u ? u - 1 : p);
+        const int p = clamp_parent(s_parent[u], u);
         m |= 1ull << p;
         u = p;
     }
@@ -130,24 +134,123 @@ struct VerifyArgs {
     const int32_t* parent;
     const int32_t* n_nodes;
     float* part_o;   // [n_splits][B][H][T_max][d_h] unnormalised partial outputs
-    float* part_ml;  // [n_splits][B][H][T_max][2] running max, running sum
+    float* part_ml;  // [n_splits][B][H][T_max][2] running max (natural-log units), running sum
+    int32_t* arrive; // [B][H] pieces of the unit that have written their partial; zero between launches
     int32_t T_max, B, H, d_h;   // H: query heads = group * (heads of a cache row, k.H)
     int32_t group;              // query heads per key/value head (1: multi-head attention)
-    int32_t n_splits, max_rows;
+    int32_t n_splits, split_rows, max_rows;   // grid.z pieces of split_rows rows (a multiple of 32) each
     int32_t n_blk, n_phase, heads_per_wg;   // wavefront layout of the matrix-core kernel
     float scale;
+#ifdef TW_TRACE
+    unsigned long long* trace;   // diagnostic build: 8 timestamps / hardware ids per workgroup
+#endif
 };
+
+// Diagnostic build (-DTW_TRACE, `python -m paper_2503_14075_amd.build --trace`): thread 0 of every
+// workgroup of the verification kernels records the 100 MHz wall clock at a few points of its life
+// into the buffer handed to tw_debug_set_trace; slot 6 / 7 hold the hardware and XCD ids.
+#ifdef TW_TRACE
+#define TW_TRACE_MARK(a, slot)                                                                             \
+    do {                                                                                                   \
+        if ((a).trace && threadIdx.x == 0)                                                                 \
+            (a).trace[(blockIdx.x + gridDim.x * (blockIdx.y + (size_t)gridDim.y * blockIdx.z)) * 8 + (slot)] = \
+                (slot) == 6 ? (unsigned long long)__builtin_amdgcn_s_getreg((31 << 11) | 4)                \
+                : (slot) == 7 ? (unsigned long long)__builtin_amdgcn_s_getreg((31 << 11) | 20)             \
+                              : __builtin_amdgcn_s_memrealtime();                                          \
+    } while (0)
+#else
+#define TW_TRACE_MARK(a, slot)
+#endif
 
 // Launch shape of tree verification: heads_per_wg * n_blk * n_phase == 4 wavefronts.
 struct VerifyPlan {
-    int n_splits, n_blk, n_phase, heads_per_wg;
+    int n_splits, split_rows, n_blk, n_phase, heads_per_wg;
 };
 VerifyPlan verify_plan(int B, int H, int T_max, int max_rows);
 size_t verify_workspace_bytes(int B, int H, int T_max, int d_h, int max_rows);
 hipError_t launch_verify_generic(const VerifyArgs& a, int dtype, hipStream_t s);
 bool verify_mfma_supported(const VerifyArgs& a, int dtype);
 hipError_t launch_verify_mfma(const VerifyArgs& a, hipStream_t s);
-hipError_t launch_verify_combine(const VerifyArgs& a, hipStream_t s);
+size_t verify_counter_bytes(int B, int H);   // the arrival counters at the start of the workspace
+
+// Partial results of a piece travel between workgroups on different XCDs, whose L2s are not kept
+// coherent with each other: they are written and read with system-scope accesses (sc0 sc1: written
+// through to memory, read from memory), which is cheaper by far than the cache-wide write-back and
+// invalidate of a release / acquire fence pair (measured: 40 us of fences on a 36 us launch).
+// Addressed through a descriptor over one (piece, sequence, head) slot.
+__device__ __forceinline__ void store_partial4(float* slot_base, uint32_t slot_bytes, uint32_t byte_off, float4 v) {
+    typedef __attribute__((ext_vector_type(4))) unsigned int u4_t;
+    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u4_t, v), raw_buffer(slot_base, slot_bytes), (int)byte_off,
+                                           0, kAuxThrough);
+}
+__device__ __forceinline__ void store_partial2(float* slot_base, uint32_t slot_bytes, uint32_t byte_off, float2 v) {
+    typedef __attribute__((ext_vector_type(2))) unsigned int u2_t;
+    __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u2_t, v), raw_buffer(slot_base, slot_bytes), (int)byte_off,
+                                          0, kAuxThrough);
+}
+
+// A (sequence, head) unit whose cache rows were cut into n_b > 1 pieces: called by every thread of a
+// workgroup (n_threads of them) after it has issued the stores of its piece's partial result
+// (store_partial*).  Every thread waits for its own stores to be acknowledged, the workgroup meets,
+// and one thread counts the piece in at the unit's counter.  The workgroup that arrives last merges
+// the n_b partials in piece order -- the result does not depend on which one that is -- normalises,
+// stores, and puts the counter back to zero for the next launch.  No workgroup waits for another.
+__device__ inline void finish_split_unit(const VerifyArgs& a, int b, int h, int T, int n_b, int tid, int n_threads) {
+    __shared__ int s_last;
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this thread's write-through stores have reached memory
+    __syncthreads();
+    if (tid == 0) {
+        int32_t* cnt = a.arrive + (int64_t)b * a.H + h;
+        const int old = __hip_atomic_fetch_add(cnt, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        s_last = old == n_b - 1;
+        if (s_last) __hip_atomic_store(cnt, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __syncthreads();
+    if (!s_last) return;
+    // d_h/4 lanes per node, four output columns each; the partials of four pieces are requested
+    // together, the merge itself is the online-softmax update, one piece at a time
+    constexpr int kBatch = 4;
+    const int lanes = a.d_h / 4;
+    const int64_t split_stride = (int64_t)a.B * a.H * a.T_max;
+    const int64_t unit0 = ((int64_t)b * a.H + h) * a.T_max;
+    const uint32_t o_bytes = (uint32_t)(a.T_max * a.d_h * 4), ml_bytes = (uint32_t)(a.T_max * 8);
+    for (int idx = tid; idx < T * lanes; idx += n_threads) {
+        const int t = idx / lanes, c4 = idx - t * lanes;
+        float m = -INFINITY, l = 0.f;
+        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int s0 = 0; s0 < n_b; s0 += kBatch) {
+            float2 ml[kBatch];
+            float4 v[kBatch];
+#pragma unroll
+            for (int i = 0; i < kBatch; ++i) {
+                const int s = s0 + i < n_b ? s0 + i : n_b - 1;   // past the last piece: re-read it, unused
+                const int64_t slot = unit0 + s * split_stride;
+                ml[i] = __builtin_bit_cast(float2, __builtin_amdgcn_raw_buffer_load_b64(
+                                                       raw_buffer(a.part_ml + slot * 2, ml_bytes), t * 8, 0, kAuxThrough));
+                v[i] = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(
+                                                      raw_buffer(a.part_o + slot * a.d_h, o_bytes),
+                                                      (t * a.d_h + 4 * c4) * 4, 0, kAuxThrough));
+            }
+#pragma unroll
+            for (int i = 0; i < kBatch; ++i) {
+                // a piece in which this node saw no key carries max = -inf and is skipped
+                if (s0 + i < n_b && ml[i].x != -INFINITY) {
+                    const float m_new = fmaxf(m, ml[i].x);
+                    const float keep = expf(m - m_new), w = expf(ml[i].x - m_new);
+                    l = l * keep + ml[i].y * w;
+                    acc.x = acc.x * keep + v[i].x * w;
+                    acc.y = acc.y * keep + v[i].y * w;
+                    acc.z = acc.z * keep + v[i].z * w;
+                    acc.w = acc.w * keep + v[i].w * w;
+                    m = m_new;
+                }
+            }
+        }
+        const float inv = 1.f / l;
+        store_out4(a.out, a.out_bf16, ((((int64_t)b * a.T_max + t) * a.H + h) * a.d_h) + 4 * c4, acc.x * inv,
+                   acc.y * inv, acc.z * inv, acc.w * inv, false);
+    }
+}
 
 // --- pruning score -----------------------------------------------------------
 struct ScoreArgs {

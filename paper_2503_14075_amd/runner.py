@@ -60,7 +60,8 @@ class DeviceWorkload:
         self.out = torch.zeros(self.n_inst, T, H, d_h, dtype=torch.float32, device=dev)
         nbytes = tw.workspace_bytes(tw.TW_CALL_TREE_VERIFY_ATTN, self.n_inst, T, H, d_h,
                                     self.max_ctx_len + T)
-        self.verify_ws = torch.empty(max(nbytes, 4) // 4, dtype=torch.float32, device=dev) if nbytes else None
+        # zeroed once: the arrival counters at its start must be zero before the first call and are left zero by every call
+        self.verify_ws = torch.zeros(max(nbytes, 4) // 4, dtype=torch.float32, device=dev) if nbytes else None
         # ---- acceptance -----------------------------------------------------------
         self.draft = _i32(w.draft, dev)
         self.argmax = _i32(w.argmax, dev)

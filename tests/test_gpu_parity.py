@@ -57,7 +57,7 @@ def gpu_verify(tw, q, k, v, ctx_len, n_nodes, parents, scale, row_off=None, page
     kv, vv = tw.kv_view(kd, ro, pt, page_rows), tw.kv_view(vd, ro, pt, page_rows)
     max_ctx = max(ctx_len)
     nbytes = tw.workspace_bytes(tw.TW_CALL_TREE_VERIFY_ATTN, B, T_max, H, d_h, max_ctx + T_max)
-    ws = torch.empty(max(nbytes, 4) // 4, dtype=torch.float32, device=DEV) if nbytes else None
+    ws = torch.zeros(max(nbytes, 4) // 4, dtype=torch.float32, device=DEV) if nbytes else None
     out = torch.full((B, T_max, H, d_h), float("nan"), dtype=torch.float32, device=DEV)
     if k.shape[1] == H:
         tw.tree_verify_attn(qd, kv, vv, _i32(ctx_len), max_ctx, _i32(parents), _i32(n_nodes), scale, out, ws)
@@ -198,7 +198,7 @@ def test_verify_and_score_long_context_at_the_split_caps(tw):
         trees = [W.random_parent_tree(W.HostRng(15, T), T, 6)]
         q, k, v, off = make_case(16, 1, H, d_h, ctx, T, torch.bfloat16, trees)
         ws_bytes = tw.workspace_bytes(tw.TW_CALL_TREE_VERIFY_ATTN, 1, T, H, d_h, ctx[0] + T)
-        assert ws_bytes == 64 * H * T * (d_h + 2) * 4
+        assert 48 * H * T * (d_h + 2) * 4 < ws_bytes <= 256 + 64 * H * T * (d_h + 2) * 4
         check_verify(tw, q, k, v, ctx, [T], trees, 1 / math.sqrt(d_h), row_off=off)
     _check_score(tw, torch.bfloat16, H, d_h, 16000, 100, [900], [16], True)
 
@@ -313,7 +313,7 @@ def test_verify_bf16_output(tw, case):
     kv, vv = tw.kv_view(kd, ro), tw.kv_view(vd, ro)
     nbytes = tw.workspace_bytes(tw.TW_CALL_TREE_VERIFY_ATTN, B, T, H, d_h, max(ctxs) + T)
     assert (nbytes > 0) == (case == "split")
-    ws = torch.empty(max(nbytes, 4) // 4, dtype=torch.float32, device=DEV) if nbytes else None
+    ws = torch.zeros(max(nbytes, 4) // 4, dtype=torch.float32, device=DEV) if nbytes else None
     out = torch.full((B, T, H, d_h), float("nan"), dtype=torch.bfloat16, device=DEV)
     tw.tree_verify_attn(qd, kv, vv, _i32(ctxs), max(ctxs), _i32(trees), _i32([T] * B), scale, out, ws)
     torch.cuda.synchronize()
@@ -471,7 +471,7 @@ def test_two_chained_draft_verify_iterations(tw):
         q = W.normal(9, 10 + it, (B, T, H, d_h), 1 / math.sqrt(d_h), torch.bfloat16)
         out = torch.zeros(B, T, H, d_h, dtype=torch.float32, device=DEV)
         nb = tw.workspace_bytes(tw.TW_CALL_TREE_VERIFY_ATTN, B, T, H, d_h, max(cur_ctx) + T)
-        ws = torch.empty(max(nb, 4) // 4, dtype=torch.float32, device=DEV) if nb else None
+        ws = torch.zeros(max(nb, 4) // 4, dtype=torch.float32, device=DEV) if nb else None
         par_d, nn_d = _i32(trees), _i32([T] * B)
         tw.tree_verify_attn(q.to(DEV), kv, vv, ctx_d, max(cur_ctx), par_d, nn_d, scale, out, ws)
         n_acc = torch.zeros(B, dtype=torch.int32, device=DEV)
