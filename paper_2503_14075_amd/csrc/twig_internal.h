@@ -207,48 +207,70 @@ __device__ inline void finish_split_unit(const VerifyArgs& a, int b, int h, int 
     }
     __syncthreads();
     if (!s_last) return;
-    // d_h/4 lanes per node, four output columns each; the partials of four pieces are requested
-    // together, the merge itself is the online-softmax update, one piece at a time
-    constexpr int kBatch = 4;
+    // d_h/4 lanes per node, four output columns each.  A thread owns up to kItems such items and
+    // requests the partials of two pieces for all of them before it uses any (the merge is a few
+    // microseconds of memory latency: every round of dependent loads counts); the merge itself is
+    // the online-softmax update, one piece at a time, in piece order.
+    constexpr int kItems = 4, kBatch = 2;
     const int lanes = a.d_h / 4;
     const int64_t split_stride = (int64_t)a.B * a.H * a.T_max;
     const int64_t unit0 = ((int64_t)b * a.H + h) * a.T_max;
     const uint32_t o_bytes = (uint32_t)(a.T_max * a.d_h * 4), ml_bytes = (uint32_t)(a.T_max * 8);
-    for (int idx = tid; idx < T * lanes; idx += n_threads) {
-        const int t = idx / lanes, c4 = idx - t * lanes;
-        float m = -INFINITY, l = 0.f;
-        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    const int n_items = T * lanes;
+    for (int idx0 = tid; idx0 < n_items; idx0 += n_threads * kItems) {
+        float m[kItems], l[kItems];
+        float4 acc[kItems];
+#pragma unroll
+        for (int u = 0; u < kItems; ++u) {
+            m[u] = -INFINITY;
+            l[u] = 0.f;
+            acc[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+        }
         for (int s0 = 0; s0 < n_b; s0 += kBatch) {
-            float2 ml[kBatch];
-            float4 v[kBatch];
+            float2 ml[kBatch][kItems];
+            float4 v[kBatch][kItems];
 #pragma unroll
             for (int i = 0; i < kBatch; ++i) {
                 const int s = s0 + i < n_b ? s0 + i : n_b - 1;   // past the last piece: re-read it, unused
                 const int64_t slot = unit0 + s * split_stride;
-                ml[i] = __builtin_bit_cast(float2, __builtin_amdgcn_raw_buffer_load_b64(
-                                                       raw_buffer(a.part_ml + slot * 2, ml_bytes), t * 8, 0, kAuxThrough));
-                v[i] = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(
-                                                      raw_buffer(a.part_o + slot * a.d_h, o_bytes),
-                                                      (t * a.d_h + 4 * c4) * 4, 0, kAuxThrough));
+                const __amdgpu_buffer_rsrc_t rml = raw_buffer(a.part_ml + slot * 2, ml_bytes);
+                const __amdgpu_buffer_rsrc_t ro = raw_buffer(a.part_o + slot * a.d_h, o_bytes);
+#pragma unroll
+                for (int u = 0; u < kItems; ++u) {
+                    // items past the end fall outside the descriptors and read zeros
+                    const int idx = idx0 + u * n_threads, t = idx / lanes, c4 = idx - t * lanes;
+                    ml[i][u] = __builtin_bit_cast(float2, __builtin_amdgcn_raw_buffer_load_b64(rml, t * 8, 0, kAuxThrough));
+                    v[i][u] = __builtin_bit_cast(
+                        float4, __builtin_amdgcn_raw_buffer_load_b128(ro, (t * a.d_h + 4 * c4) * 4, 0, kAuxThrough));
+                }
             }
 #pragma unroll
             for (int i = 0; i < kBatch; ++i) {
-                // a piece in which this node saw no key carries max = -inf and is skipped
-                if (s0 + i < n_b && ml[i].x != -INFINITY) {
-                    const float m_new = fmaxf(m, ml[i].x);
-                    const float keep = expf(m - m_new), w = expf(ml[i].x - m_new);
-                    l = l * keep + ml[i].y * w;
-                    acc.x = acc.x * keep + v[i].x * w;
-                    acc.y = acc.y * keep + v[i].y * w;
-                    acc.z = acc.z * keep + v[i].z * w;
-                    acc.w = acc.w * keep + v[i].w * w;
-                    m = m_new;
+#pragma unroll
+                for (int u = 0; u < kItems; ++u) {
+                    // a piece in which this node saw no key carries max = -inf and is skipped
+                    if (s0 + i < n_b && ml[i][u].x != -INFINITY) {
+                        const float m_new = fmaxf(m[u], ml[i][u].x);
+                        const float keep = expf(m[u] - m_new), w = expf(ml[i][u].x - m_new);
+                        l[u] = l[u] * keep + ml[i][u].y * w;
+                        acc[u].x = acc[u].x * keep + v[i][u].x * w;
+                        acc[u].y = acc[u].y * keep + v[i][u].y * w;
+                        acc[u].z = acc[u].z * keep + v[i][u].z * w;
+                        acc[u].w = acc[u].w * keep + v[i][u].w * w;
+                        m[u] = m_new;
+                    }
                 }
             }
         }
-        const float inv = 1.f / l;
-        store_out4(a.out, a.out_bf16, ((((int64_t)b * a.T_max + t) * a.H + h) * a.d_h) + 4 * c4, acc.x * inv,
-                   acc.y * inv, acc.z * inv, acc.w * inv, false);
+#pragma unroll
+        for (int u = 0; u < kItems; ++u) {
+            const int idx = idx0 + u * n_threads, t = idx / lanes, c4 = idx - t * lanes;
+            if (idx < n_items) {
+                const float inv = 1.f / l[u];
+                store_out4(a.out, a.out_bf16, ((((int64_t)b * a.T_max + t) * a.H + h) * a.d_h) + 4 * c4, acc[u].x * inv,
+                           acc[u].y * inv, acc[u].z * inv, acc[u].w * inv, false);
+            }
+        }
     }
 }
 
