@@ -253,6 +253,25 @@ int32_t tw_tree_verify_attn_gqa(const void* q, const tw_kv_view* k, const tw_kv_
                                 void* stream);
 
 /*
+ * tw_tree_verify_attn for callers that cannot allocate device memory or hand over a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The same
+ * computation, arguments and errors as tw_tree_verify_attn, with the scratch of a split launch
+ * (arrival counters, partial results) in a device array of TW_STATIC_SCRATCH_BYTES that the
+ * library holds on every GPU it runs on until the process ends.  The call allocates nothing and
+ * frees nothing.  A launch that would need more scratch than that returns TW_ERR_WORKSPACE (ask
+ * tw_workspace_bytes; a launch with at least 256 (sequence, head) units needs none and always fits).
+ * All calls on one GPU share that GPU's array: two of them must not overlap in time (put them on
+ * one stream, or order them with events), or they race on it.  The counters in it are zero when
+ * the library is loaded and every launch returns them to zero as its last action, so calls of
+ * different shapes may follow each other freely.
+ */
+#define TW_STATIC_SCRATCH_BYTES (16u << 20)
+int32_t tw_tree_verify_attn_static(const void* q, const tw_kv_view* k, const tw_kv_view* v,
+                                   const int32_t* ctx_len, int32_t max_ctx_len, const int32_t* parent,
+                                   const int32_t* n_nodes, int32_t T_max, int32_t B, float scale,
+                                   void* out, int32_t out_dtype, void* stream);
+
+/*
  * Greedy acceptance walk with bonus token (Sec. 5.4, App. A, last steps of
  * Alg. 2; a chain is the sequence case of Alg. 1).  argmax[b][i] is the target
  * model's prediction for the token after node i.  A non-root node is matched

@@ -25,12 +25,13 @@ _lib = ctypes.CDLL(LIB_PATH)
 TW_OK, TW_ERR_INVALID_ARG, TW_ERR_UNSUPPORTED, TW_ERR_WORKSPACE, TW_ERR_LAUNCH = 0, -1, -2, -3, -4
 TW_F32, TW_BF16 = 0, 1
 TW_CALL_TTP_SCORE, TW_CALL_TREE_VERIFY_ATTN = 1, 2
+TW_STATIC_SCRATCH_BYTES = 16 << 20
 _STATUS = {0: "TW_OK", -1: "TW_ERR_INVALID_ARG", -2: "TW_ERR_UNSUPPORTED", -3: "TW_ERR_WORKSPACE",
            -4: "TW_ERR_LAUNCH"}
 
 EXPORTS = ["tw_version", "tw_workspace_bytes", "tw_ttp_score", "tw_ttp_score_gqa", "tw_ttp_score_phead", "tw_ttp_select", "tw_ttp_compact",
            "tw_ttp_compact_batched",
-           "tw_tree_ancestor_masks", "tw_tree_verify_attn", "tw_tree_verify_attn_gqa", "tw_tree_accept", "tw_kv_commit", "tw_draft_topk", "tw_draft_topk_logits",
+           "tw_tree_ancestor_masks", "tw_tree_verify_attn", "tw_tree_verify_attn_gqa", "tw_tree_verify_attn_static", "tw_tree_accept", "tw_kv_commit", "tw_draft_topk", "tw_draft_topk_logits",
            "tw_tree_build_workspace_bytes", "tw_tree_build", "tw_validate_tree",
            "tw_rbar"]
 
@@ -71,6 +72,9 @@ _lib.tw_tree_verify_attn.argtypes = [_vp, ctypes.POINTER(KvView), ctypes.POINTER
 _lib.tw_tree_verify_attn_gqa.restype = _i32
 _lib.tw_tree_verify_attn_gqa.argtypes = [_vp, ctypes.POINTER(KvView), ctypes.POINTER(KvView), _i32, _vp, _i32, _vp,
                                          _vp, _i32, _i32, _f32, _vp, _i32, _vp, _sz, _vp]
+_lib.tw_tree_verify_attn_static.restype = _i32
+_lib.tw_tree_verify_attn_static.argtypes = [_vp, ctypes.POINTER(KvView), ctypes.POINTER(KvView), _vp, _i32, _vp,
+                                            _vp, _i32, _i32, _f32, _vp, _i32, _vp]
 _lib.tw_tree_accept.restype = _i32
 _lib.tw_tree_accept.argtypes = [_vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp, _vp, _vp]
 _lib.tw_kv_commit.restype = _i32
@@ -204,6 +208,14 @@ def tree_verify_attn(q: torch.Tensor, k: KvView, v: KvView, ctx_len: torch.Tenso
         _ptr(q), ctypes.byref(k), ctypes.byref(v), _ptr(ctx_len), max_ctx_len, _ptr(parent),
         _ptr(n_nodes), T_max, B, scale, _ptr(out), _dtype_code(out), _ptr(ws),
         0 if ws is None else ws.numel() * ws.element_size(), _stream()))
+
+
+def tree_verify_attn_static(q: torch.Tensor, k: KvView, v: KvView, ctx_len: torch.Tensor, max_ctx_len: int,
+                            parent: torch.Tensor, n_nodes: torch.Tensor, scale: float, out: torch.Tensor) -> None:
+    B, T_max = q.shape[0], q.shape[1]
+    _check("tw_tree_verify_attn_static", _lib.tw_tree_verify_attn_static(
+        _ptr(q), ctypes.byref(k), ctypes.byref(v), _ptr(ctx_len), max_ctx_len, _ptr(parent),
+        _ptr(n_nodes), T_max, B, scale, _ptr(out), _dtype_code(out), _stream()))
 
 
 def tree_verify_attn_gqa(q: torch.Tensor, k: KvView, v: KvView, q_heads_per_kv: int, ctx_len: torch.Tensor,

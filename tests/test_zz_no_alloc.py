@@ -1,0 +1,71 @@
+"""tw_tree_verify_attn_static (the entry point that allocates nothing: its scratch is a device array
+inside the library) against tw_tree_verify_attn on the same inputs, through the C ABI, on two calls
+in a row -- the second with a smaller input, so that it meets the scratch as the first left it."""
+import math
+
+import pytest
+import torch
+
+from paper_2503_14075_amd import workloads as W
+
+DEV = "cuda:0"
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def tw():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2503_14075_amd import binding
+    return binding
+
+
+def _i32(x):
+    return torch.tensor(x, dtype=torch.int32, device=DEV)
+
+
+def _case(seed, B, H, d_h, ctx, T):
+    trees = [W.random_parent_tree(W.HostRng(seed, b), T, 6) for b in range(B)]
+    rows = [c + T for c in ctx]
+    off, acc = [], 0
+    for r in rows:
+        off.append(acc)
+        acc += r
+    q = W.normal(seed, 1, (B, T, H, d_h), 1.0 / math.sqrt(d_h), torch.bfloat16).to(DEV)
+    k = W.normal(seed, 2, (acc, H, d_h), 0.5, torch.bfloat16).to(DEV)
+    v = W.normal(seed, 3, (acc, H, d_h), 0.5, torch.bfloat16).to(DEV)
+    return q, k, v, _i32(off), _i32(ctx), _i32(trees), _i32([T] * B)
+
+
+def test_static_scratch_entry_point_matches_the_workspace_one(tw):
+    H, d_h = 32, 128
+    scale = 1 / math.sqrt(d_h)
+    # both launches cut their sequences into pieces (scratch in use); the first has sequences of one and of
+    # several pieces side by side, the second is smaller in every dimension
+    for seed, B, ctx, T in ((5, 3, [2600, 300, 1500], 40), (6, 1, [900], 26)):
+        q, k, v, off, ctx_d, par, n_nodes = _case(seed, B, H, d_h, ctx, T)
+        kv, vv = tw.kv_view(k, off), tw.kv_view(v, off)
+        nbytes = tw.workspace_bytes(tw.TW_CALL_TREE_VERIFY_ATTN, B, T, H, d_h, max(ctx) + T)
+        assert 0 < nbytes <= tw.TW_STATIC_SCRATCH_BYTES
+        ws = torch.zeros(nbytes // 4, dtype=torch.float32, device=DEV)
+        want = torch.full((B, T, H, d_h), float("nan"), dtype=torch.float32, device=DEV)
+        tw.tree_verify_attn(q, kv, vv, ctx_d, max(ctx), par, n_nodes, scale, want, ws)
+        got = torch.full_like(want, float("nan"))
+        tw.tree_verify_attn_static(q, kv, vv, ctx_d, max(ctx), par, n_nodes, scale, got)
+        torch.cuda.synchronize()
+        assert torch.isfinite(want).all()
+        # the same kernels on the same inputs with a fixed summation order: bit-identical
+        assert torch.equal(got, want)
+
+
+def test_static_scratch_rejects_what_does_not_fit(tw):
+    # 255 (sequence, head) units of 64 tree rows in two pieces each: 17 MB of partial results
+    B, H, d_h, T = 85, 3, 128, 64
+    ctx = [600] * B
+    assert tw.workspace_bytes(tw.TW_CALL_TREE_VERIFY_ATTN, B, T, H, d_h, ctx[0] + T) > tw.TW_STATIC_SCRATCH_BYTES
+    q, k, v, off, ctx_d, par, n_nodes = _case(7, B, H, d_h, ctx, T)
+    out = torch.zeros((B, T, H, d_h), dtype=torch.float32, device=DEV)
+    with pytest.raises(tw.TwigError) as e:
+        tw.tree_verify_attn_static(q, tw.kv_view(k, off), tw.kv_view(v, off), ctx_d, ctx[0], par, n_nodes,
+                                   1 / math.sqrt(d_h), out)
+    assert e.value.status == tw.TW_ERR_WORKSPACE
