@@ -110,11 +110,8 @@ size_t tw_workspace_bytes(int32_t which, int32_t B, int32_t rows, int32_t H, int
  *   scores  [dev] [B][M] fp32 out
  * Preconditions on device contents: 1 <= n_q[b] <= n_q_max,
  * q_pos0[b] + n_q[b] <= n_tot[b] <= n_tot_max, v_start + M <= n_tot[b].
- * Accuracy: fp32 accumulation throughout.  On the kernels that read the keys once
- * (bf16, d_h 64/128; at most 128 scoring rows and 768 keys with scale > 0, or at
- * most 32 scoring rows and more than 768 keys) an attention weight passes through
- * 16-bit fixed point (step 2^-16 of the row maximum's weight): a score is within
- * 2^-17 of the exact mean in the worst case and within 1e-6 once H * n_q[b] >= 256.
+ * Accuracy: logits are fp32 sums of exact bf16 (or fp32) products; exponentials, normalisers,
+ * weights and the sums over rows and heads are fp32.  A score is within 1e-6 of the exact mean.
  * The result does not depend on launch order (fixed summation order).
  * Errors: INVALID_ARG for null pointers, negative sizes, v_start + M > n_tot_max,
  * paged k view; UNSUPPORTED for d_h; WORKSPACE.

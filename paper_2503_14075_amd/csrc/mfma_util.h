@@ -25,12 +25,6 @@ __device__ __forceinline__ int acc_row(int r, int g) { return 8 * (r >> 2) + 4 *
 // v_exp_f32: 2^x at 1 ulp; results below 2^-126 flush to zero, which is what a softmax weight that small is worth
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-// Two weights in [0, 1] as 16-bit fixed point (v_cvt_pknorm_u16_f32, round to nearest): a stored
-// value v stands for v / 65535, absolute step 2^-16.
-__device__ __forceinline__ uint32_t pack_unorm16(float a, float b) {
-    return __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pknorm_u16(a, b));
-}
-
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 

@@ -4,21 +4,20 @@
 // The normaliser of a scoring row is known only after its last key, and a score is a sum over
 // rows, so the weights cannot be summed while the keys stream by.  Instead of reading the keys a
 // second time, the stream kernel leaves, per 32-key chunk of the visual span, the exponentials
-// exp2(logit - m) as 16-bit fixed point (m = the row's running maximum after that chunk, kept
-// beside them), 2 bytes per (row, key) against the 2 * d_h bytes of a key.  The weights kernel
-// then scales each chunk by exp2(m - final maximum) / final sum and adds the rows.
+// exp2(logit - m) in fp32 (m = the row's running maximum after that chunk, kept beside them),
+// 4 bytes per (row, key) against the 2 * d_h bytes of a key.  The weights kernel then scales
+// each chunk by exp2(m - final maximum) / final sum and adds the rows.
 //
 //   score_stream_kernel          grid (ceil(H / 4), B, key splits), one wavefront per head:
 //                                K chunk -> LDS -> K.Q^T on the matrix cores (a lane owns one
 //                                scoring row), online (max, sum), table rows out through an LDS
-//                                transpose as whole 64-byte lines; per-split (max, sum) per row.
-//   score_stream_weights_kernel  grid (ceil(span chunks / 16), H, B): merges the splits'
-//                                statistics in split order; a lane owns 8 keys of one chunk and
+//                                transpose as whole 128-byte lines; per-split (max, sum) per row.
+//   score_stream_weights_kernel  grid (ceil(span chunks / 8), H, B): merges the splits'
+//                                statistics in split order; a lane owns 4 keys of one chunk and
 //                                adds the table rows in row order.
 //   score_reduce_kernel          adds the heads in index order (shared with the other kernels).
 //
-// A stored exponential is off by at most 2^-17 of its chunk's reference, the same reach as the
-// kernel that keeps this table in shared memory for short prompts.
+// Every weight is fp32 from the logit to the column sum.
 #include "mfma_util.h"
 #include "twig_internal.h"
 
@@ -26,7 +25,7 @@ namespace tw {
 
 constexpr int kStThreads = 256;
 constexpr int kStChunk = 32;
-constexpr int kStTrStride = 72;   // bytes per row of the transpose area: 8-byte aligned, conflict-free
+constexpr int kStTrStride = 144;  // bytes per row of the transpose area (32 floats, padded): 16-byte aligned
 
 template <int DH>
 struct StCfg {
@@ -107,7 +106,7 @@ __global__ __launch_bounds__(kStThreads, 2) void score_stream_kernel(ScoreArgs a
     const int span_end = a.v_start + a.M, c_base = a.v_start / kStChunk * kStChunk;
     const int e_rows = stream_table_rows(a.n_q_max), max_chunks = stream_max_chunks(a.n_tot_max);
     const int64_t unit = (int64_t)b * a.H + h;
-    uint16_t* etab = a.etab + unit * max_chunks * e_rows * kStChunk;
+    float* etab = a.etab + unit * max_chunks * e_rows * kStChunk;
     float* rtab = a.rtab + unit * max_chunks * 32;
 
     float run_m = -INFINITY, run_l = 0.f;   // run_l: this lane group's share of the row sum
@@ -147,23 +146,23 @@ __global__ __launch_bounds__(kStThreads, 2) void score_stream_kernel(ScoreArgs a
         run_l = run_l * fast_exp2(run_m - m_safe) + psum;
         run_m = m_new;
         if (base + kStChunk > a.v_start && base < span_end) {
-            // rows x 32 keys of fixed point through the transpose area, out as 64-byte lines
+            // rows x 32 keys through the transpose area, out as 128-byte lines: registers 4q .. 4q+3 of
+            // lane (row li, group g) are the keys 8q + 4g .. + 3 of the chunk
             const int cid = (base - c_base) / kStChunk;
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                uint2 w2;
-                w2.x = pack_unorm16(e[4 * q], e[4 * q + 1]);
-                w2.y = pack_unorm16(e[4 * q + 2], e[4 * q + 3]);
-                *(uint2*)(s_tr + li * kStTrStride + (8 * q + 4 * g) * 2) = w2;
-            }
+            for (int q = 0; q < 4; ++q)
+                *(float4*)(s_tr + li * kStTrStride + (8 * q + 4 * g) * 4) =
+                    make_float4(e[4 * q], e[4 * q + 1], e[4 * q + 2], e[4 * q + 3]);
             lds_sync();
             const int row = lane >> 1, half = lane & 1;
-            const uint2* src = (const uint2*)(s_tr + row * kStTrStride + half * 32);
-            const uint2 p0 = src[0], p1 = src[1], p2 = src[2], p3 = src[3];
+            const f32x4* src = (const f32x4*)(s_tr + row * kStTrStride + half * 64);
+            const f32x4 p0 = src[0], p1 = src[1], p2 = src[2], p3 = src[3];
             if (row < e_rows) {
-                u32x4* dst = (u32x4*)(etab + ((int64_t)cid * e_rows + row) * kStChunk + half * 16);
-                __builtin_nontemporal_store((u32x4){p0.x, p0.y, p1.x, p1.y}, dst);
-                __builtin_nontemporal_store((u32x4){p2.x, p2.y, p3.x, p3.y}, dst + 1);
+                f32x4* dst = (f32x4*)(etab + ((int64_t)cid * e_rows + row) * kStChunk + half * 16);
+                __builtin_nontemporal_store(p0, dst);
+                __builtin_nontemporal_store(p1, dst + 1);
+                __builtin_nontemporal_store(p2, dst + 2);
+                __builtin_nontemporal_store(p3, dst + 3);
             }
             if (g == 0) rtab[cid * 32 + li] = m_safe;
         }
@@ -173,8 +172,8 @@ __global__ __launch_bounds__(kStThreads, 2) void score_stream_kernel(ScoreArgs a
     if (g == 0) ((float2*)a.stats)[(unit * a.n_splits + split) * 32 + li] = make_float2(run_m, l);
 }
 
-// grid (ceil(span chunks / 16), H, B), one wavefront per workgroup.  A lane owns 8 consecutive keys
-// of one chunk: chunk 16 * blockIdx.x + lane / 4, keys 8 * (lane % 4) .. + 7, and walks the table
+// grid (ceil(span chunks / 8), H, B), one wavefront per workgroup.  A lane owns 4 consecutive keys
+// of one chunk: chunk 8 * blockIdx.x + lane / 8, keys 4 * (lane % 8) .. + 3, and walks the table
 // rows of that chunk with one 16-byte load per row, adding them in row order.
 // ER = table rows per chunk.  The table and reference loads are requested before the statistics
 // are merged, so the kernel is three memory latencies long, not five.
@@ -193,23 +192,23 @@ __global__ __launch_bounds__(64) void score_stream_weights_kernel(ScoreArgs a) {
     constexpr int e_rows = ER;
     const int max_chunks = stream_max_chunks(a.n_tot_max);
     const int64_t unit = (int64_t)b * a.H + h;
-    const uint16_t* etab = a.etab + unit * max_chunks * e_rows * kStChunk;
+    const float* etab = a.etab + unit * max_chunks * e_rows * kStChunk;
     const float* rtab = a.rtab + unit * max_chunks * 32;
     float* partial = a.ws + unit * a.M;
 
-    const int cid = 16 * blockIdx.x + (lane >> 2), kq = lane & 3;
+    const int cid = 8 * blockIdx.x + (lane >> 3), kq = lane & 7;
     const int base = c_base + cid * kStChunk;
     const bool in_span = cid < span_chunks;
     const bool valid = in_span && base < n_tot;   // the stream kernel has written this chunk
 
     const int cc = valid ? cid : 0;   // lanes without a chunk read chunk 0 of the unit and drop it
-    const u32x4* blk = (const u32x4*)(etab + (int64_t)cc * e_rows * kStChunk + 8 * kq);
+    const f32x4* blk = (const f32x4*)(etab + (int64_t)cc * e_rows * kStChunk + 4 * kq);
     const float* ref = rtab + cc * 32;
-    u32x4 w[ER];
+    f32x4 w[ER];
     float rf[ER];
 #pragma unroll
     for (int r = 0; r < ER; ++r) {
-        w[r] = blk[r * (kStChunk * 2 / 16)];
+        w[r] = blk[r * (kStChunk / 4)];
         rf[r] = ref[r];
     }
 
@@ -231,30 +230,26 @@ __global__ __launch_bounds__(64) void score_stream_weights_kernel(ScoreArgs a) {
                 m = m_new;
             }
         }
-        // log2(65535) undoes the fixed-point scale of the stored exponentials
-        if (jj < n_q && l > 0.f) msum = m + log2f(l) + 15.99997798f;
+        if (jj < n_q && l > 0.f) msum = m + log2f(l);
     }
     if (lane < 32) s_msum[jj] = msum;
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
-    float acc[8];
-#pragma unroll
-    for (int k = 0; k < 8; ++k) acc[k] = 0.f;
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int r = 0; r < ER; ++r) {
         const float f = valid ? fast_exp2(rf[r] - s_msum[r]) : 0.f;
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            acc[2 * k] = fmaf((float)(w[r][k] & 0xFFFFu), f, acc[2 * k]);
-            acc[2 * k + 1] = fmaf((float)(w[r][k] >> 16), f, acc[2 * k + 1]);
-        }
+        acc.x = fmaf(w[r].x, f, acc.x);
+        acc.y = fmaf(w[r].y, f, acc.y);
+        acc.z = fmaf(w[r].z, f, acc.z);
+        acc.w = fmaf(w[r].w, f, acc.w);
     }
     if (in_span) {
 #pragma unroll
-        for (int k = 0; k < 8; ++k) {
-            const int j = base + 8 * kq + k;
+        for (int k = 0; k < 4; ++k) {
+            const int j = base + 4 * kq + k;
             if (j >= a.v_start && j < span_end) partial[j - a.v_start] = j < n_tot ? acc[k] : 0.f;
         }
     }
@@ -267,14 +262,14 @@ bool score_stream_supported(const ScoreArgs& a, int dtype) {
 size_t score_stream_workspace_floats(int B, int H, int n_q_max, int n_tot_max) {
     const size_t units = (size_t)B * H, chunks = (size_t)stream_max_chunks(n_tot_max);
     const size_t rtab = units * chunks * 32;
-    const size_t etab = units * chunks * stream_table_rows(n_q_max) * kStChunk / 2;   // 16-bit entries
+    const size_t etab = units * chunks * stream_table_rows(n_q_max) * kStChunk;
     return rtab + etab;
 }
 
 hipError_t launch_score_stream(const ScoreArgs& a0, float* tables, hipStream_t s) {
     ScoreArgs a = a0;
     a.rtab = tables;
-    a.etab = (uint16_t*)(tables + (size_t)a.B * a.H * stream_max_chunks(a.n_tot_max) * 32);
+    a.etab = tables + (size_t)a.B * a.H * stream_max_chunks(a.n_tot_max) * 32;
     const dim3 grid((a.H + 3) / 4, a.B, a.n_splits);
     if (a.d_h == 128)
         hipLaunchKernelGGL(score_stream_kernel<128>, grid, dim3(kStThreads), 4 * (size_t)StCfg<128>::kWaveLds, s, a);
@@ -284,7 +279,7 @@ hipError_t launch_score_stream(const ScoreArgs& a0, float* tables, hipStream_t s
     if (e != hipSuccess) return e;
     const int c_base = a.v_start / kStChunk * kStChunk;
     const int span_chunks = (a.v_start + a.M - c_base + kStChunk - 1) / kStChunk;
-    const dim3 wgrid((span_chunks + 15) / 16, a.H, a.B);
+    const dim3 wgrid((span_chunks + 7) / 8, a.H, a.B);
     switch (stream_table_rows(a.n_q_max)) {
         case 8: hipLaunchKernelGGL(score_stream_weights_kernel<8>, wgrid, dim3(64), 0, s, a); break;
         case 16: hipLaunchKernelGGL(score_stream_weights_kernel<16>, wgrid, dim3(64), 0, s, a); break;

@@ -285,7 +285,7 @@ struct ScoreArgs {
     float* ws;
     float* stats = nullptr;    // per-split row statistics, inside ws (set by the launcher)
     float* rtab = nullptr;     // long-prompt kernel: per-chunk reference maxima, inside ws
-    uint16_t* etab = nullptr;  // long-prompt kernel: per-chunk exponentials, inside ws
+    float* etab = nullptr;     // long-prompt kernel: per-chunk exponentials, inside ws
     int32_t n_splits = 1;
     // Scoring rows taken in two launches (rows 0..63, then the rest) by the shared-memory one-pass
     // kernel: a launch covers rows row0 .. row0 + n_q_max - 1 of the q_stride rows that q_sel holds

@@ -20,15 +20,6 @@ SCORE_TOL = 1e-6
 DEV = "cuda:0"
 
 
-def score_tol(H, n_q):
-    """Bar for one sequence's scores.  The one-pass kernel keeps an attention weight's exponential as
-    16-bit fixed point: a weight is off by at most 2^-17 (uniform, standard deviation 2^-17/sqrt(3) =
-    4.4e-6, times a factor <= 1/row sum <= 1).  A score is the mean of H*n_q weights, so its error has
-    standard deviation <= 4.4e-6/sqrt(H*n_q); 3.6 of those cover the maximum over a few hundred keys.
-    From 256 rows on (the paper's shapes have 32 heads x 64 rows) the bar is the flat 1e-6."""
-    return max(SCORE_TOL, 1.6e-5 / math.sqrt(H * n_q))
-
-
 @pytest.fixture(scope="module")
 def tw():
     from paper_2503_14075_amd import binding
@@ -653,7 +644,7 @@ def test_violated_device_preconditions_stay_in_bounds(tw):
     tw.ttp_score(qs.to(DEV), tw.kv_view(kd, row_off=ro), _i32([0, 1000, 9]),
                  _i32([big, neg, pos0[2]]), _i32([-1, 10 ** 9, n_tot[2]]), max(n_tot), v0, M, scale, True, sc, ws)
     torch.cuda.synchronize()
-    assert float((sc[2].cpu().double() - want_s[2]).abs().max()) <= score_tol(H, 9)
+    assert float((sc[2].cpu().double() - want_s[2]).abs().max()) <= SCORE_TOL
 
     # compaction: kept indices and lengths from nowhere (the row offsets are the caller's own)
     R = 5
@@ -755,7 +746,7 @@ def test_pools_larger_than_4_gib(tw):
         torch.cuda.synchronize()
         for b in range(2):
             err = float((scores[b].cpu().double() - want_s[b]).abs().max())
-            assert err <= score_tol(H, n_q[b]), f"score error {err:.3e}"
+            assert err <= SCORE_TOL, f"score error {err:.3e}"
 
     # P-Head form: keys from one pool, their gates from the other
     qp = W.normal(64, 1, (2, H, d_h), 1.0, torch.bfloat16)
@@ -827,17 +818,10 @@ def _check_score(tw, dtype, H, d_h, M, v0, n_text, n_q, causal, q_std=1.0, seed=
     torch.cuda.synchronize()
     got = scores.cpu().double()
     assert torch.isfinite(got).all()
-    # the documented reach of the one-pass kernel (16-bit stored exponentials); the other kernels
-    # keep fp32 throughout and are held to the flat bar
-    span_chunks = (v0 + M - 1) // 32 - v0 // 32 + 1
-    one_pass = (dtype == torch.bfloat16 and d_h in (64, 128) and n_q_max <= 128 and max(n_tot) <= 768
-                and span_chunks <= (23 if n_q_max > 32 else 24) and scale > 0)
-    # long prompts with at most 32 scoring rows: the same 16-bit table, kept in global memory
-    one_pass = one_pass or (dtype == torch.bfloat16 and d_h in (64, 128) and n_q_max <= 32 and max(n_tot) > 768)
+    # one bar for every shape and every kernel behind the call (fp32 weights throughout)
     for b in range(B):
         err = float((got[b] - want[b]).abs().max())
-        tol = score_tol(H, n_q[b]) if one_pass else SCORE_TOL
-        assert err <= tol, f"score error {err:.3e} in sequence {b} (bar {tol:.1e})"
+        assert err <= SCORE_TOL, f"score error {err:.3e} in sequence {b}"
     again = torch.empty_like(scores)
     run(again)
     torch.cuda.synchronize()
@@ -1022,7 +1006,7 @@ def test_draft_topk_logits(tw, V, E):
 
 
 @pytest.mark.parametrize("E,K", [(10, 10), (20, 20), (40, 30)])
-def test_tree_build_bit_exact_and_feeds_verification(tw, E, K):
+def test_tree_build_against_fp64_confidences_and_feeds_verification(tw, E, K):
     # E = K = 10 are the paper's defaults (310 candidates); 1220 and 3640 candidates take the wider
     # one-launch kernel and the three-launch path
     B, D, T_max = 7, 4, 61                        # N_max = 60 candidates + root
@@ -1060,11 +1044,33 @@ def test_tree_build_bit_exact_and_feeds_verification(tw, E, K):
     ws = torch.empty(tw.tree_build_workspace_bytes(B, N, T_max) // 4 + 1, dtype=torch.float32, device=DEV)
     tw.tree_build(cp, ct, pb, n_cand, root, T_max, po, to, so, nn, ws)
     torch.cuda.synchronize()
+    n_exact = 0
     for b, (par, tok, prob) in enumerate(cands):
         n, wp, wt, wsrc = oracle.tree_build(par, tok, prob, 100 + b, T_max)
         assert int(nn[b]) == n
-        assert torch.equal(po[b].cpu(), wp) and torch.equal(to[b].cpu(), wt) and torch.equal(so[b].cpu(), wsrc)
-        assert tw.validate_tree(po[b].cpu()[:n].tolist()) == tw.TW_OK
+        gp, gt, gs = po[b].cpu().tolist(), to[b].cpu().tolist(), so[b].cpu().tolist()
+        kept = gs[1:n]
+        # (1) which candidates are kept.  The oracle ranks the fp64 products, the kernel its own fp32
+        # products: the two sets may differ only in candidates whose confidence is within the fp32
+        # rounding of a product of up to D factors (1e-6 relative) of the last kept one.
+        conf = oracle.tree_confidence(par, prob)
+        diff = set(kept) ^ set(wsrc[1:n].tolist())
+        if diff:
+            thr = float(torch.sort(conf, descending=True).values[n - 2])
+            assert all(abs(float(conf[c]) - thr) <= 1e-6 * thr for c in diff), (b, sorted(diff))
+        else:
+            n_exact += 1
+        # (2) the emitted tree is exactly the tree of that kept set: root first, kept candidates in
+        # ascending candidate index, parents renumbered, every parent kept, unused slots as documented
+        assert kept == sorted(kept) and len(set(kept)) == n - 1
+        node_of = {c: 1 + r for r, c in enumerate(kept)}
+        assert gp[0] == -1 and gt[0] == 100 + b and gs[0] == -1
+        for r, c in enumerate(kept):
+            assert par[c] < 0 or par[c] in node_of
+            assert gp[1 + r] == (0 if par[c] < 0 else node_of[par[c]]) and gt[1 + r] == tok[c]
+        assert gp[n:] == [0] * (T_max - n) and gt[n:] == [0] * (T_max - n) and gs[n:] == [-1] * (T_max - n)
+        assert tw.validate_tree(gp[:n]) == tw.TW_OK
+    assert n_exact >= B - 1      # a disagreement at the threshold is the exception
     # the emitted parent[] goes straight into the verification attention
     H, d_h = 4, 128
     ctx = [20 + 3 * b for b in range(B)]
@@ -1077,7 +1083,7 @@ def test_tree_build_bit_exact_and_feeds_verification(tw, E, K):
 # ----------------------------------------------------------------------------
 # the five configurations, whole path
 # ----------------------------------------------------------------------------
-def _path_parity(runner, cfg, verify_instances=None, check_compact_tensors=None):
+def _path_parity(runner, cfg):
     w = W.make_workload(cfg)
     dw = runner.DeviceWorkload(w, DEV)
     dw.step()
@@ -1100,15 +1106,14 @@ def _path_parity(runner, cfg, verify_instances=None, check_compact_tensors=None)
             thr = torch.sort(want_sc[b], descending=True).values[R - 1]
             assert all(abs(float(want_sc[b, m] - thr)) <= 2 * SCORE_TOL for m in diff)
     # S3 compact: bit-exact given the kept indices the GPU selected
-    idx = range(len(w.compact_src)) if check_compact_tensors is None else check_compact_tensors
-    for t in idx:
+    for t in range(len(w.compact_src)):
         got_dst = dw.compact_dst[t].cpu()
         for b in range(B):
             s0, d0, n_keep = w.score_row_off[b], w.compact_dst_off[b], R + w.n_text[b]
             want = oracle.ttp_compact(got_kept[b], 0, M, w.compact_src[t][s0:s0 + w.n_tot[b]])
             assert torch.equal(got_dst[d0:d0 + n_keep].view(torch.int16), want.view(torch.int16)), (b, t)
-    # S5 verify on all or on sampled instances
-    insts = list(range(dw.n_inst)) if verify_instances is None else verify_instances
+    # S5 verify, every instance
+    insts = list(range(dw.n_inst))
     sub = lambda xs: [xs[i] for i in insts]
     want = oracle.tree_verify_attn(
         w.q_tree[insts].contiguous(), w.k_pool, w.v_pool, sub(w.ctx_len), sub(w.n_nodes), sub(w.parent),
@@ -1135,8 +1140,9 @@ def test_cfg1_llava_shape_single_layer(runner):
 
 @pytest.mark.parametrize("name", ["cfg2_p0", "cfg2_p256", "cfg2_p1024"])
 def test_cfg2_all_layers(runner, name):
-    # 32 independent layer caches in one launch; the oracle checks first, middle and last layers
-    _path_parity(runner, W.CONFIGS[name], verify_instances=[0, 13, 31], check_compact_tensors=[0, 1, 30, 60])
+    # 32 independent layer caches in one launch: every instance and every one of the 61 gathered
+    # tensors is compared with the oracle
+    _path_parity(runner, W.CONFIGS[name])
 
 
 def test_cfg3_ragged_paged_batch(runner):
@@ -1144,7 +1150,7 @@ def test_cfg3_ragged_paged_batch(runner):
 
 
 def test_cfg4_high_resolution(runner):
-    _path_parity(runner, W.CONFIGS["cfg4"], verify_instances=[0, 3])
+    _path_parity(runner, W.CONFIGS["cfg4"])
 
 
 def test_bench_launch_configuration_sampled(runner):
