@@ -237,6 +237,28 @@ def draft_topk_logits(logits: torch.Tensor, E: int):
     return ids, probs
 
 
+def draft_tree(logits: torch.Tensor, E: int, K: int, D: int):
+    """The level-wise drafting loop on a logits table [1 + N][V] (row 0: after the root, row 1 + c: after
+    candidate c).  Returns (parent [n] int32, token [n] int32, prob [n] fp64, conf [n] fp64,
+    expanded [D-1][K] int32, margin [D-1] fp64)."""
+    assert logits.dtype == torch.float32 and logits.dim() == 2
+    N = E + (D - 1) * K * E
+    V = logits.shape[1]
+    if logits.shape[0] != 1 + N or E > V:
+        raise ValueError(f"oracle draft_tree: logits must be [1 + {N}][V >= E], got {tuple(logits.shape)}")
+    par = torch.empty(N, dtype=torch.int32)
+    tok = torch.empty(N, dtype=torch.int32)
+    prob = torch.empty(N, dtype=torch.float64)
+    conf = torch.empty(N, dtype=torch.float64)
+    exp = torch.full((max(D - 1, 1), K), -1, dtype=torch.int32)
+    margin = torch.ones(max(D - 1, 1), dtype=torch.float64)
+    n = lib().orc_draft_tree(_p(logits.contiguous()), V, int(E), int(K), int(D), _p(par), _p(tok), _p(prob), _p(conf),
+                             _p(exp), _p(margin))
+    if n < 0:
+        raise ValueError(f"oracle draft_tree: invalid argument (code {n})")
+    return par[:n], tok[:n], prob[:n], conf[:n], exp[:D - 1], margin[:D - 1]
+
+
 def tree_confidence(cand_parent: Sequence[int], cand_prob: Sequence[float]) -> torch.Tensor:
     """fp64 confidence (product of draft probabilities along the path) of every candidate."""
     cp = _i32(cand_parent)

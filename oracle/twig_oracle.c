@@ -440,6 +440,87 @@ int orc_draft_topk_logits(const float* logits, int n, int V, int E, int32_t* ids
     return 0;
 }
 
+typedef struct { double s; int32_t m; } orc_pair_d;
+
+static int pair_d_cmp(const void* a, const void* b) {
+    const orc_pair_d* x = (const orc_pair_d*)a;
+    const orc_pair_d* y = (const orc_pair_d*)b;
+    if (x->s > y->s) return -1;
+    if (x->s < y->s) return 1;
+    return (x->m > y->m) - (x->m < y->m);
+}
+
+/*
+ * The level-wise drafting loop of tree-based self-speculative decoding (Sec. 5.4 / App. A) on given
+ * logits: level 1 holds the E most probable tokens after the root; every later level, up to D,
+ * expands the K most confident nodes of the level before it (confidence = product of the draft
+ * probabilities along the path, fp64; ties toward the lower candidate index; all of them when
+ * the level has fewer than K) by their E most probable tokens, the expanded nodes taken in ascending
+ * candidate index.  logits is [1 + N][V] fp32 with N = E + (D - 1) * K * E: row 0 holds the logits
+ * after the root, row 1 + c those after candidate c (only the rows of expanded nodes are read: they
+ * stand for the draft model's forward passes).  Candidates come out in generation order:
+ * cand_parent (-1 under the root), cand_token, cand_prob and cand_conf [N]; expanded [(D - 1) * K]
+ * lists the nodes expanded at levels 2..D (-1 for unused slots); margin [D - 1] is the relative gap
+ * between the least confident expanded node and the most confident node left out (1 when none is
+ * left out), which tells a test how far a selection is from a tie.  Composes orc_draft_topk_logits.
+ * Returns the number of candidates, -1 on invalid arguments, -3 when out of memory.
+ */
+int orc_draft_topk_logits(const float* logits, int n, int V, int E, int32_t* ids, double* probs);
+
+int orc_draft_tree(const float* logits, int V, int E, int K, int D, int32_t* cand_parent, int32_t* cand_token,
+                   double* cand_prob, double* cand_conf, int32_t* expanded, double* margin) {
+    if (V < 1 || E < 1 || E > V || K < 1 || D < 1 || !logits || !cand_parent || !cand_token || !cand_prob || !cand_conf)
+        return -1;
+    if (D > 1 && (!expanded || !margin)) return -1;
+    int32_t* ids = (int32_t*)malloc(sizeof(int32_t) * (size_t)E);
+    double* pr = (double*)malloc(sizeof(double) * (size_t)E);
+    orc_pair_d* order = (orc_pair_d*)malloc(sizeof(orc_pair_d) * (size_t)(K * E > E ? K * E : E));
+    int32_t* chosen = (int32_t*)malloc(sizeof(int32_t) * (size_t)K);
+    if (!ids || !pr || !order || !chosen) return -3;
+    for (int i = 0; i < (D - 1) * K; ++i) expanded[i] = -1;
+    /* level 1: the root's E most probable tokens */
+    orc_draft_topk_logits(logits, 1, V, E, ids, pr);
+    for (int e = 0; e < E; ++e) {
+        cand_parent[e] = -1;
+        cand_token[e] = ids[e];
+        cand_prob[e] = pr[e];
+        cand_conf[e] = pr[e];
+    }
+    int prev_off = 0, prev_n = E, n = E;
+    for (int level = 2; level <= D; ++level) {
+        /* the K most confident nodes of the previous level, then in ascending candidate index */
+        for (int i = 0; i < prev_n; ++i) {
+            order[i].s = cand_conf[prev_off + i];
+            order[i].m = prev_off + i;
+        }
+        qsort(order, (size_t)prev_n, sizeof(orc_pair_d), pair_d_cmp);
+        const int k = prev_n < K ? prev_n : K;
+        margin[level - 2] = k < prev_n ? (order[k - 1].s - order[k].s) / order[k - 1].s : 1.0;
+        for (int j = 0; j < k; ++j) chosen[j] = order[j].m;
+        qsort(chosen, (size_t)k, sizeof(int32_t), int_cmp);
+        const int out_off = n;
+        for (int j = 0; j < k; ++j) {
+            const int u = chosen[j];
+            expanded[(level - 2) * K + j] = u;
+            orc_draft_topk_logits(logits + (size_t)(1 + u) * V, 1, V, E, ids, pr);
+            for (int e = 0; e < E; ++e) {
+                cand_parent[n] = u;
+                cand_token[n] = ids[e];
+                cand_prob[n] = pr[e];
+                cand_conf[n] = cand_conf[u] * pr[e];
+                ++n;
+            }
+        }
+        prev_off = out_off;
+        prev_n = k * E;
+    }
+    free(ids);
+    free(pr);
+    free(order);
+    free(chosen);
+    return n;
+}
+
 /*
  * Confidence of drafted candidates (App. A): the product of the draft
  * probabilities along the path from the root to the candidate, in fp64.  A
@@ -454,16 +535,6 @@ int orc_tree_confidence(const int32_t* cand_parent, const float* cand_prob, int 
         conf[i] = (cand_parent[i] < 0 ? 1.0 : conf[cand_parent[i]]) * (double)cand_prob[i];
     }
     return 0;
-}
-
-typedef struct { double s; int32_t m; } orc_pair_d;
-
-static int pair_d_cmp(const void* a, const void* b) {
-    const orc_pair_d* x = (const orc_pair_d*)a;
-    const orc_pair_d* y = (const orc_pair_d*)b;
-    if (x->s > y->s) return -1;
-    if (x->s < y->s) return 1;
-    return (x->m > y->m) - (x->m < y->m);
 }
 
 /*

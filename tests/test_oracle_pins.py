@@ -723,3 +723,62 @@ def test_tree_build_special_cases():
     assert n == 1 and p.tolist() == [-1, 0, 0, 0] and int(t[0]) == 77
     with pytest.raises(ValueError):
         oracle.tree_build([-1, 1], [1, 2], [0.5, 0.5], 0, 4)          # parent not before child
+
+
+# ----------------------------------------------------------------------------
+# level-wise drafting loop (App. A, tree-based SSD)
+# ----------------------------------------------------------------------------
+def _draft_tree_brute(logits, E, K, D):
+    """The same loop from its definition with library routines: fp64 softmax, full sorts."""
+    sm = torch.softmax(logits.double(), dim=1)
+    top = lambda row: sorted(range(logits.shape[1]), key=lambda t: (-float(logits[row, t]), t))[:E]
+    par, tok, prob, conf = [], [], [], []
+    for t in top(0):
+        par.append(-1), tok.append(t), prob.append(float(sm[0, t])), conf.append(float(sm[0, t]))
+    prev, expanded = list(range(E)), []
+    for _ in range(2, D + 1):
+        chosen = sorted(sorted(prev, key=lambda c: (-conf[c], c))[:K])
+        expanded.append(chosen)
+        cur = []
+        for u in chosen:
+            for t in top(1 + u):
+                par.append(u), tok.append(t), prob.append(float(sm[1 + u, t])), conf.append(conf[u] * float(sm[1 + u, t]))
+                cur.append(len(par) - 1)
+        prev = cur
+    return par, tok, prob, conf, expanded
+
+
+@pytest.mark.parametrize("E,K,D,V", [(3, 2, 3, 50), (4, 4, 2, 37), (2, 5, 4, 16), (5, 1, 1, 9)])
+def test_draft_tree_against_its_definition(E, K, D, V):
+    N = E + (D - 1) * K * E
+    g = torch.Generator().manual_seed(100 * E + 10 * K + D)
+    logits = torch.randn(1 + N, V, generator=g) * 2.0
+    par, tok, prob, conf, exp, margin = oracle.draft_tree(logits, E, K, D)
+    bp, bt, bpr, bc, bexp = _draft_tree_brute(logits, E, K, D)
+    assert par.tolist() == bp and tok.tolist() == bt
+    assert np.allclose(prob.numpy(), bpr, rtol=1e-12, atol=0) and np.allclose(conf.numpy(), bc, rtol=1e-12, atol=0)
+    for lvl, chosen in enumerate(bexp):
+        assert [c for c in exp[lvl].tolist() if c >= 0] == chosen
+    # structure: parents precede children, level sizes, confidence = product along the path
+    assert all(p < c for c, p in enumerate(par.tolist()))
+    want_conf = oracle.tree_confidence(par.tolist(), prob.float().tolist())
+    assert np.allclose(conf.numpy(), want_conf.numpy(), rtol=1e-6)
+    assert (margin >= 0).all() and (margin <= 1).all()
+
+
+def test_draft_tree_by_hand():
+    # V = 4, E = 2, K = 1, D = 2 with probabilities chosen through their logarithms:
+    # root: p = (0.5, 0.3, 0.15, 0.05) -> candidates 0 (token 0, 0.5), 1 (token 1, 0.3); the more
+    # confident one (candidate 0) is expanded with p = (0.1, 0.2, 0.3, 0.4) -> tokens 3 (0.4), 2 (0.3)
+    lg = torch.log(torch.tensor([[0.5, 0.3, 0.15, 0.05],
+                                 [0.1, 0.2, 0.3, 0.4],     # after candidate 0
+                                 [0.7, 0.1, 0.1, 0.1],     # after candidate 1: never read
+                                 [0.25, 0.25, 0.25, 0.25],
+                                 [0.25, 0.25, 0.25, 0.25]])).float()
+    par, tok, prob, conf, exp, margin = oracle.draft_tree(lg, 2, 1, 2)
+    assert par.tolist() == [-1, -1, 0, 0] and tok.tolist() == [0, 1, 3, 2]
+    assert np.allclose(prob.numpy(), [0.5, 0.3, 0.4, 0.3], rtol=1e-6)
+    assert np.allclose(conf.numpy(), [0.5, 0.3, 0.2, 0.15], rtol=1e-6)
+    assert exp.tolist() == [[0]] and abs(float(margin[0]) - 0.4) < 1e-6      # (0.5 - 0.3) / 0.5
+    with pytest.raises(ValueError):
+        oracle.draft_tree(lg[:, :1].contiguous(), 2, 1, 2)      # E > V
