@@ -41,6 +41,13 @@
 extern "C" {
 #endif
 
+/* The library is built with hidden visibility; these are its only exported symbols. */
+#if defined(__GNUC__) || defined(__clang__)
+#define TW_API __attribute__((visibility("default")))
+#else
+#define TW_API
+#endif
+
 typedef enum {
     TW_OK = 0,
     TW_ERR_INVALID_ARG = -1, /* null pointer, negative size, R > M, span outside the sequence ... */
@@ -75,7 +82,7 @@ typedef struct tw_kv_view {
 } tw_kv_view;
 
 /* Library version, 1000*major + minor (2.0: the verification workspace carries counters that start at zero). */
-int32_t tw_version(void);
+TW_API int32_t tw_version(void);
 
 /*
  * Scratch bytes needed by a call.  `which` is a tw_call.  For
@@ -92,7 +99,7 @@ int32_t tw_version(void);
  * calls of any shape.  With counters that are not zero the output is unspecified (still memory-
  * safe, and no kernel waits for another).  After TW_ERR_LAUNCH zero it again.
  */
-size_t tw_workspace_bytes(int32_t which, int32_t B, int32_t rows, int32_t H, int32_t d_h,
+TW_API size_t tw_workspace_bytes(int32_t which, int32_t B, int32_t rows, int32_t H, int32_t d_h,
                           int32_t max_rows);
 
 /*
@@ -116,7 +123,7 @@ size_t tw_workspace_bytes(int32_t which, int32_t B, int32_t rows, int32_t H, int
  * Errors: INVALID_ARG for null pointers, negative sizes, v_start + M > n_tot_max,
  * paged k view; UNSUPPORTED for d_h; WORKSPACE.
  */
-int32_t tw_ttp_score(const void* q_sel, int32_t n_q_max, const int32_t* n_q, const int32_t* q_pos0,
+TW_API int32_t tw_ttp_score(const void* q_sel, int32_t n_q_max, const int32_t* n_q, const int32_t* q_pos0,
                      const tw_kv_view* k, const int32_t* n_tot, int32_t n_tot_max, int32_t B,
                      int32_t v_start, int32_t M, float scale, int32_t causal, float* scores,
                      void* ws, size_t ws_bytes, void* stream);
@@ -130,7 +137,7 @@ int32_t tw_ttp_score(const void* q_sel, int32_t n_q_max, const int32_t* n_q, con
  * Errors as tw_ttp_score, plus INVALID_ARG (q_heads_per_kv < 1) and UNSUPPORTED
  * (q_heads_per_kv > 64, H_q > 65535).
  */
-int32_t tw_ttp_score_gqa(const void* q_sel, int32_t n_q_max, const int32_t* n_q, const int32_t* q_pos0,
+TW_API int32_t tw_ttp_score_gqa(const void* q_sel, int32_t n_q_max, const int32_t* n_q, const int32_t* q_pos0,
                          const tw_kv_view* k, int32_t q_heads_per_kv, const int32_t* n_tot, int32_t n_tot_max,
                          int32_t B, int32_t v_start, int32_t M, float scale, int32_t causal, float* scores,
                          void* ws, size_t ws_bytes, void* stream);
@@ -149,7 +156,7 @@ int32_t tw_ttp_score_gqa(const void* q_sel, int32_t n_q_max, const int32_t* n_q,
  * Errors: INVALID_ARG (null pointers, paged views, span outside the pools),
  * UNSUPPORTED (d_h, view mismatch, M > 32768), WORKSPACE.
  */
-int32_t tw_ttp_score_phead(const void* q, const void* gq, const tw_kv_view* k, const tw_kv_view* gk,
+TW_API int32_t tw_ttp_score_phead(const void* q, const void* gq, const tw_kv_view* k, const tw_kv_view* gk,
                            int32_t B, int32_t v_start, int32_t M, float scale, float* scores, void* ws,
                            size_t ws_bytes, void* stream);
 
@@ -161,7 +168,7 @@ int32_t tw_ttp_score_phead(const void* q, const void* gq, const tw_kv_view* k, c
  * R == M returns 0..M-1, R == 0 writes nothing.  Errors: INVALID_ARG for
  * R < 0, R > M, null pointers with non-empty sizes; UNSUPPORTED for M > 2^20.
  */
-int32_t tw_ttp_select(const float* scores, int32_t B, int32_t M, int32_t R, int32_t* kept,
+TW_API int32_t tw_ttp_select(const float* scores, int32_t B, int32_t M, int32_t R, int32_t* kept,
                       void* stream);
 
 /*
@@ -179,7 +186,7 @@ int32_t tw_ttp_select(const float* scores, int32_t B, int32_t M, int32_t R, int3
  * Errors: INVALID_ARG for null tables or entries, R > M, v_start + M > n_tot,
  * row_bytes == 0.
  */
-int32_t tw_ttp_compact(const int32_t* kept, int32_t R, int32_t v_start, int32_t M, int32_t n_tot,
+TW_API int32_t tw_ttp_compact(const int32_t* kept, int32_t R, int32_t v_start, int32_t M, int32_t n_tot,
                        const void* const* src, void* const* dst, int32_t n_tensors,
                        size_t row_bytes, void* stream);
 
@@ -194,7 +201,7 @@ int32_t tw_ttp_compact(const int32_t* kept, int32_t R, int32_t v_start, int32_t 
  * caller's rows are and are taken as they come).
  * Errors as tw_ttp_compact, plus UNSUPPORTED for B > 65535.
  */
-int32_t tw_ttp_compact_batched(const int32_t* kept, int32_t R, int32_t v_start, int32_t M,
+TW_API int32_t tw_ttp_compact_batched(const int32_t* kept, int32_t R, int32_t v_start, int32_t M,
                                const int32_t* n_tot, int32_t n_tot_max, const int32_t* src_row_off,
                                const int32_t* dst_row_off, int32_t B, const void* const* src,
                                void* const* dst, int32_t n_tensors, size_t row_bytes, void* stream);
@@ -205,7 +212,7 @@ int32_t tw_ttp_compact_batched(const int32_t* kept, int32_t R, int32_t v_start, 
  *   parent [dev] [B][T_max];  n_nodes [dev] [B];  masks [dev] [B][T_max] uint64 out
  * (entries past n_nodes[b] are written as 0).
  */
-int32_t tw_tree_ancestor_masks(const int32_t* parent, const int32_t* n_nodes, int32_t T_max,
+TW_API int32_t tw_tree_ancestor_masks(const int32_t* parent, const int32_t* n_nodes, int32_t T_max,
                                int32_t B, uint64_t* masks, void* stream);
 
 /*
@@ -229,7 +236,7 @@ int32_t tw_tree_ancestor_masks(const int32_t* parent, const int32_t* n_nodes, in
  * plus half a bf16 unit in the last place of the result for bf16 out.
  * Errors: INVALID_ARG, UNSUPPORTED (T_max > 64, d_h, view mismatch, out_dtype), WORKSPACE.
  */
-int32_t tw_tree_verify_attn(const void* q, const tw_kv_view* k, const tw_kv_view* v,
+TW_API int32_t tw_tree_verify_attn(const void* q, const tw_kv_view* k, const tw_kv_view* v,
                             const int32_t* ctx_len, int32_t max_ctx_len, const int32_t* parent,
                             const int32_t* n_nodes, int32_t T_max, int32_t B, float scale,
                             void* out, int32_t out_dtype, void* ws, size_t ws_bytes, void* stream);
@@ -243,7 +250,7 @@ int32_t tw_tree_verify_attn(const void* q, const tw_kv_view* k, const tw_kv_view
  * Errors as tw_tree_verify_attn, plus INVALID_ARG (q_heads_per_kv < 1) and
  * UNSUPPORTED (q_heads_per_kv > 64, H_q > 65535).
  */
-int32_t tw_tree_verify_attn_gqa(const void* q, const tw_kv_view* k, const tw_kv_view* v,
+TW_API int32_t tw_tree_verify_attn_gqa(const void* q, const tw_kv_view* k, const tw_kv_view* v,
                                 int32_t q_heads_per_kv, const int32_t* ctx_len, int32_t max_ctx_len,
                                 const int32_t* parent, const int32_t* n_nodes, int32_t T_max, int32_t B,
                                 float scale, void* out, int32_t out_dtype, void* ws, size_t ws_bytes,
@@ -263,7 +270,7 @@ int32_t tw_tree_verify_attn_gqa(const void* q, const tw_kv_view* k, const tw_kv_
  * different shapes may follow each other freely.
  */
 #define TW_STATIC_SCRATCH_BYTES (16u << 20)
-int32_t tw_tree_verify_attn_static(const void* q, const tw_kv_view* k, const tw_kv_view* v,
+TW_API int32_t tw_tree_verify_attn_static(const void* q, const tw_kv_view* k, const tw_kv_view* v,
                                    const int32_t* ctx_len, int32_t max_ctx_len, const int32_t* parent,
                                    const int32_t* n_nodes, int32_t T_max, int32_t B, float scale,
                                    void* out, int32_t out_dtype, void* stream);
@@ -279,7 +286,7 @@ int32_t tw_tree_verify_attn_static(const void* q, const tw_kv_view* k, const tw_
  * = their node indices from the root side, remaining slots -1,
  * bonus[b] = argmax at the end point.  All arrays [dev] int32.
  */
-int32_t tw_tree_accept(const int32_t* draft, const int32_t* argmax, const int32_t* parent,
+TW_API int32_t tw_tree_accept(const int32_t* draft, const int32_t* argmax, const int32_t* parent,
                        const int32_t* n_nodes, int32_t T_max, int32_t B, int32_t* n_acc,
                        int32_t* path, int32_t* bonus, void* stream);
 
@@ -297,7 +304,7 @@ int32_t tw_tree_accept(const int32_t* draft, const int32_t* argmax, const int32_
  * Precondition on device contents: path strictly increasing, 1 <= path[b][i] < T_max.
  * Errors: INVALID_ARG (null pointers, malformed views), UNSUPPORTED (T_max > 64, B > 65535).
  */
-int32_t tw_kv_commit(const int32_t* path, const int32_t* n_acc, int32_t T_max, const tw_kv_view* views,
+TW_API int32_t tw_kv_commit(const int32_t* path, const int32_t* n_acc, int32_t T_max, const tw_kv_view* views,
                      int32_t n_views, const int32_t* ctx_len, int32_t B, int32_t* new_ctx_len,
                      void* stream);
 
@@ -309,7 +316,7 @@ int32_t tw_kv_commit(const int32_t* path, const int32_t* n_acc, int32_t T_max, c
  * [n][E] fp32.  Errors: INVALID_ARG (E > V, null pointers), UNSUPPORTED (E > 256,
  * V > 2^20).
  */
-int32_t tw_draft_topk(const float* probs, int32_t n, int32_t V, int32_t E, int32_t* ids, float* vals,
+TW_API int32_t tw_draft_topk(const float* probs, int32_t n, int32_t V, int32_t E, int32_t* ids, float* vals,
                       void* stream);
 
 /*
@@ -323,8 +330,31 @@ int32_t tw_draft_topk(const float* probs, int32_t n, int32_t V, int32_t E, int32
  * 16-byte loads; any other shape is accepted and read element by element.
  * Errors: INVALID_ARG (E > V, null pointers), UNSUPPORTED (E > 256, V > 2^20).
  */
-int32_t tw_draft_topk_logits(const float* logits, int32_t n, int32_t V, int32_t E, int32_t* ids, float* probs,
+TW_API int32_t tw_draft_topk_logits(const float* logits, int32_t n, int32_t V, int32_t E, int32_t* ids, float* probs,
                              void* stream);
+
+/*
+ * One level of the drafting loop (Sec. 5.4 / App. A: level 1 holds the E most probable tokens after
+ * the root; every later level expands the K most confident nodes of the level before it by E tokens
+ * each).  The candidates of sequence b live in arrays [B][N] in generation order, in the format
+ * tw_tree_build takes.  This call writes one level: candidate out_off + j * E + e is token e of
+ * expanded node j,
+ *   cand_parent = prev_off + sel[b][j]   (-1 when sel is NULL: the root is the one expanded node),
+ *   cand_token = ids[b][j][e],  cand_prob = probs[b][j][e],
+ *   cand_conf = cand_conf[parent] * cand_prob   (fp32; 1 * cand_prob under the root),
+ * and level_conf[b][j * E + e] = cand_conf of the same candidate, the row that tw_ttp_select takes
+ * to pick the next level's expanded nodes (their indices inside this level, ascending).
+ *   sel        [dev] [B][n_exp] indices into the previous level's slice [prev_off, out_off), or NULL
+ *   ids, probs [dev] [B][n_exp][E], as tw_draft_topk_logits writes them for the expanded nodes' rows
+ *   cand_parent, cand_token [dev] [B][N] int32;  cand_prob, cand_conf [dev] [B][N] fp32
+ *   level_conf [dev] [B][n_exp * E] fp32 out
+ * Errors: INVALID_ARG (negative sizes, out_off + n_exp * E > N, sel with prev_off >= out_off, no sel
+ * with n_exp > 1, null pointers), UNSUPPORTED (n_exp * E > 65536, B > 65535).
+ */
+TW_API int32_t tw_draft_expand(const int32_t* sel, int32_t n_exp, int32_t prev_off, int32_t out_off,
+                               const int32_t* ids, const float* probs, int32_t E, int32_t N, int32_t B,
+                               int32_t* cand_parent, int32_t* cand_token, float* cand_prob, float* cand_conf,
+                               float* level_conf, void* stream);
 
 /*
  * Pruning of a drafted token tree to its most confident candidates (App. A:
@@ -344,18 +374,18 @@ int32_t tw_draft_topk_logits(const float* logits, int32_t n, int32_t V, int32_t 
  * ws: tw_tree_build_workspace_bytes(B, N, T_max).  Errors: INVALID_ARG,
  * UNSUPPORTED (T_max > 64, N > 8192, B > 65535), WORKSPACE.
  */
-size_t tw_tree_build_workspace_bytes(int32_t B, int32_t N, int32_t T_max);
-int32_t tw_tree_build(const int32_t* cand_parent, const int32_t* cand_token, const float* cand_prob,
+TW_API size_t tw_tree_build_workspace_bytes(int32_t B, int32_t N, int32_t T_max);
+TW_API int32_t tw_tree_build(const int32_t* cand_parent, const int32_t* cand_token, const float* cand_prob,
                       const int32_t* n_cand, const int32_t* root_token, int32_t N, int32_t B, int32_t T_max,
                       int32_t* parent_out, int32_t* token_out, int32_t* src_out, int32_t* n_nodes_out,
                       void* ws, size_t ws_bytes, void* stream);
 
 /* Host helper: TW_OK when parent[0] == -1 and 0 <= parent[i] < i for 0 < i < T <= 64. */
-int32_t tw_validate_tree(const int32_t* parent_host, int32_t T);
+TW_API int32_t tw_validate_tree(const int32_t* parent_host, int32_t T);
 
 /* Host helper: average retained visual tokens with FinalWipe (Sec. 4.2 Eq. 6;
  * K_f = L gives Sec. 3.1 Eq. 4), rounded to the nearest integer. */
-int32_t tw_rbar(int32_t M, int32_t K, int32_t R, int32_t K_f, int32_t L);
+TW_API int32_t tw_rbar(int32_t M, int32_t K, int32_t R, int32_t K_f, int32_t L);
 
 #ifdef __cplusplus
 }

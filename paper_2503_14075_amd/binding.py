@@ -31,7 +31,7 @@ _STATUS = {0: "TW_OK", -1: "TW_ERR_INVALID_ARG", -2: "TW_ERR_UNSUPPORTED", -3: "
 
 EXPORTS = ["tw_version", "tw_workspace_bytes", "tw_ttp_score", "tw_ttp_score_gqa", "tw_ttp_score_phead", "tw_ttp_select", "tw_ttp_compact",
            "tw_ttp_compact_batched",
-           "tw_tree_ancestor_masks", "tw_tree_verify_attn", "tw_tree_verify_attn_gqa", "tw_tree_verify_attn_static", "tw_tree_accept", "tw_kv_commit", "tw_draft_topk", "tw_draft_topk_logits",
+           "tw_tree_ancestor_masks", "tw_tree_verify_attn", "tw_tree_verify_attn_gqa", "tw_tree_verify_attn_static", "tw_tree_accept", "tw_kv_commit", "tw_draft_topk", "tw_draft_topk_logits", "tw_draft_expand",
            "tw_tree_build_workspace_bytes", "tw_tree_build", "tw_validate_tree",
            "tw_rbar"]
 
@@ -83,6 +83,8 @@ _lib.tw_draft_topk.restype = _i32
 _lib.tw_draft_topk.argtypes = [_vp, _i32, _i32, _i32, _vp, _vp, _vp]
 _lib.tw_draft_topk_logits.restype = _i32
 _lib.tw_draft_topk_logits.argtypes = [_vp, _i32, _i32, _i32, _vp, _vp, _vp]
+_lib.tw_draft_expand.restype = _i32
+_lib.tw_draft_expand.argtypes = [_vp, _i32, _i32, _i32, _vp, _vp, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp]
 _lib.tw_tree_build_workspace_bytes.restype = _sz
 _lib.tw_tree_build_workspace_bytes.argtypes = [_i32, _i32, _i32]
 _lib.tw_tree_build.restype = _i32
@@ -253,6 +255,15 @@ def draft_topk_logits(logits: torch.Tensor, E: int, ids: torch.Tensor, probs: to
     n, V = logits.shape
     _check("tw_draft_topk_logits",
            _lib.tw_draft_topk_logits(_ptr(logits), n, V, E, _ptr(ids), _ptr(probs), _stream()))
+
+
+def draft_expand(sel: Optional[torch.Tensor], prev_off: int, out_off: int, ids: torch.Tensor, probs: torch.Tensor,
+                 cand_parent: torch.Tensor, cand_token: torch.Tensor, cand_prob: torch.Tensor,
+                 cand_conf: torch.Tensor, level_conf: torch.Tensor) -> None:
+    B, n_exp, E = ids.shape
+    _check("tw_draft_expand", _lib.tw_draft_expand(
+        _ptr(sel), n_exp, prev_off, out_off, _ptr(ids), _ptr(probs), E, cand_parent.shape[1], B, _ptr(cand_parent),
+        _ptr(cand_token), _ptr(cand_prob), _ptr(cand_conf), _ptr(level_conf), _stream()))
 
 
 def tree_build_workspace_bytes(B: int, N: int, T_max: int) -> int:

@@ -1,6 +1,9 @@
 // C-ABI entry points of libtwigpath: argument validation, launch planning and
 // dispatch.  Every call enqueues on the caller's stream and returns.
 #include "twig_internal.h"
+#ifdef TW_TRACE
+#include <cstdlib>
+#endif
 
 using namespace tw;
 
@@ -38,7 +41,7 @@ VerifyPlan verify_plan(int B, int H, int T_max, int max_rows) {
     p.n_blk = T_max > 32 ? 2 : 1;
     const long units = (long)B * H * p.n_blk;
     p.n_splits = 1;
-    p.split_rows = (max_rows + 31) / 32 * 32;
+    p.split_rows = (int)(((int64_t)max_rows + 31) / 32 * 32);
     if (units >= 768) {
         p.heads_per_wg = 4 / p.n_blk;
         p.n_phase = 1;
@@ -51,12 +54,15 @@ VerifyPlan verify_plan(int B, int H, int T_max, int max_rows) {
     long cap = max_rows / 256;
     if (cap < 1) cap = 1;
     if (cap > 64) cap = 64;
-    const int n = (int)(want < cap ? want : cap);
+    int n = (int)(want < cap ? want : cap);
+#ifdef TW_TRACE
+    if (const char* f = getenv("TW_FORCE_SPLITS")) n = atoi(f) > 0 ? atoi(f) : n;   // diagnostic build: plan sweeps
+#endif
     if (n > 1) {
         // whole 32-row chunks per piece, then as few pieces as cover the longest sequence
         const int per = (max_rows + n - 1) / n;
         p.split_rows = (per + 31) / 32 * 32;
-        p.n_splits = (max_rows + p.split_rows - 1) / p.split_rows;
+        p.n_splits = (int)(((int64_t)max_rows + p.split_rows - 1) / p.split_rows);
     }
     return p;
 }
@@ -73,7 +79,7 @@ size_t verify_workspace_bytes(int B, int H, int T_max, int d_h, int max_rows) {
 
 #ifdef TW_TRACE
 static unsigned long long* g_trace = nullptr;
-extern "C" void tw_debug_set_trace(void* p) { g_trace = (unsigned long long*)p; }
+extern "C" TW_API void tw_debug_set_trace(void* p) { g_trace = (unsigned long long*)p; }
 #endif
 
 extern "C" {
@@ -384,6 +390,22 @@ int32_t tw_draft_topk_logits(const float* logits, int32_t n, int32_t V, int32_t 
     hipError_t err = hipSuccess;
     if (!launch_topk_rows(logits, n, V, E, ids, probs, true, (hipStream_t)stream, &err)) return TW_ERR_UNSUPPORTED;
     return err == hipSuccess ? TW_OK : TW_ERR_LAUNCH;
+}
+
+int32_t tw_draft_expand(const int32_t* sel, int32_t n_exp, int32_t prev_off, int32_t out_off, const int32_t* ids,
+                        const float* probs, int32_t E, int32_t N, int32_t B, int32_t* cand_parent,
+                        int32_t* cand_token, float* cand_prob, float* cand_conf, float* level_conf, void* stream) {
+    if (B < 0 || n_exp < 0 || E < 0 || N < 0 || prev_off < 0 || out_off < 0) return TW_ERR_INVALID_ARG;
+    if ((int64_t)n_exp * E > 65536 || B > 65535) return TW_ERR_UNSUPPORTED;
+    if ((int64_t)out_off + (int64_t)n_exp * E > N) return TW_ERR_INVALID_ARG;
+    if (sel ? prev_off >= out_off : n_exp > 1) return TW_ERR_INVALID_ARG;   // a slice to pick from, or the root alone
+    if (B == 0 || n_exp == 0 || E == 0) return TW_OK;
+    if (!ids || !probs || !cand_parent || !cand_token || !cand_prob || !cand_conf || !level_conf)
+        return TW_ERR_INVALID_ARG;
+    return launch_draft_expand(sel, n_exp, prev_off, out_off, ids, probs, E, N, B, cand_parent, cand_token, cand_prob,
+                               cand_conf, level_conf, (hipStream_t)stream) == hipSuccess
+               ? TW_OK
+               : TW_ERR_LAUNCH;
 }
 
 size_t tw_tree_build_workspace_bytes(int32_t B, int32_t N, int32_t T_max) {

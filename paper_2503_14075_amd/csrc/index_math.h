@@ -48,6 +48,19 @@ TW_HD int clamp_parent(int p, int i) { return p < 0 ? 0 : (p >= i ? i - 1 : p); 
 // --- key/value pools ------------------------------------------------------------------------------
 // Contiguous view: first pool row of a sequence, and how many rows past it stay inside the pool.
 TW_HD int64_t seq_first_row(int row_off_raw, int64_t pool_rows) { return clampl(row_off_raw, 0, pool_rows - 1); }
+// Contiguous view, streaming kernels: the last cache row a workgroup may touch (its piece's last row,
+// cut off at the end of the pool), and the cache row of row r of the chunk that starts at `base`
+// (loads past the last row read it again), 0 <= result <= last_row.
+TW_HD int seq_last_row(int last, int64_t first_row, int64_t pool_rows) {
+    const int64_t room = pool_rows - 1 - first_row;
+    const int l = last < room ? last : (int)room;
+    return l < 0 ? 0 : l;
+}
+TW_HD int chunk_start(int base, int last_row) { return base < last_row ? (base < 0 ? 0 : base) : last_row; }
+TW_HD int chunk_row_offset(int r, int start, int last_row) {
+    const int lim = last_row - start;
+    return r < lim ? (r < 0 ? 0 : r) : lim;
+}
 // Paged view: page-table slot of cache row r (r >= 0), and the pool row of (page id, r).
 TW_HD int page_slot(int r, int page_rows, int page_shift, int max_pages) {
     const int pi = page_shift >= 0 ? r >> page_shift : r / page_rows;
@@ -80,9 +93,28 @@ TW_HD int compact_src_row_from(int kept_raw, int R, int v_start, int M, int n_to
 // --- commit of the accepted path -------------------------------------------------------------------
 // Number of accepted nodes and the context length, held where C + T_max cannot wrap.
 TW_HD int commit_n_acc(int n_acc_raw, int T_max) { return clampi(n_acc_raw, 0, T_max - 1); }
-TW_HD int commit_ctx(int ctx_raw) { return clampi(ctx_raw, 0, 0x3FFFFFFF); }
-// Tree node whose row moves to slot i of the accepted path (1 <= result < T_max).
-TW_HD int commit_path_node(int path_raw, int T_max) { return clampi(path_raw, 1, T_max - 1 > 1 ? T_max - 1 : 1); }
+TW_HD int commit_ctx(int ctx_raw) { return clampi(ctx_raw, 0, 1 << 30); }
+// Tree node whose row moves to the next slot of the accepted path, given the previous one (0 before
+// the first): strictly increasing and inside the tree whatever the contents, so that a move never
+// writes a row that a later move reads.
+TW_HD int commit_next_node(int prev, int path_raw, int T_max) {
+    const int p = path_raw <= prev ? prev + 1 : path_raw;
+    return p > T_max - 1 ? T_max - 1 : p;
+}
+// Tree size of a sequence for the integer kernels (ancestor masks, acceptance walk).
+TW_HD int tree_nodes(int n_nodes_raw, int T_max) { return clampi(n_nodes_raw, 1, T_max); }
+// Candidates of a drafted tree: their number inside [0, N]; the next step of a walk from candidate
+// u towards the root: an earlier candidate, or -1 (a child of the root; also what a parent entry
+// that does not precede u is taken for), so every walk ends after at most u + 1 steps.
+TW_HD int cand_count(int n_cand_raw, int N) { return clampi(n_cand_raw, 0, N); }
+TW_HD int cand_walk_parent(int parent_raw, int u) { return parent_raw < u ? (parent_raw < 0 ? -1 : parent_raw) : -1; }
+// The node that a level of the drafting loop expands: entry `sel_raw` of the previous level's slice
+// [prev_off, out_off) of the candidate arrays (out_off > prev_off >= 0).
+TW_HD int expand_parent(int sel_raw, int prev_off, int out_off) {
+    return prev_off + clampi(sel_raw, 0, out_off - prev_off - 1);
+}
+// Kept candidate number r of the select, inside [0, N).
+TW_HD int kept_candidate(int kept_raw, int N) { return clampi(kept_raw, 0, N - 1); }
 
 // --- pruning score ----------------------------------------------------------------------------------
 // Scoring rows, prompt length and first scoring position of a sequence: 0 <= n_q <= n_q_max rows of

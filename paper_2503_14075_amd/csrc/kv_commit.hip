@@ -23,19 +23,16 @@ __global__ __launch_bounds__(kCommitThreads) void kv_commit_kernel(CommitArgs a)
     const KvDev& kv = a.views[blockIdx.y];
     const size_t row_bytes = (size_t)kv.H * kv.d_h * (a.elem_bytes[blockIdx.y]);
     const size_t col = ((size_t)blockIdx.x * kCommitThreads + threadIdx.x) * 16;
-    int n = a.n_acc[b];
-    n = n < 0 ? 0 : (n > a.T_max - 1 ? a.T_max - 1 : n);
+    const int n = commit_n_acc(a.n_acc[b], a.T_max);
     // held where C + T_max cannot wrap; rows past the pool are clamped by pool_row
-    const int C = a.ctx_len[b] < 0 ? 0 : (a.ctx_len[b] > (1 << 30) ? (1 << 30) : a.ctx_len[b]);
+    const int C = commit_ctx(a.ctx_len[b]);
     if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0 && a.new_ctx_len) a.new_ctx_len[b] = C + 1 + n;
     if (col >= row_bytes) return;
     char* base = (char*)kv.base;
     int prev = 0;
     for (int i = 0; i < n; ++i) {
-        int p = a.path[(int64_t)b * a.T_max + i];
-        // keep the order property even on malformed input: strictly increasing, inside the tree
-        p = p <= prev ? prev + 1 : p;
-        p = p > a.T_max - 1 ? a.T_max - 1 : p;
+        // keeps the order property even on malformed input: strictly increasing, inside the tree
+        const int p = commit_next_node(prev, a.path[(int64_t)b * a.T_max + i], a.T_max);
         prev = p;
         if (p == i + 1) continue;   // already in place
         const char* src = base + (size_t)pool_row(kv, b, C + p) * row_bytes + col;

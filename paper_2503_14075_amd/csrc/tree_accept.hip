@@ -10,8 +10,7 @@ __global__ __launch_bounds__(64) void ancestor_masks_kernel(const int32_t* __res
                                                             int T_max, uint64_t* __restrict__ masks) {
     __shared__ int s_parent[TW_MAX_TREE];
     const int b = blockIdx.x, i = threadIdx.x;
-    int T = n_nodes[b];
-    T = T < 1 ? 1 : (T > T_max ? T_max : T);
+    const int T = tree_nodes(n_nodes[b], T_max);
     s_parent[i] = i < T ? parent[(int64_t)b * T_max + i] : 0;
     __syncthreads();
     if (i < T_max) masks[(int64_t)b * T_max + i] = i < T ? ancestor_mask(s_parent, i) : 0ull;
@@ -33,13 +32,9 @@ __global__ __launch_bounds__(64) void accept_kernel(const int32_t* __restrict__ 
     __shared__ unsigned long long s_best_anc;
     const int b = blockIdx.x, i = threadIdx.x;
     const int64_t base = (int64_t)b * T_max;
-    int T = n_nodes[b];
-    T = T < 1 ? 1 : (T > T_max ? T_max : T);
+    const int T = tree_nodes(n_nodes[b], T_max);
     int par = 0;
-    if (i < T) {
-        par = parent[base + i];
-        par = i == 0 ? -1 : (par < 0 ? 0 : (par >= i ? i - 1 : par));
-    }
+    if (i < T) par = i == 0 ? -1 : clamp_parent(parent[base + i], i);
     s_parent[i] = par;
     __syncthreads();
     const uint64_t anc = i < T ? ancestor_mask(s_parent, i) : 0ull;

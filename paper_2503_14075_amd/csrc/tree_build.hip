@@ -21,8 +21,7 @@ __device__ __forceinline__ float path_confidence(const int32_t* __restrict__ can
     int u = i;
     for (int step = 0; step < N && u >= 0; ++step) {
         c *= cand_prob[row + u];
-        const int p = cand_parent[row + u];
-        u = p < u ? p : -1;
+        u = cand_walk_parent(cand_parent[row + u], u);
     }
     return c;
 }
@@ -33,8 +32,7 @@ __global__ __launch_bounds__(kTbThreads) void tree_conf_kernel(const int32_t* __
                                                                float* __restrict__ conf) {
     const int b = blockIdx.y, i = blockIdx.x * kTbThreads + threadIdx.x;
     if (i >= N) return;
-    int n = n_cand[b];
-    n = n < 0 ? 0 : (n > N ? N : n);
+    const int n = cand_count(n_cand[b], N);
     conf[(int64_t)b * N + i] = path_confidence(cand_parent, cand_prob, (int64_t)b * N, i, n, N);
 }
 
@@ -43,8 +41,7 @@ __global__ __launch_bounds__(kTbThreads) void tree_conf_kernel(const int32_t* __
 // s_inv: N ints of LDS, candidate index -> node id, 0 = not kept.
 __device__ __forceinline__ void emit_tree(const TreeBuildArgs& a, int b, int32_t* s_inv) {
     const int tid = threadIdx.x;
-    int n = a.n_cand[b];
-    n = n < 0 ? 0 : (n > a.N ? a.N : n);
+    const int n = cand_count(a.n_cand[b], a.N);
     const int n_keep = n < a.R ? n : a.R;
     for (int i = tid; i < a.N; i += kTbThreads) s_inv[i] = 0;
     __syncthreads();
@@ -60,8 +57,7 @@ __device__ __forceinline__ void emit_tree(const TreeBuildArgs& a, int b, int32_t
             par = -1;
             tok = a.root_token[b];
         } else if (t <= n_keep) {
-            int c = a.kept[(int64_t)b * a.R + t - 1];
-            c = c < 0 ? 0 : (c >= a.N ? a.N - 1 : c);
+            const int c = kept_candidate(a.kept[(int64_t)b * a.R + t - 1], a.N);
             const int p = a.cand_parent[(int64_t)b * a.N + c];
             par = (p >= 0 && p < c) ? s_inv[p] : 0;   // a child of the root, or of a kept candidate
             par = par < t ? par : 0;
@@ -88,8 +84,7 @@ __global__ __launch_bounds__(kTbThreads) void tree_build_fused_kernel(TreeBuildA
                                                                       float* conf) {
     extern __shared__ int32_t s_inv[];
     const int b = blockIdx.x;
-    int n = a.n_cand[b];
-    n = n < 0 ? 0 : (n > a.N ? a.N : n);
+    const int n = cand_count(a.n_cand[b], a.N);
     const int64_t row = (int64_t)b * a.N;
     for (int i = threadIdx.x; i < a.N; i += kTbThreads)
         conf[row + i] = path_confidence(a.cand_parent, cand_prob, row, i, n, a.N);

@@ -349,26 +349,21 @@ struct SeqAddr {
     __device__ __forceinline__ SeqAddr(const VerifyArgs& a, int b, int hc, int row_bytes, uint32_t pool_stride,
                                        int last) {
         stride = pool_stride;
-        const int64_t last_pool = a.k.pool_rows - 1;
         int64_t row0 = 0;
         if (PAGED) {
             ptab = a.k.page_table + (int64_t)b * a.k.max_pages;
             last_row = last;
         } else {
             ptab = nullptr;
-            row0 = (int64_t)a.k.row_off[b];
-            row0 = row0 < 0 ? 0 : (row0 > last_pool ? last_pool : row0);
-            const int64_t room = last_pool - row0;
-            last_row = last < room ? last : (int)room;
+            row0 = seq_first_row(a.k.row_off[b], a.k.pool_rows);
+            last_row = seq_last_row(last, row0, a.k.pool_rows);
         }
         k_seq = (const unsigned char*)a.k.base + (uint64_t)row0 * pool_stride + (int64_t)hc * row_bytes;
         v_seq = (const unsigned char*)a.v.base + (uint64_t)row0 * pool_stride + (int64_t)hc * row_bytes;
     }
     __device__ __forceinline__ int page(const VerifyArgs& a, int r) const {
         r = r < last_row ? r : last_row;
-        int pi = a.k.page_shift >= 0 ? r >> a.k.page_shift : r / a.k.page_rows;
-        pi = pi < a.k.max_pages ? pi : a.k.max_pages - 1;
-        return ptab[pi];
+        return ptab[page_slot(r, a.k.page_rows, a.k.page_shift, a.k.max_pages)];
     }
     __device__ __forceinline__ ChunkAddr chunk(const unsigned char* seq, int base) const {
         ChunkAddr c;
@@ -376,7 +371,7 @@ struct SeqAddr {
             c.base = seq;
             c.lim = 0;
         } else {
-            const int cb = base < last_row ? base : last_row;
+            const int cb = chunk_start(base, last_row);
             c.base = seq + (uint64_t)(uint32_t)cb * stride;
             c.lim = last_row - cb;
         }
@@ -387,13 +382,10 @@ struct SeqAddr {
         if (PAGED) {
             int row = base + r;
             row = row < last_row ? row : last_row;
-            const int slot = a.k.page_shift >= 0 ? row & (a.k.page_rows - 1) : row % a.k.page_rows;
-            int64_t prow = (int64_t)page * a.k.page_rows + slot;
-            const int64_t last_pool = a.k.pool_rows - 1;
-            prow = prow < 0 ? 0 : (prow > last_pool ? last_pool : prow);
+            const int64_t prow = paged_pool_row(page, row, a.k.page_rows, a.k.page_shift, a.k.pool_rows);
             return (const u32x4*)(c.base + (uint64_t)(uint32_t)prow * stride + 16 * col);
         }
-        const int rr = r < c.lim ? r : c.lim;
+        const int rr = r < c.lim ? r : c.lim;   // chunk_row_offset with the chunk's limit precomputed; r >= 0
         return (const u32x4*)(c.base + ((uint32_t)rr * stride + 16u * (uint32_t)col));
     }
 };

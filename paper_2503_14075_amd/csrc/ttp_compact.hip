@@ -12,31 +12,18 @@ namespace tw {
 constexpr int kCompactMaxThreads = 1024;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 
-__device__ __forceinline__ int compact_src_row(const int32_t* kept, int R, int v_start, int M, int r) {
-    if (r < v_start) return r;
-    if (r < v_start + R) {
-        int m = kept[r - v_start];
-        m = m < 0 ? 0 : (m >= M ? M - 1 : m);
-        return v_start + m;
-    }
-    return r - R + M;
-}
-
 template <bool kVec16>
 __global__ __launch_bounds__(kCompactMaxThreads) void compact_kernel(CompactBatch cb, CompactTable tab,
                                                                   size_t row_bytes) {
     const int r = blockIdx.x, b = blockIdx.z;
     // a sequence length from device memory is held between the end of the visual span and the host's
     // upper bound, so every row index below stays inside [0, n_tot_all) of the sequence
-    int n_tot = cb.n_tot_all;
-    if (cb.n_tot) {
-        n_tot = cb.n_tot[b];
-        n_tot = n_tot < cb.v_start + cb.M ? cb.v_start + cb.M : (n_tot > cb.n_tot_all ? cb.n_tot_all : n_tot);
-    }
+    const int n_tot = cb.n_tot ? compact_n_tot(cb.n_tot[b], cb.v_start, cb.M, cb.n_tot_all) : cb.n_tot_all;
     if (r >= n_tot - cb.M + cb.R) return;
     const int64_t s0 = cb.src_off ? cb.src_off[b] : 0, d0 = cb.dst_off ? cb.dst_off[b] : 0;
-    int sr = compact_src_row(cb.kept + (int64_t)b * cb.R, cb.R, cb.v_start, cb.M, r);
-    sr = sr < n_tot ? sr : n_tot - 1;   // stays inside the sequence even if the span does not
+    const bool in_kept = r >= cb.v_start && r < cb.v_start + cb.R;
+    const int sr = compact_src_row_from(in_kept ? cb.kept[(int64_t)b * cb.R + r - cb.v_start] : 0, cb.R, cb.v_start,
+                                        cb.M, n_tot, r);
     const char* src = (const char*)tab.src[blockIdx.y] + (size_t)(s0 + sr) * row_bytes;
     char* dst = (char*)tab.dst[blockIdx.y] + (size_t)(d0 + r) * row_bytes;
     if (kVec16) {

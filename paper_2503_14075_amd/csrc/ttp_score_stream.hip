@@ -51,12 +51,10 @@ __global__ __launch_bounds__(kStThreads, 2) void score_stream_kernel(ScoreArgs a
     const int g = lane >> 5, li = lane & 31;
     const int b = blockIdx.y, h = blockIdx.x * 4 + wave, split = blockIdx.z;
     if (h >= a.H) return;
-    int n_q = a.n_q ? a.n_q[b] : a.n_q_max;
-    n_q = n_q < 1 ? 1 : (n_q > a.n_q_max ? a.n_q_max : n_q);
-    int n_tot = a.n_tot[b];
-    n_tot = n_tot < 0 ? 0 : (n_tot > a.n_tot_max ? a.n_tot_max : n_tot);
+    const ScoreSeq sq = score_seq_from(a.n_q ? a.n_q[b] : a.n_q_max, a.n_tot[b], a.q_pos0[b], a.n_q_max, 0, a.n_q_max,
+                                       a.n_tot_max);
+    const int n_q = sq.n_q, n_tot = sq.n_tot, pos0 = sq.pos0;
     if (n_tot == 0) return;   // the weights kernel writes zeros without looking at the table
-    const int pos0 = a.q_pos0[b];
     unsigned char* ldsK = lds + wave * Cf::kWaveLds;
     unsigned char* s_tr = ldsK + kStChunk * Cf::kKStride;
 
@@ -90,8 +88,7 @@ __global__ __launch_bounds__(kStThreads, 2) void score_stream_kernel(ScoreArgs a
         for (int j = 0; j < Cf::kLoads; ++j) {
             int r = base + ld_row + Cf::kRowsPerLoad * j;
             r = r < k_end - 1 ? r : k_end - 1;   // past the end: re-read the last key (cached), masked below
-            int64_t prow = row0 + r;
-            prow = prow < 0 ? 0 : (prow > last_pool_row ? last_pool_row : prow);
+            const int64_t prow = clampl(row0 + r, 0, last_pool_row);
             pk[j] = __builtin_nontemporal_load((const u32x4*)(kbase + prow * pool_stride));   // streamed once
         }
     };
@@ -183,10 +180,8 @@ __global__ __launch_bounds__(64) void score_stream_weights_kernel(ScoreArgs a) {
     const int lane = threadIdx.x;
     const int jj = lane & 31;
     const int h = blockIdx.y, b = blockIdx.z;
-    int n_q = a.n_q ? a.n_q[b] : a.n_q_max;
-    n_q = n_q < 1 ? 1 : (n_q > a.n_q_max ? a.n_q_max : n_q);
-    int n_tot = a.n_tot[b];
-    n_tot = n_tot < 0 ? 0 : (n_tot > a.n_tot_max ? a.n_tot_max : n_tot);
+    const ScoreSeq sq = score_seq_from(a.n_q ? a.n_q[b] : a.n_q_max, a.n_tot[b], 0, a.n_q_max, 0, a.n_q_max, a.n_tot_max);
+    const int n_q = sq.n_q, n_tot = sq.n_tot;
     const int span_end = a.v_start + a.M, c_base = a.v_start / kStChunk * kStChunk;
     const int span_chunks = (span_end - c_base + kStChunk - 1) / kStChunk;
     constexpr int e_rows = ER;

@@ -41,17 +41,11 @@ inline KvDev to_dev(const tw_kv_view& v) {
 // Pool row of cache row r of sequence b, clamped into the pool.
 __device__ __forceinline__ int64_t pool_row(const KvDev& kv, int b, int r) {
     r = r < 0 ? 0 : r;   // a row index made from unchecked device contents may have wrapped
-    int64_t row;
     if (kv.page_table) {
-        int pi = kv.page_shift >= 0 ? r >> kv.page_shift : r / kv.page_rows;
-        const int slot = kv.page_shift >= 0 ? r & (kv.page_rows - 1) : r % kv.page_rows;
-        pi = pi < kv.max_pages ? pi : kv.max_pages - 1;
-        row = (int64_t)kv.page_table[(int64_t)b * kv.max_pages + pi] * kv.page_rows + slot;
-    } else {
-        row = (int64_t)kv.row_off[b] + r;
+        const int pi = page_slot(r, kv.page_rows, kv.page_shift, kv.max_pages);
+        return paged_pool_row(kv.page_table[(int64_t)b * kv.max_pages + pi], r, kv.page_rows, kv.page_shift, kv.pool_rows);
     }
-    row = row < 0 ? 0 : row;
-    return row < kv.pool_rows ? row : kv.pool_rows - 1;
+    return contiguous_pool_row(kv.row_off[b], r, kv.pool_rows);
 }
 
 __device__ __forceinline__ float bf16_to_f32(uint16_t x) { return __uint_as_float((uint32_t)x << 16); }
@@ -362,6 +356,9 @@ hipError_t launch_tree_conf(const int32_t* cand_parent, const float* cand_prob, 
 bool launch_tree_build_fused(const TreeBuildArgs& a, const float* cand_prob, float* conf, int B, hipStream_t s,
                              hipError_t* err);
 hipError_t launch_tree_emit(const TreeBuildArgs& a, int B, hipStream_t s);
+hipError_t launch_draft_expand(const int32_t* sel, int n_exp, int prev_off, int out_off, const int32_t* ids,
+                               const float* probs, int E, int N, int B, int32_t* cand_parent, int32_t* cand_token,
+                               float* cand_prob, float* cand_conf, float* level_conf, hipStream_t s);
 
 // --- commit of the accepted path ------------------------------------------------
 constexpr int kCommitMaxViews = 32;

@@ -124,6 +124,14 @@ def test_argument_validation_without_launch():
     assert sg(P, 8, P, P, ctypes.byref(v), 65, P, 700, 2, 0, 576, 0.1, 1, P, P, 1 << 30, None) == tw.TW_ERR_UNSUPPORTED
     assert sg(P, 8, P, P, ctypes.byref(v), 7, P, 700, 2, 0, 576, 0.1, 1, P, P, 16, None) == tw.TW_ERR_WORKSPACE
     assert sg(P, 8, P, P, ctypes.byref(v), 7, P, 700, 0, 0, 576, 0.1, 1, P, P, 0, None) == tw.TW_OK
+    de = lambda **kw: lib.tw_draft_expand(kw.get("sel", P), kw.get("n_exp", 10), kw.get("prev", 10), kw.get("out", 110), P,
+                                          kw.get("probs", P), 10, kw.get("N", 310), kw.get("B", 2), P, P, P, P, P, None)
+    assert de(N=200) == tw.TW_ERR_INVALID_ARG                 # the level does not fit the candidate arrays
+    assert de(prev=110) == tw.TW_ERR_INVALID_ARG              # empty previous level
+    assert de(sel=None) == tw.TW_ERR_INVALID_ARG              # only the root is expanded without a selection
+    assert de(probs=None) == tw.TW_ERR_INVALID_ARG
+    assert de(n_exp=7000) == tw.TW_ERR_UNSUPPORTED
+    assert de(B=0) == tw.TW_OK
     tb = lambda **kw: lib.tw_tree_build(kw.get("cp", P), P, P, P, P, kw.get("N", 310), kw.get("B", 1),
                                         kw.get("T", 61), P, P, P, P, kw.get("ws", None), kw.get("ws_bytes", 0), None)
     assert tb(T=65) == tw.TW_ERR_UNSUPPORTED

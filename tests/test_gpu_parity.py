@@ -1080,6 +1080,104 @@ def test_tree_build_against_fp64_confidences_and_feeds_verification(tw, E, K):
     check_verify(tw, q, k, v, ctx, n_nodes, trees, 1 / math.sqrt(d_h), row_off=off)
 
 
+def test_drafting_loop_end_to_end(tw):
+    # App. A, tree-based SSD with the paper's E = 10, K = 10, D = 4, N_max = 60, entirely through library
+    # calls: top-E from logits, candidate bookkeeping on the device (tw_draft_expand), top-K of the level by
+    # cumulative confidence (tw_ttp_select), pruning to N_max (tw_tree_build), then verification attention and
+    # the acceptance walk on the tree that came out.  The oracle runs the same loop from its own functions.
+    # The draft model between the levels is a seeded table of logits (row 0 after the root, row 1 + c after
+    # candidate c); gathering the rows of the expanded nodes stands in for its forward passes.
+    E, K, D, V, T_max, B = 10, 10, 4, 32000, 61, 2
+    N = E + (D - 1) * K * E
+    tables = [W.normal(7000 + b, 1, (1 + N, V), 3.0, torch.float32) for b in range(B)]
+    ref = [oracle.draft_tree(t, E, K, D) for t in tables]
+    # the seeds are chosen so that no level's selection sits at a near-tie (then fp32 and fp64 may expand
+    # different nodes and the trees are not comparable any more)
+    assert all(float(r[5].min()) > 1e-3 for r in ref)
+    tab = torch.stack(tables).to(DEV)                                   # [B][1 + N][V]
+    cp = torch.full((B, N), -7, dtype=torch.int32, device=DEV)
+    ct = torch.full((B, N), -7, dtype=torch.int32, device=DEV)
+    pb = torch.zeros((B, N), dtype=torch.float32, device=DEV)
+    cf = torch.zeros((B, N), dtype=torch.float32, device=DEV)
+    prev_off, prev_n, out_off, sel = 0, 0, 0, None
+    expanded = []
+    for level in range(1, D + 1):
+        if level == 1:
+            rows = tab[:, 0:1]                                          # [B][1][V]
+        else:
+            k_l = min(K, prev_n)
+            sel = torch.empty((B, k_l), dtype=torch.int32, device=DEV)
+            tw.ttp_select(level_conf, k_l, sel)
+            idx = (1 + prev_off + sel.long()).unsqueeze(-1).expand(B, k_l, V)
+            rows = torch.gather(tab, 1, idx)                            # the "forward passes"
+            expanded.append((prev_off + sel).cpu())
+        n_exp = rows.shape[1]
+        ids = torch.empty((B, n_exp, E), dtype=torch.int32, device=DEV)
+        pr = torch.empty((B, n_exp, E), dtype=torch.float32, device=DEV)
+        tw.draft_topk_logits(rows.reshape(B * n_exp, V).contiguous(), E, ids.view(B * n_exp, E), pr.view(B * n_exp, E))
+        level_conf = torch.empty((B, n_exp * E), dtype=torch.float32, device=DEV)
+        tw.draft_expand(sel, prev_off, out_off, ids, pr, cp, ct, pb, cf, level_conf)
+        prev_off, prev_n, out_off = out_off, n_exp * E, out_off + n_exp * E
+    assert out_off == N
+    root = _i32([11, 12])
+    po = torch.full((B, T_max), -9, dtype=torch.int32, device=DEV)
+    to = torch.full((B, T_max), -9, dtype=torch.int32, device=DEV)
+    so = torch.full((B, T_max), -9, dtype=torch.int32, device=DEV)
+    nn = torch.full((B,), -9, dtype=torch.int32, device=DEV)
+    ws = torch.empty(tw.tree_build_workspace_bytes(B, N, T_max) // 4 + 1, dtype=torch.float32, device=DEV)
+    tw.tree_build(cp, ct, pb, _i32([N] * B), root, T_max, po, to, so, nn, ws)
+    torch.cuda.synchronize()
+    for b in range(B):
+        wpar, wtok, wprob, wconf, wexp, _ = ref[b]
+        # candidates: structure and tokens exact, probabilities and confidences to fp32 accuracy
+        assert torch.equal(cp[b].cpu(), wpar) and torch.equal(ct[b].cpu(), wtok)
+        assert float(((pb[b].cpu().double() - wprob).abs() / wprob).max()) <= 2e-5
+        assert float(((cf[b].cpu().double() - wconf).abs() / wconf).max()) <= 1e-4
+        for lvl in range(D - 1):
+            assert expanded[lvl][b].tolist() == [c for c in wexp[lvl].tolist() if c >= 0]
+        # pruning to N_max: the oracle prunes its own candidates; the kept sets may differ only within the
+        # accuracy of the fp32 confidences (probabilities to 2e-5, four factors) of the last kept one
+        n, _, _, wsrc = oracle.tree_build(wpar.tolist(), wtok.tolist(), wprob.float().tolist(), int(root[b]), T_max)
+        assert int(nn[b]) == n == T_max
+        kept = so[b].cpu().tolist()[1:n]
+        diff = set(kept) ^ set(wsrc[1:n].tolist())
+        if diff:
+            thr = float(torch.sort(wconf, descending=True).values[n - 2])
+            assert all(abs(float(wconf[c]) - thr) <= 2e-4 * thr for c in diff), (b, sorted(diff))
+        node_of = {c: 1 + r for r, c in enumerate(kept)}
+        gp, gt = po[b].cpu().tolist(), to[b].cpu().tolist()
+        assert kept == sorted(kept) and gp[0] == -1 and gt[0] == int(root[b])
+        for r, c in enumerate(kept):
+            assert gp[1 + r] == (0 if int(wpar[c]) < 0 else node_of[int(wpar[c])]) and gt[1 + r] == int(wtok[c])
+    # the drafted trees go through verification and acceptance as they are
+    H, d_h = 8, 128
+    ctx = [130, 77]
+    trees = [po[b].cpu().tolist() for b in range(B)]
+    q, k, v, off = make_case(93, B, H, d_h, ctx, T_max, torch.bfloat16, trees)
+    check_verify(tw, q, k, v, ctx, [T_max] * B, trees, 1 / math.sqrt(d_h), row_off=off)
+    rng = W.HostRng(94, 0)
+    argmax = []
+    for b in range(B):
+        # the target agrees with the draft along one root-to-leaf path and nowhere else
+        am = [rng.randint(0, V - 1) for _ in range(T_max)]
+        u, toks = 0, to[b].cpu().tolist()
+        while True:
+            kids = [i for i in range(1, T_max) if trees[b][i] == u]
+            if not kids:
+                break
+            am[u] = toks[kids[0]]
+            u = kids[0]
+        argmax.append(am)
+    n_acc = torch.zeros(B, dtype=torch.int32, device=DEV)
+    path = torch.zeros((B, T_max), dtype=torch.int32, device=DEV)
+    bonus = torch.zeros(B, dtype=torch.int32, device=DEV)
+    tw.tree_accept(to, _i32(argmax), po, nn, n_acc, path, bonus)
+    torch.cuda.synchronize()
+    wa = oracle.tree_accept([to[b].cpu().tolist() for b in range(B)], argmax, trees, [T_max] * B)
+    assert torch.equal(n_acc.cpu(), wa[0]) and torch.equal(path.cpu(), wa[1]) and torch.equal(bonus.cpu(), wa[2])
+    assert int(n_acc.min()) >= 1
+
+
 # ----------------------------------------------------------------------------
 # the five configurations, whole path
 # ----------------------------------------------------------------------------
