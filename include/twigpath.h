@@ -143,6 +143,18 @@ TW_API int32_t tw_ttp_score_gqa(const void* q_sel, int32_t n_q_max, const int32_
                          void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * tw_ttp_score followed by tw_ttp_select in one call, with one launch fewer: the launch that adds
+ * the heads also keeps the R best visual tokens of every row (rows of up to 1024 scores; longer
+ * rows get the separate select launch).  scores and kept come out bit-identical to the two
+ * separate calls.  kept [dev] [B][R] int32 out; R == 0 leaves it untouched.
+ * Errors: those of tw_ttp_score and tw_ttp_select.
+ */
+TW_API int32_t tw_ttp_score_select(const void* q_sel, int32_t n_q_max, const int32_t* n_q, const int32_t* q_pos0,
+                                   const tw_kv_view* k, const int32_t* n_tot, int32_t n_tot_max, int32_t B,
+                                   int32_t v_start, int32_t M, float scale, int32_t causal, float* scores,
+                                   int32_t R, int32_t* kept, void* ws, size_t ws_bytes, void* stream);
+
+/*
  * Pruning score in the P-Head form (Sec. 5.1 Eq. 7).  One query per sequence
  * (the last text token).  For head h and visual key m the logit is
  *   scale * sum_c (gq[b][h][c] * q[b][h][c]) * (gk[key][h][c] * K[key][h][c]),   key = v_start + m,

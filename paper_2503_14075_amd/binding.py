@@ -29,7 +29,7 @@ TW_STATIC_SCRATCH_BYTES = 16 << 20
 _STATUS = {0: "TW_OK", -1: "TW_ERR_INVALID_ARG", -2: "TW_ERR_UNSUPPORTED", -3: "TW_ERR_WORKSPACE",
            -4: "TW_ERR_LAUNCH"}
 
-EXPORTS = ["tw_version", "tw_workspace_bytes", "tw_ttp_score", "tw_ttp_score_gqa", "tw_ttp_score_phead", "tw_ttp_select", "tw_ttp_compact",
+EXPORTS = ["tw_version", "tw_workspace_bytes", "tw_ttp_score", "tw_ttp_score_gqa", "tw_ttp_score_select", "tw_ttp_score_phead", "tw_ttp_select", "tw_ttp_compact",
            "tw_ttp_compact_batched",
            "tw_tree_ancestor_masks", "tw_tree_verify_attn", "tw_tree_verify_attn_gqa", "tw_tree_verify_attn_static", "tw_tree_accept", "tw_kv_commit", "tw_draft_topk", "tw_draft_topk_logits", "tw_draft_expand",
            "tw_tree_build_workspace_bytes", "tw_tree_build", "tw_validate_tree",
@@ -53,6 +53,9 @@ _lib.tw_ttp_score.argtypes = [_vp, _i32, _vp, _vp, ctypes.POINTER(KvView), _vp, 
 _lib.tw_ttp_score_gqa.restype = _i32
 _lib.tw_ttp_score_gqa.argtypes = [_vp, _i32, _vp, _vp, ctypes.POINTER(KvView), _i32, _vp, _i32, _i32, _i32, _i32,
                                   _f32, _i32, _vp, _vp, _sz, _vp]
+_lib.tw_ttp_score_select.restype = _i32
+_lib.tw_ttp_score_select.argtypes = [_vp, _i32, _vp, _vp, ctypes.POINTER(KvView), _vp, _i32, _i32, _i32, _i32,
+                                     _f32, _i32, _vp, _i32, _vp, _vp, _sz, _vp]
 _lib.tw_ttp_score_phead.restype = _i32
 _lib.tw_ttp_score_phead.argtypes = [_vp, _vp, ctypes.POINTER(KvView), ctypes.POINTER(KvView), _i32, _i32, _i32,
                                     _f32, _vp, _vp, _sz, _vp]
@@ -151,6 +154,16 @@ def ttp_score(q_sel: torch.Tensor, k: KvView, n_q: Optional[torch.Tensor], q_pos
     _check("tw_ttp_score", _lib.tw_ttp_score(
         _ptr(q_sel), n_q_max, _ptr(n_q), _ptr(q_pos0), ctypes.byref(k), _ptr(n_tot), n_tot_max, B,
         v_start, M, scale, int(causal), _ptr(scores), _ptr(ws),
+        0 if ws is None else ws.numel() * ws.element_size(), _stream()))
+
+
+def ttp_score_select(q_sel: torch.Tensor, k: KvView, n_q: Optional[torch.Tensor], q_pos0: torch.Tensor,
+                     n_tot: torch.Tensor, n_tot_max: int, v_start: int, M: int, scale: float, causal: bool,
+                     scores: torch.Tensor, R: int, kept: torch.Tensor, ws: Optional[torch.Tensor]) -> None:
+    B, n_q_max = q_sel.shape[0], q_sel.shape[1]
+    _check("tw_ttp_score_select", _lib.tw_ttp_score_select(
+        _ptr(q_sel), n_q_max, _ptr(n_q), _ptr(q_pos0), ctypes.byref(k), _ptr(n_tot), n_tot_max, B,
+        v_start, M, scale, int(causal), _ptr(scores), R, _ptr(kept), _ptr(ws),
         0 if ws is None else ws.numel() * ws.element_size(), _stream()))
 
 

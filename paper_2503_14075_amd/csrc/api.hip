@@ -102,10 +102,35 @@ int32_t tw_ttp_score(const void* q_sel, int32_t n_q_max, const int32_t* n_q, con
                             scores, ws, ws_bytes, stream);
 }
 
+// score, and with kept != NULL the top-R keep of every row inside the last launch
+static int32_t score_impl(const void* q_sel, int32_t n_q_max, const int32_t* n_q, const int32_t* q_pos0,
+                          const tw_kv_view* k, int32_t q_heads_per_kv, const int32_t* n_tot, int32_t n_tot_max,
+                          int32_t B, int32_t v_start, int32_t M, float scale, int32_t causal, float* scores,
+                          int32_t R, int32_t* kept, void* ws, size_t ws_bytes, void* stream);
+
 int32_t tw_ttp_score_gqa(const void* q_sel, int32_t n_q_max, const int32_t* n_q, const int32_t* q_pos0,
                          const tw_kv_view* k, int32_t q_heads_per_kv, const int32_t* n_tot, int32_t n_tot_max,
                          int32_t B, int32_t v_start, int32_t M, float scale, int32_t causal, float* scores,
                          void* ws, size_t ws_bytes, void* stream) {
+    return score_impl(q_sel, n_q_max, n_q, q_pos0, k, q_heads_per_kv, n_tot, n_tot_max, B, v_start, M, scale, causal,
+                      scores, 0, nullptr, ws, ws_bytes, stream);
+}
+
+int32_t tw_ttp_score_select(const void* q_sel, int32_t n_q_max, const int32_t* n_q, const int32_t* q_pos0,
+                            const tw_kv_view* k, const int32_t* n_tot, int32_t n_tot_max, int32_t B, int32_t v_start,
+                            int32_t M, float scale, int32_t causal, float* scores, int32_t R, int32_t* kept, void* ws,
+                            size_t ws_bytes, void* stream) {
+    if (R < 0 || R > M) return TW_ERR_INVALID_ARG;
+    if (M > (1 << 20)) return TW_ERR_UNSUPPORTED;
+    if (R > 0 && B > 0 && !kept) return TW_ERR_INVALID_ARG;
+    return score_impl(q_sel, n_q_max, n_q, q_pos0, k, 1, n_tot, n_tot_max, B, v_start, M, scale, causal, scores, R,
+                      R > 0 ? kept : nullptr, ws, ws_bytes, stream);
+}
+
+static int32_t score_impl(const void* q_sel, int32_t n_q_max, const int32_t* n_q, const int32_t* q_pos0,
+                          const tw_kv_view* k, int32_t q_heads_per_kv, const int32_t* n_tot, int32_t n_tot_max,
+                          int32_t B, int32_t v_start, int32_t M, float scale, int32_t causal, float* scores,
+                          int32_t R, int32_t* kept, void* ws, size_t ws_bytes, void* stream) {
     if (B < 0 || M < 0 || n_q_max < 1 || n_tot_max < 1 || v_start < 0 || q_heads_per_kv < 1)
         return TW_ERR_INVALID_ARG;
     if (q_heads_per_kv > 64) return TW_ERR_UNSUPPORTED;
@@ -137,6 +162,8 @@ int32_t tw_ttp_score_gqa(const void* q_sel, int32_t n_q_max, const int32_t* n_q,
     a.M = M;
     a.causal = causal != 0;
     a.scale = scale;
+    a.kept = kept;
+    a.R = R;
     return launch_score(a, k->dtype, (hipStream_t)stream) == hipSuccess ? TW_OK : TW_ERR_LAUNCH;
 }
 

@@ -25,6 +25,7 @@
 // sum over scoring rows is in-lane).  Everything else takes the generic fp32
 // vector path.
 #include "mfma_util.h"
+#include "select_block.h"
 #include "twig_internal.h"
 
 namespace tw {
@@ -432,6 +433,35 @@ __global__ __launch_bounds__(256) void score_reduce_kernel(ScoreArgs a) {
     a.scores[(int64_t)b * a.M + m] = acc / ((float)a.H * (float)n_q);
 }
 
+// The same head reduction followed, inside the launch, by the top-R keep of the row (TopR of
+// Sec. 3.1 Eq. 3) for rows of up to 1024 scores: one workgroup of 1024 lanes per sequence, a lane
+// per column (all loads of a batch in flight together, heads added in the order of
+// score_reduce_kernel so the scores are bit-identical).  Each lane writes its score and the select
+// reads it back through the same lane, so no other lane's write is ever read.
+constexpr int kFusedSelectMaxM = 1024;
+__global__ __launch_bounds__(1024) void score_reduce_select_kernel(ScoreArgs a) {
+    const int b = blockIdx.x, m = threadIdx.x;
+    if (m < a.M) {
+        const int q_rows = a.q_stride ? a.q_stride : a.n_q_max;
+        const int n_q = clampi(a.n_q ? a.n_q[b] : q_rows, 1, q_rows);
+        float acc = 0.f;
+        for (int half = 0; half < a.n_halves; ++half) {
+            const float* p = a.ws + ((int64_t)half * a.B + b) * a.H * a.M + m;
+            int h = 0;
+            for (; h + 8 <= a.H; h += 8) {
+                float v[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) v[u] = p[(int64_t)(h + u) * a.M];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) acc += v[u];
+            }
+            for (; h < a.H; ++h) acc += p[(int64_t)h * a.M];
+        }
+        a.scores[(int64_t)b * a.M + m] = acc / ((float)a.H * (float)n_q);
+    }
+    select_block<1, 1024>(a.scores + (int64_t)b * a.M, a.M, a.R, a.kept + (int64_t)b * a.R, nullptr);
+}
+
 // Key splits of the two-pass matrix-core kernel: up to 256 workgroups in all (more brought
 // nothing in timing sweeps over 1..16 sequences of 700..3000 keys, and cost time with 128
 // scoring rows, where a compute unit holds one workgroup), at least two 32-key chunks per split.
@@ -486,8 +516,14 @@ static hipError_t launch_score_mfma_rows(const ScoreArgs& a, hipStream_t s) {
 }
 
 hipError_t launch_score_reduce(const ScoreArgs& a, hipStream_t s) {
+    if (a.kept && a.R > 0 && a.M <= kFusedSelectMaxM) {
+        hipLaunchKernelGGL(score_reduce_select_kernel, dim3(a.B), dim3(1024), 0, s, a);
+        return hipGetLastError();
+    }
     hipLaunchKernelGGL(score_reduce_kernel, dim3((a.M + 255) / 256, a.B), dim3(256), 0, s, a);
-    return hipGetLastError();
+    hipError_t e = hipGetLastError();
+    if (e == hipSuccess && a.kept && a.R > 0) e = launch_select(a.scores, a.B, a.M, a.R, a.kept, s);
+    return e;
 }
 
 hipError_t launch_score(const ScoreArgs& a, int dtype, hipStream_t s) {

@@ -288,6 +288,9 @@ struct ScoreArgs {
     int32_t n_q_max, n_tot_max, B, H, d_h, v_start, M, causal;   // H: query heads = group * k.H
     int32_t group = 1;   // query heads per key head (1: multi-head attention)
     float scale;
+    // tw_ttp_score_select: the head reduction also keeps the R best of every row (kept [B][R])
+    int32_t* kept = nullptr;
+    int32_t R = 0;
 };
 int score_key_splits(int B, int H, int n_tot_max);
 size_t score_workspace_bytes(int B, int H, int n_q_max, int n_tot_max);

@@ -77,6 +77,12 @@ class DeviceWorkload:
         tw.ttp_score(self.q_sel, self.k_score_view, self.n_q, self.q_pos0, self.n_tot, self.n_tot_max,
                      0, cfg.M, cfg.scale, True, self.scores, self.score_ws)
 
+    def run_score_select(self) -> None:
+        """Score and top-R keep in one call (the head reduction and the select share a launch)."""
+        cfg = self.cfg
+        tw.ttp_score_select(self.q_sel, self.k_score_view, self.n_q, self.q_pos0, self.n_tot, self.n_tot_max,
+                            0, cfg.M, cfg.scale, True, self.scores, cfg.R, self.kept, self.score_ws)
+
     def run_select(self) -> None:
         tw.ttp_select(self.scores, self.cfg.R, self.kept)
 
@@ -102,8 +108,9 @@ class DeviceWorkload:
     def step(self) -> None:
         """One pass of the whole path: score -> select -> compact -> verify -> accept."""
         if self.has_score:
-            self.run_score()
-        self.run_select()
+            self.run_score_select()
+        else:
+            self.run_select()
         if self.compact_src:
             self.run_compact()
         self.run_verify()
@@ -119,8 +126,9 @@ class DeviceWorkload:
             self.run_verify()
             self.run_accept()
         if self.has_score:
-            self.run_score()
-        self.run_select()
+            self.run_score_select()
+        else:
+            self.run_select()
         if self.compact_src:
             self.run_compact()
         cur.wait_stream(side)

@@ -828,6 +828,43 @@ def _check_score(tw, dtype, H, d_h, M, v0, n_text, n_q, causal, q_std=1.0, seed=
     assert torch.equal(again, scores)          # fixed summation order
 
 
+@pytest.mark.parametrize("M,R,n_text,n_q", [(576, 64, [64, 40, 64, 9, 33], [64, 40, 64, 9, 33]),
+                                            (30, 7, [5, 9, 2], [5, 9, 2]),
+                                            (1000, 1, [16, 16], [16, 16]),
+                                            (640, 640, [8], [8]),
+                                            (641, 0, [8], [8]),
+                                            (576, 100, [128, 70], [128, 70]),
+                                            (2880, 320, [128, 128], [16, 16])])
+def test_score_select_in_one_call_equals_the_two_calls(tw, M, R, n_text, n_q):
+    # the launch that adds the heads also keeps the R best (rows up to 1024 scores; longer rows take the
+    # separate select inside the call): scores and kept are bit-identical to tw_ttp_score + tw_ttp_select,
+    # and kept is the oracle's selection on those scores
+    H, d_h, v0, B = 8, 128, 0, len(n_text)
+    n_tot = [v0 + M + n for n in n_text]
+    off, acc = [], 0
+    for n in n_tot:
+        off.append(acc)
+        acc += n
+    q = W.normal(31, 1, (B, max(n_q), H, d_h), 1.0, torch.bfloat16).to(DEV)
+    kd, ro = W.normal(31, 2, (acc, H, d_h), 1.0, torch.bfloat16).to(DEV), _i32(off)
+    view = tw.kv_view(kd, row_off=ro)
+    pos0 = _i32([nt - nq for nt, nq in zip(n_tot, n_q)])
+    ws = torch.empty(tw.workspace_bytes(tw.TW_CALL_TTP_SCORE, B, max(n_q), H, d_h, max(n_tot)) // 4,
+                     dtype=torch.float32, device=DEV)
+    sc_a = torch.full((B, M), float("nan"), dtype=torch.float32, device=DEV)
+    sc_b = torch.full_like(sc_a, float("nan"))
+    kept_a = torch.full((B, max(R, 1)), -5, dtype=torch.int32, device=DEV)[:, :R].contiguous()
+    kept_b = torch.full_like(kept_a, -6)
+    scale = 1 / math.sqrt(d_h)
+    tw.ttp_score(q, view, _i32(n_q), pos0, _i32(n_tot), max(n_tot), v0, M, scale, True, sc_a, ws)
+    tw.ttp_select(sc_a, R, kept_a)
+    tw.ttp_score_select(q, view, _i32(n_q), pos0, _i32(n_tot), max(n_tot), v0, M, scale, True, sc_b, R, kept_b, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(sc_a, sc_b) and torch.equal(kept_a, kept_b)
+    if R > 0:
+        assert torch.equal(kept_b.cpu(), oracle.ttp_select(sc_b.cpu(), R))
+
+
 def test_score_key_splits(tw):
     # few (sequence, head) pairs and long sequences: the keys are split over workgroups (a row
     # statistics launch, then a weights launch that merges them).  Ragged lengths leave some key
