@@ -36,6 +36,16 @@ def verify_bytes(cfg, w):
     return total
 
 
+def verify_sources_hash():
+    """sha256 over the sources the verification kernel is built from; printed with --sources-hash for
+    the profile summaries, which record it."""
+    import hashlib
+    h = hashlib.sha256()
+    for f in ("tree_verify_mfma.hip", "twig_internal.h", "index_math.h", "mfma_util.h"):
+        h.update(open(os.path.join(ROOT, "paper_2503_14075_amd", "csrc", f), "rb").read())
+    return h.hexdigest()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -53,7 +63,11 @@ def main():
                     help="replays of the HIP-graph leg (0 = skip)")
     ap.add_argument("--single-iters", type=int, default=200,
                     help="launches of the single-sequence latency leg (0 = skip)")
+    ap.add_argument("--sources-hash", action="store_true", help="print the hash of the verification kernel's sources and exit")
     args = ap.parse_args()
+    if args.sources_hash:
+        print(verify_sources_hash())
+        return
     if args.gpus != 1:
         print("bench.py: this build is single-GPU; run with --gpus 1 (no multi-GPU path exists)",
               file=sys.stderr)
@@ -247,11 +261,28 @@ def main():
     if args.other_configs:
         flush_a = torch.empty(1 << 29, dtype=torch.bfloat16, device=dev)
         flush_b = torch.empty_like(flush_a)
-        for name in ("cfg2_p0", "cfg2_p256", "cfg2_p1024", "cfg3", "cfg4"):
-            wo = W.make_workload(W.CONFIGS[name], device=dev, with_compact=False, with_score=False)
+        import dataclasses
+        # the bench batch again with the paper's default tree: N_max = 60 candidates + the root (App. A)
+        t61 = dataclasses.replace(W.replicate(W.CONFIGS["cfg1"], args.batch), name=f"cfg1_T61x{args.batch}", T=61,
+                                  tree=("random", 6))
+        named = [(n, W.CONFIGS[n]) for n in ("cfg2_p0", "cfg2_p256", "cfg2_p1024", "cfg3", "cfg4")] + [(t61.name, t61)]
+        for name, ocfg in named:
+            wo = W.make_workload(ocfg, device=dev, with_compact=False, with_score=False)
             do = runner.DeviceWorkload(wo, dev)
             for _ in range(2):
                 do.run_verify()
+            # back-to-back launches first (caches and address translation warm from the launch before:
+            # what a decode loop sees), then cold ones
+            evw = []
+            for _ in range(10):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                do.run_verify()
+                e1.record()
+                evw.append((e0, e1))
+            torch.cuda.synchronize()
+            tw_ = sorted(x.elapsed_time(y) for x, y in evw)
+            warm_med = tw_[len(tw_) // 2]
             evs = []
             for _ in range(10):
                 flush_b.copy_(flush_a)
@@ -267,6 +298,8 @@ def main():
             others[name] = {"kernel_us_median": med * 1e3, "algorithmic_MB": nbytes / 1e6,
                             "GBps": nbytes / (med * 1e-3) / 1e9,
                             "frac_of_8TBps": nbytes / (med * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                            "kernel_us_median_back_to_back": warm_med * 1e3,
+                            "frac_of_8TBps_back_to_back": nbytes / (warm_med * 1e-3) / 1e9 / HBM_PEAK_GBS,
                             "tree_tokens": sum(wo.n_nodes),
                             "tokens_per_s": sum(wo.n_nodes) / (med * 1e-3),
                             # one launch covers every layer cache of the config: tree rows of one
@@ -401,8 +434,8 @@ def main():
         n_done, t_cpu = 0, 0.0
         # sequences are taken in order and the batch is walked again until the time budget is used,
         # so the sample is 10-15 s of CPU work whatever the speed of the host
-        while t_cpu < args.cpu_seconds:
-            b = n_done % cfg.B
+        def one_sequence(b):
+            """Seconds the oracle takes for the whole path of sequence b (inputs copied out beforehand)."""
             n_tot, off = w.n_tot[b], w.score_row_off[b]
             q_sel = w.q_sel[b:b + 1].cpu()
             k_sc = w.k_score[off:off + n_tot].cpu()
@@ -419,20 +452,17 @@ def main():
             oracle.tree_verify_attn(qt, kp, vp, [w.ctx_len[b]], [w.n_nodes[b]], [w.parent[b]], cfg.scale,
                                     row_off=[0])
             oracle.tree_accept([w.draft[b]], [w.argmax[b]], [w.tree_seq[b]], [cfg.T])
-            t_cpu += time.perf_counter() - s
+            return time.perf_counter() - s
+
+        while t_cpu < args.cpu_seconds:
+            t_cpu += one_sequence(n_done % cfg.B)
             n_done += 1
-        # the same oracle on one thread, a quarter of the budget
+        # the same whole path with the oracle held to one thread, a quarter of the budget
         n_thr = oracle.max_threads()
         oracle.set_threads(1)
         n1, t1_cpu = 0, 0.0
         while t1_cpu < args.cpu_seconds / 4:
-            b = n1 % cfg.B
-            r0, nr = w.row_off[b], w.ctx_len[b] + w.n_nodes[b]
-            kp, vp, qt = w.k_pool[r0:r0 + nr].cpu(), w.v_pool[r0:r0 + nr].cpu(), w.q_tree[b:b + 1].cpu()
-            s = time.perf_counter()
-            oracle.tree_verify_attn(qt, kp, vp, [w.ctx_len[b]], [w.n_nodes[b]], [w.parent[b]], cfg.scale,
-                                    row_off=[0])
-            t1_cpu += time.perf_counter() - s
+            t1_cpu += one_sequence(n1 % cfg.B)
             n1 += 1
         oracle.set_threads(n_thr)
         model = ""
@@ -445,18 +475,23 @@ def main():
             pass
         cpu = {"value": n_done * cfg.T / t_cpu, "unit": "tokens/s", "cores": n_thr,
                "kind": "oracle", "cpu_model": model,
-               "verify_only_single_thread_tokens_per_s": n1 * cfg.T / t1_cpu,
+               "single_thread_tokens_per_s": n1 * cfg.T / t1_cpu,
+               "single_thread_sample": f"whole path on {n1} sequences, one thread ({t1_cpu:.1f} s)",
                "sample": f"whole path on {n_done} sequences drawn in order (with wrap-around) from the "
                          f"{cfg.B} of the same batch ({t_cpu:.1f} s of fp64 C, OpenMP over heads/rows)"}
 
-    # HBM bytes per launch from the committed rocprofv3 counter summary (same workload only)
-    traffic = None
+    # HBM bytes per launch: taken from the committed rocprofv3 counter summary, and only when that summary
+    # was made from the very kernel sources of this build (it records their hash) and the same batch;
+    # otherwise null -- the counters are not measured inside this run
+    traffic, traffic_src = None, None
     tpath = os.path.join(ROOT, "profiles", "verify_mfma_cfg1x128_hbm_traffic.md")
     if os.path.exists(tpath):
         rec = dict(ln.split("=", 1) for ln in open(tpath) if ln.count("=") == 1 and ln[0].isalpha())
         rec = {k.strip(): v.strip() for k, v in rec.items()}
-        if rec.get("batch") == str(args.batch) and "hbm_bytes_per_launch" in rec:
+        if (rec.get("batch") == str(args.batch) and "hbm_bytes_per_launch" in rec
+                and rec.get("verify_kernel_sources_sha256") == verify_sources_hash()):
             traffic = int(rec["hbm_bytes_per_launch"])
+            traffic_src = "profiles/verify_mfma_cfg1x128_hbm_traffic.md (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, same sources)"
 
     out = {
         "metric": "tree-verify attention tokens/s (whole hot-path step), LLaVA-7B shape",
@@ -468,7 +503,8 @@ def main():
         "config": {"workload": f"cfg1 LLaVA-1.5-7B shape x {cfg.B} independent sequences per step: "
                                f"M=576 N=64 R=64 C=256 T=26 H=32 d_h=128, one layer",
                    "batch": cfg.B, "tree_tokens_per_step": tokens},
-        "roofline": {"bound": "hbm", "kernel": "verify_mfma_kernel<128,1,contiguous>",
+        "roofline": {"bound": "hbm", "kernel": "void tw::verify_mfma_kernel<128, false, true>(tw::VerifyArgs)",
+                     "traffic_source": traffic_src,
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "algorithmic_bytes_per_launch": vbytes, "kernel_ms_avg": ker_avg,

@@ -78,8 +78,35 @@ size_t verify_workspace_bytes(int B, int H, int T_max, int d_h, int max_rows) {
 }  // namespace tw
 
 #ifdef TW_TRACE
+// Diagnostic build only (build.py --trace): the timeline buffer of the verification kernels, and a bare
+// read-only stream over `bytes` of memory (16-byte non-temporal loads, eight in flight per lane, `wgs`
+// workgroups of 256 lanes) -- what the memory system gives a kernel that does nothing but read.
 static unsigned long long* g_trace = nullptr;
 extern "C" TW_API void tw_debug_set_trace(void* p) { g_trace = (unsigned long long*)p; }
+
+typedef __attribute__((ext_vector_type(4))) unsigned int dbg_u32x4;
+__global__ __launch_bounds__(256) void debug_stream_read_kernel(const dbg_u32x4* __restrict__ src, size_t n16,
+                                                                unsigned* sink) {
+    const size_t stride = (size_t)gridDim.x * 256;
+    dbg_u32x4 acc = {0u, 0u, 0u, 0u};
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += 8 * stride) {
+        dbg_u32x4 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const size_t j = i + u * stride;
+            v[u] = __builtin_nontemporal_load(src + (j < n16 ? j : n16 - 1));
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc ^= v[u];
+    }
+    if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x12345678u) sink[0] = 1u;   // never true in practice: keeps the loads
+}
+extern "C" TW_API int32_t tw_debug_stream_read(const void* src, size_t bytes, int32_t wgs, void* sink, void* stream) {
+    if (!src || !sink || bytes < 16 || wgs < 1) return TW_ERR_INVALID_ARG;
+    hipLaunchKernelGGL(debug_stream_read_kernel, dim3(wgs), dim3(256), 0, (hipStream_t)stream,
+                       (const dbg_u32x4*)src, bytes / 16, (unsigned*)sink);
+    return hipGetLastError() == hipSuccess ? TW_OK : TW_ERR_LAUNCH;
+}
 #endif
 
 extern "C" {
