@@ -180,6 +180,36 @@ def test_verify_split_cache_single_sequence(tw):
         check_verify(tw, q, k, v, ctx, [T], trees, 1 / math.sqrt(d_h), row_off=off)
 
 
+def test_verify_workspace_serves_launch_after_launch(tw):
+    # One workspace, zeroed once, serves launches of different shapes one after another: the arrival
+    # counters at its start are back at zero after every launch, and whatever else it holds does not
+    # matter (the partial results behind the counters are overwritten with NaNs between the calls).
+    H, d_h = 32, 128
+    scale = 1 / math.sqrt(d_h)
+    cases = [(3, [2600, 300, 1500], 40), (1, [900], 26), (2, [700, 2050], 64), (1, [900], 26)]
+    need = [tw.workspace_bytes(tw.TW_CALL_TREE_VERIFY_ATTN, B, T, H, d_h, max(ctx) + T) for B, ctx, T in cases]
+    assert min(need) > 0
+    shared = torch.zeros(max(need) // 4, dtype=torch.float32, device=DEV)
+    for i, (B, ctx, T) in enumerate(cases):
+        trees = [W.random_parent_tree(W.HostRng(70 + i, b), T, 6) for b in range(B)]
+        q, k, v, off = make_case(71 + i, B, H, d_h, ctx, T, torch.bfloat16, trees)
+        qd, kd, vd, ro = q.to(DEV), k.to(DEV), v.to(DEV), _i32(off)
+        kv, vv = tw.kv_view(kd, ro), tw.kv_view(vd, ro)
+        args = (_i32(ctx), max(ctx), _i32(trees), _i32([T] * B), scale)
+        fresh = torch.zeros(need[i] // 4, dtype=torch.float32, device=DEV)
+        want = torch.full((B, T, H, d_h), float("nan"), dtype=torch.float32, device=DEV)
+        got = torch.full_like(want, float("nan"))
+        tw.tree_verify_attn(qd, kv, vv, *args, want, fresh)
+        tw.tree_verify_attn(qd, kv, vv, *args, got, shared)
+        torch.cuda.synchronize()
+        assert torch.equal(got, want) and torch.isfinite(got).all()
+        n_counters = (B * H * 4 + 255) // 256 * 64
+        assert int(shared.view(torch.int32)[:n_counters].abs().max()) == 0
+        shared[n_counters:] = float("nan")
+        ref = oracle.tree_verify_attn(q, k, v, ctx, [T] * B, trees, scale, row_off=off)
+        assert float((got.cpu().double() - ref).abs().max()) <= ATTN_TOL
+
+
 def test_verify_and_score_long_context_at_the_split_caps(tw):
     # one sequence, four heads, 17000 rows: the row split of verification reaches its cap of 64
     # workgroups per head, the key split of the score its cap of 32
