@@ -81,11 +81,13 @@ struct RsCfg {
     static constexpr int kRowsPerLoad = 64 / kPieces;
     static constexpr int kLoads = kRsChunk / kRowsPerLoad;   // loads per chunk (per lane)
     // LDS layout (bytes)
+    static constexpr int kQBytes = kRows * kStride;
     static constexpr int kOffQ = 0;
-    static constexpr int kOffStage = kOffQ + kRows * kStride;
+    static constexpr int kOffStage = kOffQ + 2 * kQBytes;
     static constexpr int kWaveStage = kRsChunk * kStride;     // one whole chunk per wavefront
     static constexpr int kOffPart = kOffStage + kRsWaves * kWaveStage;
-    static constexpr int kLds = kOffPart + kRsWaves * kRows * 2 * 4;
+    static constexpr int kPartBytes = kRsWaves * kRows * 2 * 4;
+    static constexpr int kLds = kOffPart + 2 * kPartBytes;
 };
 
 template <int DH, int NB>
@@ -97,9 +99,7 @@ __global__ __launch_bounds__(kRsThreads, 2) void score_resident_kernel(ScoreArgs
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int g = lane >> 5, li = lane & 31;
     const int ld_row = lane / Cf::kPieces, ld_col = lane % Cf::kPieces;
-    unsigned char* s_q = lds + Cf::kOffQ;                                 // Q rows of the pair
     unsigned char* stage = lds + Cf::kOffStage + wave * Cf::kWaveStage;   // one K chunk of this wavefront
-    float* s_part = (float*)(lds + Cf::kOffPart);    // [wave][row][2]: maximum and sum of each wavefront
 
     const uint32_t pool_stride = (uint32_t)(a.k.H * Cf::kRowB);   // a cache row holds the key heads
     const int64_t last_pool_row = a.k.pool_rows - 1;
@@ -174,7 +174,8 @@ __global__ __launch_bounds__(kRsThreads, 2) void score_resident_kernel(ScoreArgs
             qn[u] = __builtin_nontemporal_load((const u32x4*)(sbase + (uint32_t)(ic * a.H * DH + 8 * col)));
         }
     };
-    auto store_q = [&](const PairInfo& p) {
+    auto store_q = [&](const PairInfo& p, int buf) {
+        unsigned char* s_q = lds + Cf::kOffQ + buf * Cf::kQBytes;
         const int t = fresh_tid();
 #pragma unroll
         for (int u = 0; u < kQLoads; ++u) {
@@ -196,9 +197,12 @@ __global__ __launch_bounds__(kRsThreads, 2) void score_resident_kernel(ScoreArgs
     issue_chunk(cur, 0, 0, true);
     issue_chunk(cur, 1, 1, true);
     issue_q(cur);
-    store_q(cur);
+    store_q(cur, 0);
+    __syncthreads();
+    int par = 0;
     while (pair < n_pairs) {
-        __syncthreads();   // Q rows of this pair are in LDS; every wavefront is done with the previous pair
+        const unsigned char* s_q = lds + Cf::kOffQ + par * Cf::kQBytes;
+        float* s_part = (float*)(lds + Cf::kOffPart + par * Cf::kPartBytes);
         const int next = pair + gridDim.x;
         const bool has_next = next < n_pairs;
         const PairInfo nxt = pair_info(has_next ? next : pair);
@@ -291,8 +295,8 @@ __global__ __launch_bounds__(kRsThreads, 2) void score_resident_kernel(ScoreArgs
                 s_part[(wave * Cf::kRows + 32 * nb + t1) * 2 + 1] = l;
             }
         }
-        __syncthreads();   // row statistics of all wavefronts are complete
-        store_q(nxt);      // every wavefront is past its last read of the Q rows
+        store_q(nxt, par ^ 1);
+        __syncthreads();   // row statistics of all wavefronts are complete; next pair's Q rows in place
 
         // From here to the end of the pair a wavefront works on its own registers only.
         // ---- merge: factor 2^(own max - row max) / row sum for the lane's rows ----------------------
@@ -336,6 +340,7 @@ __global__ __launch_bounds__(kRsThreads, 2) void score_resident_kernel(ScoreArgs
         }
         pair = next;
         cur = nxt;
+        par ^= 1;
     }
 }
 
