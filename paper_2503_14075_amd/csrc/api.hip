@@ -7,6 +7,10 @@
 
 using namespace tw;
 
+#ifdef TW_TRACE
+static unsigned long long* g_trace = nullptr;   // timeline buffer of the diagnostic build (tw_debug_set_trace)
+#endif
+
 namespace {
 
 bool dh_ok(int d_h) { return d_h >= 8 && d_h <= 128 && d_h % 8 == 0; }
@@ -81,7 +85,6 @@ size_t verify_workspace_bytes(int B, int H, int T_max, int d_h, int max_rows) {
 // Diagnostic build only (build.py --trace): the timeline buffer of the verification kernels, and a bare
 // read-only stream over `bytes` of memory (16-byte non-temporal loads, eight in flight per lane, `wgs`
 // workgroups of 256 lanes) -- what the memory system gives a kernel that does nothing but read.
-static unsigned long long* g_trace = nullptr;
 extern "C" TW_API void tw_debug_set_trace(void* p) { g_trace = (unsigned long long*)p; }
 
 typedef __attribute__((ext_vector_type(4))) unsigned int dbg_u32x4;
@@ -191,6 +194,10 @@ static int32_t score_impl(const void* q_sel, int32_t n_q_max, const int32_t* n_q
     a.scale = scale;
     a.kept = kept;
     a.R = R;
+#ifdef TW_TRACE
+    a.trace = g_trace;
+    if (const char* d = getenv("TW_SCORE_DRY")) a.dry = atoi(d);
+#endif
     return launch_score(a, k->dtype, (hipStream_t)stream) == hipSuccess ? TW_OK : TW_ERR_LAUNCH;
 }
 

@@ -10,8 +10,10 @@
 //           logits of the wavefront's three chunks stay in its registers as fp32
 //           accumulator tiles (lane = scoring row, registers = keys).  Row maximum
 //           over the wavefront's keys, exponentials in place, row sum.
-//   merge   the eight wavefronts publish (max, sum) per row; every lane turns
-//           them into the factor 2^(own max - row max) / row sum of its rows.
+//   merge   the eight wavefronts publish (max, sum) per row; one workgroup barrier
+//           (the only one of the pair: the Q rows and the statistics area are
+//           double-buffered); every lane turns the statistics into the factor
+//           2^(own max - row max) / row sum of its rows.
 //   pass 2  each wavefront, for its own chunks of the visual span: weights =
 //           exponentials * factor, summed over the scoring rows -- over the row
 //           blocks inside the lane, over the 32 lanes by a reduce-scatter of
@@ -26,6 +28,23 @@
 #include "twig_internal.h"
 
 namespace tw {
+
+// Diagnostic build: lane 0 of every wavefront records the 100 MHz wall clock at eight points of each of
+// its first 16 pairs: [workgroup][wavefront][pair][mark].
+#ifdef TW_TRACE
+#define RS_MARK(slot)                                                                                  \
+    do {                                                                                               \
+        asm volatile("" ::: "memory");                                                                 \
+        const unsigned long long t_ = __builtin_amdgcn_s_memrealtime();                                \
+        if (a.trace && lane == 0 && iter < 16)                                                         \
+            a.trace[(((size_t)blockIdx.x * kRsWaves + wave) * 16 + iter) * 8 + (slot)] = t_;           \
+        asm volatile("" ::: "memory");                                                                 \
+    } while (0)
+#define RS_DRY(level) (a.dry >= (level))
+#else
+#define RS_MARK(slot)
+#define RS_DRY(level) false
+#endif
 
 constexpr int kRsWaves = 8;
 constexpr int kRsThreads = kRsWaves * 64;
@@ -200,13 +219,17 @@ __global__ __launch_bounds__(kRsThreads, 2) void score_resident_kernel(ScoreArgs
     store_q(cur, 0);
     __syncthreads();
     int par = 0;
+#ifdef TW_TRACE
+    int iter = 0;
+#endif
     while (pair < n_pairs) {
+        RS_MARK(0);   // top of the pair
         const unsigned char* s_q = lds + Cf::kOffQ + par * Cf::kQBytes;
         float* s_part = (float*)(lds + Cf::kOffPart + par * Cf::kPartBytes);
         const int next = pair + gridDim.x;
         const bool has_next = next < n_pairs;
         const PairInfo nxt = pair_info(has_next ? next : pair);
-        issue_q(nxt);
+        if (!RS_DRY(4)) issue_q(nxt);
         const int n_q = cur.n_q, n_tot = cur.n_tot, pos0 = cur.pos0;
         const int vis_all = a.causal ? min(pos0 + 1, n_tot) : n_tot;   // keys visible to every row
 
@@ -230,9 +253,12 @@ __global__ __launch_bounds__(kRsThreads, 2) void score_resident_kernel(ScoreArgs
             }
             // the slot's registers are free again: chunk 2 of this pair after chunk 0, then chunks 1
             // and 0 of the next pair
+            if (c == 0) RS_MARK(1);        // chunk 0 has arrived and is staged
+            else if (c == 1) RS_MARK(3);   // chunk 1
+            else RS_MARK(4);               // chunk 2
             if (c == 0) issue_chunk(cur, 2, 0, true);
             else issue_chunk(nxt, c == 1 ? 1 : 0, slot, has_next);
-            if (live) {
+            if (live && !RS_DRY(1)) {
                 lds_sync();
                 // A operand: lane (j, g) takes K[key base + j][16dc + 8g .. +7]
                 u32x4 kf[Cf::kDC];
@@ -264,6 +290,7 @@ __global__ __launch_bounds__(kRsThreads, 2) void score_resident_kernel(ScoreArgs
                     row_m[nb] = fmaxf(row_m[nb], mx);
                     st[c][nb] = s;
                 }
+                if (c == 0) RS_MARK(2);   // logits of chunk 0 done
             } else {
 #pragma unroll
                 for (int nb = 0; nb < NB; ++nb)
@@ -274,8 +301,13 @@ __global__ __launch_bounds__(kRsThreads, 2) void score_resident_kernel(ScoreArgs
         // ---- exponentials in place, relative to the wavefront's own row maximum; publish (max, sum) ----
         // scale > 0: the maximum of the scaled logits is the scaled maximum.  Base-2 units throughout.
         float own_m[NB];
+        RS_MARK(5);   // pass 1 done
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
+            if (RS_DRY(2)) {
+                own_m[nb] = 0.f;
+                continue;
+            }
             const float m = fmaxf(row_m[nb], __shfl_xor(row_m[nb], 32, 64)) * sl2;
             const float m_safe = m == -INFINITY ? 0.f : m;
             float l = 0.f;
@@ -295,8 +327,10 @@ __global__ __launch_bounds__(kRsThreads, 2) void score_resident_kernel(ScoreArgs
                 s_part[(wave * Cf::kRows + 32 * nb + t1) * 2 + 1] = l;
             }
         }
-        store_q(nxt, par ^ 1);
-        __syncthreads();   // row statistics of all wavefronts are complete; next pair's Q rows in place
+        if (!RS_DRY(4)) store_q(nxt, par ^ 1);
+        RS_MARK(6);   // exponentials done, statistics published
+        __syncthreads();
+        RS_MARK(7);   // through the barrier   // row statistics of all wavefronts are complete; next pair's Q rows in place
 
         // From here to the end of the pair a wavefront works on its own registers only.
         // ---- merge: factor 2^(own max - row max) / row sum for the lane's rows ----------------------
@@ -322,7 +356,7 @@ __global__ __launch_bounds__(kRsThreads, 2) void score_resident_kernel(ScoreArgs
 #pragma unroll
         for (int c = 0; c < kRsCpw; ++c) {
             const int chunk = wave + kRsWaves * c, base = kRsChunk * chunk;
-            if (base < span_end && base + kRsChunk > a.v_start) {
+            if (base < span_end && base + kRsChunk > a.v_start && !RS_DRY(3)) {
                 floatx16 col;
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
@@ -341,6 +375,9 @@ __global__ __launch_bounds__(kRsThreads, 2) void score_resident_kernel(ScoreArgs
         pair = next;
         cur = nxt;
         par ^= 1;
+#ifdef TW_TRACE
+        ++iter;
+#endif
     }
 }
 

@@ -291,6 +291,13 @@ struct ScoreArgs {
     // tw_ttp_score_select: the head reduction also keeps the R best of every row (kept [B][R])
     int32_t* kept = nullptr;
     int32_t R = 0;
+#ifdef TW_TRACE
+    // diagnostic build: per-wavefront timestamps of the register-resident kernel, and how much of its
+    // work is switched off at run time (0 nothing; 1 the matrix products and row maxima; 2 also the
+    // exponentials; 3 also the column sums; 4 also the Q traffic: the bare K stream and its staging)
+    unsigned long long* trace = nullptr;
+    int32_t dry = 0;
+#endif
 };
 int score_key_splits(int B, int H, int n_tot_max);
 size_t score_workspace_bytes(int B, int H, int n_q_max, int n_tot_max);
