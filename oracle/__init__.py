@@ -176,6 +176,30 @@ def tree_accept(draft, argmax, parent, n_nodes: Sequence[int]):
     return n_acc, path, bonus
 
 
+def chain_draft_len(prob, theta: float, delta: int) -> int:
+    """Tokens drafted by one sequence under the early exit (prob: fp32 [delta] or None)."""
+    if prob is None:
+        rc = lib().orc_chain_draft_len(None, ctypes.c_float(theta), int(delta))
+    else:
+        pr = torch.as_tensor(prob, dtype=torch.float32).contiguous()
+        if pr.numel() != delta:
+            raise ValueError("chain_draft_len: one probability per draft position")
+        rc = lib().orc_chain_draft_len(_p(pr), ctypes.c_float(theta), int(delta))
+    _check(0 if rc >= 0 else rc, "chain_draft_len")
+    return int(rc)
+
+
+def chain_accept(draft, argmax, n_draft: int):
+    """(n_acc, next_token) of one sequence; draft[0] is the last accepted token."""
+    d, a = _i32(draft), _i32(argmax)
+    if d.numel() <= n_draft or a.numel() <= n_draft:
+        raise ValueError("chain_accept: arrays shorter than the draft")
+    nxt = ctypes.c_int32(0)
+    rc = lib().orc_chain_accept(_p(d), _p(a), int(n_draft), ctypes.byref(nxt))
+    _check(0 if rc >= 0 else rc, "chain_accept")
+    return int(rc), int(nxt.value)
+
+
 def rbar(M: int, K: int, R: int, K_f: int, L: int) -> int:
     return int(lib().orc_rbar(int(M), int(K), int(R), int(K_f), int(L)))
 

@@ -309,6 +309,45 @@ int orc_tree_accept(const int32_t* draft, const int32_t* argmx, const int32_t* p
 }
 
 /*
+ * Sequence-based self-speculative decoding (Sec. 3.1; App. A, SSD paragraph;
+ * Alg. 1), one sequence.
+ *
+ * orc_chain_draft_len: how many tokens the draft model produces.  It stops
+ * after delta tokens, or earlier, right after a token whose probability is
+ * below theta (Alg. 1 tests the token it has just appended, so that token is
+ * part of the draft).  prob may be NULL: no early exit.
+ *
+ * orc_chain_accept: draft[i], i = 1..n_draft, are the draft tokens (draft[0] is
+ * the last accepted token and is not read); argmx[i] is the target model's
+ * prediction for the token after position i.  Accepted are the draft tokens
+ * that match the target's predictions up to the first mismatch; the target's
+ * prediction at that point is the next token.  Returns the number accepted and
+ * stores the next token.
+ */
+int orc_chain_draft_len(const float* prob, float theta, int delta) {
+    if (delta < 1) return -1;
+    if (!prob) return delta;
+    int len = 0;
+    while (len < delta) {
+        const float p = prob[len];
+        ++len;                   /* the token is appended ... */
+        if (p < theta) break;    /* ... then tested */
+    }
+    return len;
+}
+
+int orc_chain_accept(const int32_t* draft, const int32_t* argmx, int n_draft, int32_t* next_token) {
+    if (!draft || !argmx || !next_token || n_draft < 0) return -1;
+    int n = 0;
+    for (int i = 1; i <= n_draft; ++i) {
+        if (draft[i] != argmx[i - 1]) break;
+        n = i;
+    }
+    *next_token = argmx[n];
+    return n;
+}
+
+/*
  * Average number of retained visual tokens with FinalWipe (Sec. 4.2 Eq. 6;
  * Eq. 4 is the case K_f = L), rounded to the nearest integer.
  */

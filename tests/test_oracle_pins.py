@@ -481,6 +481,72 @@ def test_accept_chain_is_longest_matching_prefix_and_special_cases():
 
 
 # ----------------------------------------------------------------------------
+# sequence-based self-speculative decoding (Sec. 3.1; App. A, SSD paragraph; Alg. 1)
+# ----------------------------------------------------------------------------
+def test_chain_draft_length_by_hand():
+    th = 0.6
+    assert oracle.chain_draft_len([0.9, 0.8, 0.7, 0.65, 0.61], th, 5) == 5      # never below the threshold
+    assert oracle.chain_draft_len([0.9, 0.5, 0.9, 0.9, 0.9], th, 5) == 2        # the weak token is the last one kept
+    assert oracle.chain_draft_len([0.1, 0.9, 0.9, 0.9, 0.9], th, 5) == 1
+    assert oracle.chain_draft_len([0.9, 0.9, 0.9, 0.9, 0.1], th, 5) == 5        # delta reached at the same step
+    assert oracle.chain_draft_len([0.6, 0.6, 0.6], 0.6, 3) == 3                 # equal is not below (both fp32)
+    assert oracle.chain_draft_len(None, th, 5) == 5
+    assert oracle.chain_draft_len([0.0], th, 1) == 1
+    with pytest.raises(ValueError):
+        oracle.chain_draft_len(None, th, 0)
+
+
+def test_chain_accept_by_hand_and_against_the_tree_walk():
+    x = 77   # the last accepted token: never read
+    assert oracle.chain_accept([x, 5, 6, 7], [5, 6, 9, 4], 3) == (2, 9)    # third draft token wrong -> target's 9
+    assert oracle.chain_accept([x, 5, 6, 7], [5, 6, 7, 8], 3) == (3, 8)    # all right -> bonus token
+    assert oracle.chain_accept([x, 5, 6, 7], [4, 6, 7, 1], 3) == (0, 4)    # later matches do not count after a miss
+    assert oracle.chain_accept([x, 5, 6, 7], [5, 6, 7, 8], 2) == (2, 7)    # a shorter draft stops at its end
+    assert oracle.chain_accept([x], [3], 0) == (0, 3)
+    # the chain is a tree with parent[i] = i - 1: the exhaustively pinned tree walk gives the same
+    rng = W.HostRng(11, 3)
+    for _ in range(600):
+        T = rng.randint(1, 9)
+        dr = [rng.randint(0, 2) for _ in range(T)]
+        am = [rng.randint(0, 2) for _ in range(T)]
+        n_acc, _, bonus = oracle.tree_accept([dr], [am], [[-1] + list(range(T - 1))], [T])
+        assert oracle.chain_accept(dr, am, T - 1) == (int(n_acc[0]), int(bonus[0]))
+        # and the definition, prefix length by prefix length
+        ks = [k for k in range(T) if all(dr[i] == am[i - 1] for i in range(1, k + 1))]
+        assert oracle.chain_accept(dr, am, T - 1)[0] == max(ks)
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_chain_decoding_reproduces_the_target_model(seed):
+    # Sec. 3.1: self-speculative decoding gives the response of the target model alone.  A toy
+    # deterministic target (next token = a hash of the last three tokens), a draft model that is
+    # the target with mistakes and made-up confidences; draft-then-verify with the two functions
+    # must emit exactly the greedy decoding of the target.
+    rng = W.HostRng(100 + seed, 1)
+    V, delta, theta = 7, 5, 0.6
+    target = lambda toks: (3 * toks[-1] + 5 * toks[-2] + toks[-3] * toks[-1] + seed) % V
+    prompt = [1, 2, 3]
+    want = list(prompt)
+    for _ in range(60):
+        want.append(target(want))
+    got = list(prompt)
+    while len(got) < len(want):
+        ctx, draft, prob = list(got), [], []
+        for _ in range(delta):                       # the draft model runs delta steps; the early exit cuts them
+            t = target(ctx) if rng.uniform() < 0.7 else rng.randint(0, V - 1)
+            draft.append(t)
+            prob.append(rng.uniform())
+            ctx.append(t)
+        n_draft = oracle.chain_draft_len(prob, theta, delta)
+        draft = draft[:n_draft]
+        # one pass of the target over [last accepted token] + draft: prediction after every position
+        am = [target(got + draft[:i]) for i in range(n_draft + 1)]
+        n_acc, nxt = oracle.chain_accept([got[-1]] + draft, am, n_draft)
+        got += draft[:n_acc] + [nxt]
+    assert got[:len(want)] == want
+
+
+# ----------------------------------------------------------------------------
 # the numbers the paper prints (Sec. 4.2 Eq. 6)
 # ----------------------------------------------------------------------------
 def test_rbar_matches_printed_settings():
