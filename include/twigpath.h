@@ -303,6 +303,35 @@ TW_API int32_t tw_tree_accept(const int32_t* draft, const int32_t* argmax, const
                        int32_t* path, int32_t* bonus, void* stream);
 
 /*
+ * Sequence-based self-speculative decoding (Sec. 3.1, "Decoding acceleration via
+ * self-speculation"; App. A, SSD paragraph: delta = 5, theta = 0.6; Alg. 1) as
+ * the chain case of the tree calls: node 0 is the last accepted token, node i
+ * the i-th draft token, parent[i] = i - 1, T_max = delta + 1.
+ *
+ * tw_chain_tree -- the draft model's early exit.  prob [dev] fp32 [B][delta]:
+ * the draft model's probability of its i-th draft token (NULL: no early exit).
+ * Drafting stops after the first token whose probability is below theta (that
+ * token stays in the draft) or after delta tokens:
+ * n_nodes[b] = 1 + min(delta, 1 + first i with prob[b][i] < theta); the
+ * comparison is made in fp32.  parent [dev] int32 [B][delta + 1] receives the
+ * chain (all entries, parent[b][0] = -1).  Both outputs are what
+ * tw_tree_verify_attn and tw_chain_accept take.  1 <= delta < TW_MAX_TREE.
+ *
+ * tw_chain_accept -- draft[b][i] is the token of node i (entry 0 is not read),
+ * argmax[b][i] the target model's prediction for the token after node i.
+ * n_acc[b] = length of the longest prefix of the n_nodes[b] - 1 draft tokens
+ * with draft[b][i] == argmax[b][i - 1]; path[b][j] = j + 1 for j < n_acc[b],
+ * -1 after; bonus[b] = argmax[b][n_acc[b]], the target model's own next token.
+ * Same result as tw_tree_accept on the chain; the outputs are what
+ * tw_kv_commit takes.  All arrays [dev] int32, [B][T_max] or [B].
+ */
+TW_API int32_t tw_chain_tree(const float* prob, float theta, int32_t delta, int32_t B, int32_t* parent,
+                      int32_t* n_nodes, void* stream);
+TW_API int32_t tw_chain_accept(const int32_t* draft, const int32_t* argmax, const int32_t* n_nodes,
+                        int32_t T_max, int32_t B, int32_t* n_acc, int32_t* path, int32_t* bonus,
+                        void* stream);
+
+/*
  * Commit of the accepted path into the KV cache (the step after the acceptance
  * walk in Alg. 2; KV append of Sec. 3.1), so that the next draft-verify
  * iteration can run on the same cache.  For every sequence b and every view

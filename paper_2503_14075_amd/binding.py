@@ -31,7 +31,7 @@ _STATUS = {0: "TW_OK", -1: "TW_ERR_INVALID_ARG", -2: "TW_ERR_UNSUPPORTED", -3: "
 
 EXPORTS = ["tw_version", "tw_workspace_bytes", "tw_ttp_score", "tw_ttp_score_gqa", "tw_ttp_score_select", "tw_ttp_score_phead", "tw_ttp_select", "tw_ttp_compact",
            "tw_ttp_compact_batched",
-           "tw_tree_ancestor_masks", "tw_tree_verify_attn", "tw_tree_verify_attn_gqa", "tw_tree_verify_attn_static", "tw_tree_accept", "tw_kv_commit", "tw_draft_topk", "tw_draft_topk_logits", "tw_draft_expand",
+           "tw_tree_ancestor_masks", "tw_tree_verify_attn", "tw_tree_verify_attn_gqa", "tw_tree_verify_attn_static", "tw_tree_accept", "tw_chain_tree", "tw_chain_accept", "tw_kv_commit", "tw_draft_topk", "tw_draft_topk_logits", "tw_draft_expand",
            "tw_tree_build_workspace_bytes", "tw_tree_build", "tw_validate_tree",
            "tw_rbar"]
 
@@ -80,6 +80,10 @@ _lib.tw_tree_verify_attn_static.argtypes = [_vp, ctypes.POINTER(KvView), ctypes.
                                             _vp, _i32, _i32, _f32, _vp, _i32, _vp]
 _lib.tw_tree_accept.restype = _i32
 _lib.tw_tree_accept.argtypes = [_vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp, _vp, _vp]
+_lib.tw_chain_tree.restype = _i32
+_lib.tw_chain_tree.argtypes = [_vp, _f32, _i32, _i32, _vp, _vp, _vp]
+_lib.tw_chain_accept.restype = _i32
+_lib.tw_chain_accept.argtypes = [_vp, _vp, _vp, _i32, _i32, _vp, _vp, _vp, _vp]
 _lib.tw_kv_commit.restype = _i32
 _lib.tw_kv_commit.argtypes = [_vp, _vp, _i32, ctypes.POINTER(KvView), _i32, _vp, _i32, _vp, _vp]
 _lib.tw_draft_topk.restype = _i32
@@ -249,6 +253,19 @@ def tree_accept(draft: torch.Tensor, argmax: torch.Tensor, parent: torch.Tensor,
     _check("tw_tree_accept", _lib.tw_tree_accept(_ptr(draft), _ptr(argmax), _ptr(parent), _ptr(n_nodes),
                                                  T_max, B, _ptr(n_acc), _ptr(path), _ptr(bonus),
                                                  _stream()))
+
+
+def chain_tree(prob: Optional[torch.Tensor], theta: float, delta: int, parent: torch.Tensor,
+               n_nodes: torch.Tensor) -> None:
+    B = n_nodes.shape[0]
+    _check("tw_chain_tree", _lib.tw_chain_tree(_ptr(prob), theta, delta, B, _ptr(parent), _ptr(n_nodes), _stream()))
+
+
+def chain_accept(draft: torch.Tensor, argmax: torch.Tensor, n_nodes: torch.Tensor, n_acc: torch.Tensor,
+                 path: torch.Tensor, bonus: torch.Tensor) -> None:
+    B, T_max = draft.shape
+    _check("tw_chain_accept", _lib.tw_chain_accept(_ptr(draft), _ptr(argmax), _ptr(n_nodes), T_max, B,
+                                                   _ptr(n_acc), _ptr(path), _ptr(bonus), _stream()))
 
 
 def kv_commit(path: torch.Tensor, n_acc: torch.Tensor, views: Sequence[KvView], ctx_len: torch.Tensor,

@@ -385,6 +385,29 @@ int32_t tw_tree_accept(const int32_t* draft, const int32_t* argmax, const int32_
                : TW_ERR_LAUNCH;
 }
 
+int32_t tw_chain_tree(const float* prob, float theta, int32_t delta, int32_t B, int32_t* parent,
+                      int32_t* n_nodes, void* stream) {
+    if (B < 0 || delta < 1 || !(theta == theta)) return TW_ERR_INVALID_ARG;
+    if (delta >= TW_MAX_TREE) return TW_ERR_UNSUPPORTED;
+    if (B == 0) return TW_OK;
+    if (!parent || !n_nodes) return TW_ERR_INVALID_ARG;
+    return launch_chain_tree(prob, theta, delta, B, parent, n_nodes, (hipStream_t)stream) == hipSuccess
+               ? TW_OK
+               : TW_ERR_LAUNCH;
+}
+
+int32_t tw_chain_accept(const int32_t* draft, const int32_t* argmax, const int32_t* n_nodes, int32_t T_max,
+                        int32_t B, int32_t* n_acc, int32_t* path, int32_t* bonus, void* stream) {
+    if (B < 0 || T_max < 1) return TW_ERR_INVALID_ARG;
+    if (T_max > TW_MAX_TREE) return TW_ERR_UNSUPPORTED;
+    if (B == 0) return TW_OK;
+    if (!draft || !argmax || !n_nodes || !n_acc || !path || !bonus) return TW_ERR_INVALID_ARG;
+    return launch_chain_accept(draft, argmax, n_nodes, T_max, B, n_acc, path, bonus, (hipStream_t)stream) ==
+                   hipSuccess
+               ? TW_OK
+               : TW_ERR_LAUNCH;
+}
+
 int32_t tw_kv_commit(const int32_t* path, const int32_t* n_acc, int32_t T_max, const tw_kv_view* views,
                      int32_t n_views, const int32_t* ctx_len, int32_t B, int32_t* new_ctx_len,
                      void* stream) {

@@ -383,6 +383,10 @@ struct CommitArgs {
 };
 hipError_t launch_kv_commit(const CommitArgs& a, int n_views, int B, size_t max_row_bytes, hipStream_t s);
 
+hipError_t launch_chain_tree(const float* prob, float theta, int delta, int B, int32_t* parent, int32_t* n_nodes,
+                             hipStream_t s);
+hipError_t launch_chain_accept(const int32_t* draft, const int32_t* argmx, const int32_t* n_nodes, int T_max, int B,
+                               int32_t* n_acc, int32_t* path, int32_t* bonus, hipStream_t s);
 hipError_t launch_ancestor_masks(const int32_t* parent, const int32_t* n_nodes, int T_max, int B,
                                  uint64_t* masks, hipStream_t s);
 hipError_t launch_accept(const int32_t* draft, const int32_t* argmax, const int32_t* parent,

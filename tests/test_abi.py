@@ -88,6 +88,15 @@ def test_argument_validation_without_launch():
     assert lib.tw_tree_accept(P, P, P, P, 65, 1, P, P, P, None) == tw.TW_ERR_UNSUPPORTED
     assert lib.tw_tree_accept(P, P, P, P, 0, 1, P, P, P, None) == tw.TW_ERR_INVALID_ARG
     assert lib.tw_tree_accept(P, None, P, P, 8, 1, P, P, P, None) == tw.TW_ERR_INVALID_ARG
+    assert lib.tw_chain_tree(P, 0.6, 0, 1, P, P, None) == tw.TW_ERR_INVALID_ARG
+    assert lib.tw_chain_tree(P, float("nan"), 5, 1, P, P, None) == tw.TW_ERR_INVALID_ARG
+    assert lib.tw_chain_tree(P, 0.6, 64, 1, P, P, None) == tw.TW_ERR_UNSUPPORTED     # delta + 1 nodes > 64
+    assert lib.tw_chain_tree(P, 0.6, 5, 1, None, P, None) == tw.TW_ERR_INVALID_ARG
+    assert lib.tw_chain_tree(P, 0.6, 5, 0, None, None, None) == tw.TW_OK
+    assert lib.tw_chain_accept(P, P, P, 65, 1, P, P, P, None) == tw.TW_ERR_UNSUPPORTED
+    assert lib.tw_chain_accept(P, P, P, 0, 1, P, P, P, None) == tw.TW_ERR_INVALID_ARG
+    assert lib.tw_chain_accept(P, None, P, 6, 1, P, P, P, None) == tw.TW_ERR_INVALID_ARG
+    assert lib.tw_chain_accept(P, P, P, 6, 0, P, P, P, None) == tw.TW_OK
     assert lib.tw_tree_ancestor_masks(P, P, 65, 1, P, None) == tw.TW_ERR_UNSUPPORTED
     assert lib.tw_tree_ancestor_masks(P, None, 8, 1, P, None) == tw.TW_ERR_INVALID_ARG
 

@@ -426,6 +426,56 @@ def test_accept_chain_star_and_duplicates(tw):
 
 
 # ----------------------------------------------------------------------------
+# sequence-based self-speculative decoding: the chain calls (bit-exact)
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("delta", [1, 5, 8, 63])
+def test_chain_tree_and_accept_bit_exact(tw, delta):
+    B, T_max, theta = 700, delta + 1, 0.6
+    rng = W.HostRng(900 + delta, 0)
+    # probabilities on both sides of the threshold, some exactly on it (fp32 on both sides)
+    th32 = float(torch.tensor(theta, dtype=torch.float32))
+    prob = [[th32 if rng.randint(0, 9) == 0 else 0.35 + 0.65 * rng.uniform() ** 0.3 for _ in range(delta)]
+            for _ in range(B)]
+    prob_t = torch.tensor(prob, dtype=torch.float32)
+    parent = torch.full((B, T_max), 99, dtype=torch.int32, device=DEV)
+    n_nodes = torch.full((B,), -5, dtype=torch.int32, device=DEV)
+    tw.chain_tree(prob_t.to(DEV), theta, delta, parent, n_nodes)
+    want_nodes = [1 + oracle.chain_draft_len(prob_t[b], theta, delta) for b in range(B)]
+    assert n_nodes.cpu().tolist() == want_nodes
+    assert parent.cpu().tolist() == [list(range(-1, delta))] * B
+    if delta >= 5:
+        assert 1 < min(want_nodes) and len(set(want_nodes)) >= 4
+    # no probabilities: no early exit
+    tw.chain_tree(None, theta, delta, parent, n_nodes)
+    assert n_nodes.cpu().tolist() == [T_max] * B
+    # acceptance on chains of the early-exit lengths, small alphabet so that long prefixes occur
+    draft = [[rng.randint(0, 2) for _ in range(T_max)] for _ in range(B)]
+    argmx = [[d if rng.randint(0, 3) else rng.randint(0, 2) for d in row[1:]] + [rng.randint(0, 2)] for row in draft]
+    d_t, a_t = torch.tensor(draft, dtype=torch.int32, device=DEV), torch.tensor(argmx, dtype=torch.int32, device=DEV)
+    nn_t = torch.tensor(want_nodes, dtype=torch.int32, device=DEV)
+    n_acc = torch.full((B,), -7, dtype=torch.int32, device=DEV)
+    bonus = torch.full((B,), -7, dtype=torch.int32, device=DEV)
+    path = torch.full((B, T_max), 55, dtype=torch.int32, device=DEV)
+    tw.chain_accept(d_t, a_t, nn_t, n_acc, path, bonus)
+    want = [oracle.chain_accept(draft[b], argmx[b], want_nodes[b] - 1) for b in range(B)]
+    assert n_acc.cpu().tolist() == [w[0] for w in want]
+    assert bonus.cpu().tolist() == [w[1] for w in want]
+    assert path.cpu().tolist() == [list(range(1, w[0] + 1)) + [-1] * (T_max - w[0]) for w in want]
+    if delta >= 5:
+        assert max(w[0] for w in want) >= 4
+    # the tree walk on the same chains gives the same three arrays
+    n2, b2, p2 = torch.empty_like(n_acc), torch.empty_like(bonus), torch.empty_like(path)
+    tw.tree_accept(d_t, a_t, parent, nn_t, n2, p2, b2)
+    assert torch.equal(n2, n_acc) and torch.equal(b2, bonus) and torch.equal(p2, path)
+    # lengths outside [1, T_max] are taken as the nearest valid one, never past the arrays
+    bad = torch.tensor([0, -3, T_max + 1, 2 ** 31 - 1] * (B // 4), dtype=torch.int32, device=DEV)
+    tw.chain_accept(d_t, a_t, bad, n_acc, path, bonus)
+    clamp = [min(max(int(v), 1), T_max) for v in bad.cpu().tolist()]
+    want = [oracle.chain_accept(draft[b], argmx[b], clamp[b] - 1) for b in range(B)]
+    assert n_acc.cpu().tolist() == [w[0] for w in want] and bonus.cpu().tolist() == [w[1] for w in want]
+
+
+# ----------------------------------------------------------------------------
 # kv_commit (the step after the walk) and two chained draft-verify iterations
 # ----------------------------------------------------------------------------
 @pytest.mark.parametrize("paged", [False, True])
