@@ -11,8 +11,10 @@
 // superset of the winners.  A row whose list overflows (many values tied at the bound) is handed
 // to the general radix select, and so is every row when E is above 32.
 //
-// From logits, the row maximum and the sum of exp(l - max) are carried along the same single read
-// (rescaled when a later chunk raises the maximum), and the winners leave as probabilities.
+// From logits, every lane keeps a running maximum of its own values and the sum of exp(l - that
+// maximum), updated 16 bytes at a time in the order the loads return, so the exponentials are
+// taken while the rest of the row is still on its way; the lanes' sums are brought to the row
+// maximum once at the end, and the winners leave as probabilities.
 #include "select_block.h"
 
 namespace tw {
@@ -41,7 +43,7 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(4))) vo
     float* out_v = vals + (int64_t)blockIdx.x * E;
 
     float G = -INFINITY;                        // group maximum over the chunks so far (lane l: group l)
-    float run_m = -INFINITY, lane_sum = 0.f;    // kLogits: row maximum so far, this lane's sum of exp(l - run_m)
+    float lane_m = -INFINITY, lane_sum = 0.f;   // kLogits: this lane's maximum so far, its sum of exp(l - lane_m)
     if (tid == 0) s_n = 0u;
     for (int c0 = 0; c0 < V; c0 += kChunk) {
         // slots past the row hold -inf: below every finite value, and kept off the list by index too
@@ -51,17 +53,42 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(4))) vo
             const int first = c0 + (tid + u * THREADS) * 4;
             raw[u] = f32x4t{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
             if (kVec) {
-                if (first < V) raw[u] = __builtin_nontemporal_load((const f32x4t*)(row + first));
+                // no load inside a branch: a piece past the row reads the row's first piece and is replaced
+                // by -inf where it is used, so the wait for piece u waits for piece u, not for all of them
+                raw[u] = __builtin_nontemporal_load((const f32x4t*)(row + (first < V ? first : 0)));
             } else {
 #pragma unroll
                 for (int c = 0; c < 4; ++c)
                     if (first + c < V) raw[u][c] = __builtin_nontemporal_load(row + first + c);
             }
         }
+        __builtin_amdgcn_sched_barrier(0);   // every load of the chunk is issued before the first is waited for
         float mx = -INFINITY;
 #pragma unroll
-        for (int u = 0; u < NV; ++u)
-            mx = fmaxf(fmaxf(mx, fmaxf(raw[u][0], raw[u][1])), fmaxf(raw[u][2], raw[u][3]));
+        for (int u = 0; u < NV; ++u) {
+            if (kVec) {
+                // (the choice is made on the bits, which keeps the compiler from moving the load back
+                // under the condition)
+                const uint32_t keep = c0 + (tid + u * THREADS) * 4 < V ? 0xFFFFFFFFu : 0u;
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    raw[u][c] = __uint_as_float((__float_as_uint(raw[u][c]) & keep) | (0xFF800000u & ~keep));
+            }
+            const float pm = fmaxf(fmaxf(raw[u][0], raw[u][1]), fmaxf(raw[u][2], raw[u][3]));
+            mx = fmaxf(mx, pm);
+            if (kLogits) {
+                // (a piece of empty slots, -inf throughout, adds nothing and must not produce inf - inf)
+                const float m_new = fmaxf(lane_m, pm);
+                const float m_safe = m_new == -INFINITY ? 0.f : m_new;
+                lane_sum = lane_sum * __expf(lane_m - m_safe) +
+                           ((__expf(raw[u][0] - m_safe) + __expf(raw[u][1] - m_safe)) +
+                            (__expf(raw[u][2] - m_safe) + __expf(raw[u][3] - m_safe)));
+                lane_m = m_new;
+                // one piece at a time, in the order the loads return: the sums are pinned here, or the
+                // exponentials (needed only at the end) would all be moved behind the wait for the last load
+                if (kVec) asm volatile("" : "+v"(lane_sum), "+v"(lane_m));
+            }
+        }
         if (c0 > 0) __syncthreads();   // every wavefront has read the maxima of the chunk before
         s_max[tid] = mx;
         __syncthreads();
@@ -103,21 +130,12 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(4))) vo
                 }
             }
         }
-        if (kLogits) {
-            float m_new = G;   // the row maximum so far: the largest group maximum
-#pragma unroll
-            for (int off = 32; off >= 1; off >>= 1) m_new = fmaxf(m_new, __shfl_xor(m_new, off, 64));
-            const float rescale = run_m == m_new ? 1.f : __expf(run_m - m_new);
-            float acc = 0.f;
-#pragma unroll
-            for (int u = 0; u < NV; ++u)
-                acc += (__expf(raw[u][0] - m_new) + __expf(raw[u][1] - m_new)) +
-                       (__expf(raw[u][2] - m_new) + __expf(raw[u][3] - m_new));
-            lane_sum = lane_sum * rescale + acc;
-            run_m = m_new;
-        }
     }
+    float run_m = G;   // kLogits: the row maximum, the largest group maximum
     if (kLogits) {
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) run_m = fmaxf(run_m, __shfl_xor(run_m, off, 64));
+        lane_sum *= __expf(lane_m - (run_m == -INFINITY ? 0.f : run_m));   // a lane without values: 0 * 0
 #pragma unroll
         for (int off = 32; off >= 1; off >>= 1) lane_sum += __shfl_xor(lane_sum, off, 64);
         if (lane == 0) s_sum[tid >> 6] = lane_sum;
