@@ -292,35 +292,41 @@ __global__ __launch_bounds__(kRsThreads, 2) void score_resident_kernel(ScoreArgs
                 }
                 if (c == 0) RS_MARK(2);   // logits of chunk 0 done
             } else {
+                // no key: the weights are zero as they stand (the exponentials below skip the chunk)
 #pragma unroll
                 for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) st[c][nb][r] = -INFINITY;
+                    for (int r = 0; r < 16; ++r) st[c][nb][r] = 0.f;
             }
         }
         // ---- exponentials in place, relative to the wavefront's own row maximum; publish (max, sum) ----
         // scale > 0: the maximum of the scaled logits is the scaled maximum.  Base-2 units throughout.
-        float own_m[NB];
+        float own_m[NB], m_safe[NB], row_l[NB];
         RS_MARK(5);   // pass 1 done
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
-            if (RS_DRY(2)) {
-                own_m[nb] = 0.f;
-                continue;
+            own_m[nb] = fmaxf(row_m[nb], __shfl_xor(row_m[nb], 32, 64)) * sl2;
+            m_safe[nb] = own_m[nb] == -INFINITY ? 0.f : own_m[nb];
+            row_l[nb] = 0.f;
+        }
+#pragma unroll
+        for (int c = 0; c < kRsCpw; ++c) {
+            // a wavefront whose last chunk lies past the end of the sequence saves a third of the work
+            if (kRsChunk * (wave + kRsWaves * c) < n_tot && !RS_DRY(2)) {
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const float e = fast_exp2(__builtin_fmaf(st[c][nb][r], sl2, -m_safe[nb]));
+                        st[c][nb][r] = e;
+                        row_l[nb] += e;
+                    }
             }
-            const float m = fmaxf(row_m[nb], __shfl_xor(row_m[nb], 32, 64)) * sl2;
-            const float m_safe = m == -INFINITY ? 0.f : m;
-            float l = 0.f;
+        }
 #pragma unroll
-            for (int c = 0; c < kRsCpw; ++c)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const float e = fast_exp2(__builtin_fmaf(st[c][nb][r], sl2, -m_safe));
-                    st[c][nb][r] = e;
-                    l += e;
-                }
-            l += __shfl_xor(l, 32, 64);
-            own_m[nb] = m;
+        for (int nb = 0; nb < NB; ++nb) {
+            const float m = own_m[nb];
+            const float l = row_l[nb] + __shfl_xor(row_l[nb], 32, 64);
             const int t1 = fresh_tid() & 63;
             if (t1 < 32) {
                 s_part[(wave * Cf::kRows + 32 * nb + t1) * 2] = m;
