@@ -371,6 +371,20 @@ def main():
         tws = torch.empty(twb.tree_build_workspace_bytes(Bn, N, 61) // 4 + 1, dtype=torch.float32, device=dev)
         next_rows["tree_build_us_median"] = med_us(lambda: twb.tree_build(cp, ct, pb, nc, root, 61, outs[0], outs[1],
                                                                           outs[2], nn, tws))
+        # sequence-based speculative decoding with the paper's delta = 5, theta = 0.6: chain tree from the
+        # draft probabilities (early exit), then the accepted prefix -- latency work on KB-sized inputs
+        c_prob = torch.rand(Bn, 5, device=dev)
+        c_par = torch.empty((Bn, 6), dtype=torch.int32, device=dev)
+        c_nn = torch.empty(Bn, dtype=torch.int32, device=dev)
+        c_dr = torch.randint(0, 4, (Bn, 6), device=dev, dtype=torch.int32)
+        c_am = torch.randint(0, 4, (Bn, 6), device=dev, dtype=torch.int32)
+        c_out = [torch.empty(Bn, dtype=torch.int32, device=dev), torch.empty((Bn, 6), dtype=torch.int32, device=dev),
+                 torch.empty(Bn, dtype=torch.int32, device=dev)]
+
+        def chain_calls():
+            twb.chain_tree(c_prob, 0.6, 5, c_par, c_nn)
+            twb.chain_accept(c_dr, c_am, c_nn, c_out[0], c_out[1], c_out[2])
+        next_rows["chain_tree_plus_chain_accept_us_median"] = med_us(chain_calls)
 
         # grouped-query attention at the head layout of Qwen2.5-VL-7B (28 query heads over 4 key/value
         # heads of 128), cfg1's lengths, the same 128 sequences: the verification attention and the score
