@@ -11,8 +11,8 @@ With --ladder: the launch timed with parts of its work switched off at run time 
 the diagnostic build: 1 no matrix products / row maxima, 2 also no exponentials, 3 also no column
 sums, 4 also no Q traffic = the bare K stream with its staging and barrier), each level in a child
 process, with the compaction and verification launches of a step between the timed launches.
-Nothing here is part of the method; it exists so that the statements about this kernel in
-the design doc can be re-measured from the tree.
+Nothing here is part of the method; it exists so that what is said about where this kernel's
+time goes can be re-measured from the tree.
 """
 import ctypes
 import os

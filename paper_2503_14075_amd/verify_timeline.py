@@ -9,8 +9,8 @@ chunk done, loop done, end) plus its XCD; the report gives the launch's span, th
 starts, ends and phase lengths, and the ends by XCD and by dispatch order.  Launches are made cold
 (1 GiB streamed through the caches before each).  With --floor: what a bare read-only stream over as
 many bytes reaches on the same box, cold and warm (the ceiling for a kernel of that size).
-Nothing here is part of the method; it exists so that the ramp-up / tail statements in the design doc can
-be re-measured from the tree.
+Nothing here is part of the method; it exists so that what is said about the ramp-up and the tail of
+these launches can be re-measured from the tree.
 """
 import collections
 import ctypes
