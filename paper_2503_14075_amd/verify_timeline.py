@@ -1,7 +1,7 @@
 """Diagnostics of tree_verify_attn on small launches, from the diagnostic build of the library
 (`python -m paper_2503_14075_amd.build --trace`, which writes libtwigpath_trace.so):
 
-    python -m paper_2503_14075_amd.verify_timeline [cfg2_p0 cfg2_p256 cfg2_p1024 cfg3 cfg4 cfg1x128] [--floor]
+    python -m paper_2503_14075_amd.verify_timeline [cfg2_p0 cfg2_p256 cfg2_p1024 cfg3 cfg4 cfg1x128 cfg1_T61x128] [--floor]
 
 For every named configuration: thread 0 of each workgroup of the verification kernel records the
 100 MHz wall clock at five points of its life (start, first loads issued, masks and Q ready, first
@@ -14,6 +14,7 @@ these launches can be re-measured from the tree.
 """
 import collections
 import ctypes
+import dataclasses
 import os
 import sys
 
@@ -49,7 +50,12 @@ def main():
     flush_b = torch.empty_like(flush_a)
     sink = torch.zeros(4, dtype=torch.int32, device=dev)
     for name in names:
-        cfg = W.replicate(W.CONFIGS["cfg1"], 128) if name == "cfg1x128" else W.CONFIGS[name]
+        if name == "cfg1x128":
+            cfg = W.replicate(W.CONFIGS["cfg1"], 128)
+        elif name == "cfg1_T61x128":    # the bench batch with the paper's default tree: 60 candidates + the root
+            cfg = dataclasses.replace(W.replicate(W.CONFIGS["cfg1"], 128), name=name, T=61, tree=("random", 6))
+        else:
+            cfg = W.CONFIGS[name]
         wo = W.make_workload(cfg, device=dev, with_compact=False, with_score=False)
         do = runner.DeviceWorkload(wo, dev)
         trace = torch.zeros((1 << 16) * 8, dtype=torch.int64, device=dev)
