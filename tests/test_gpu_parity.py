@@ -6,6 +6,7 @@ within 2e-3 max-abs (bf16 inputs, fp32 accumulation); pruning scores within
 1e-6 absolute (they are O(1/n_tot)).
 """
 import math
+import os
 
 import pytest
 import torch
@@ -18,6 +19,8 @@ pytestmark = pytest.mark.gpu
 ATTN_TOL = 2e-3
 SCORE_TOL = 1e-6
 DEV = "cuda:0"
+# how many seeded random shapes the two *_random_shapes tests draw (a longer campaign: TW_RANDOM_SHAPES=400)
+N_RANDOM_SHAPES = int(os.environ.get("TW_RANDOM_SHAPES", "8"))
 
 
 @pytest.fixture(scope="module")
@@ -284,7 +287,7 @@ def test_verify_page_sizes(tw, page_rows, T):
                      tol=ATTN_TOL if dtype == torch.bfloat16 else 2e-5, page_table=w.page_table, page_rows=page_rows)
 
 
-@pytest.mark.parametrize("seed", range(8))
+@pytest.mark.parametrize("seed", range(N_RANDOM_SHAPES))
 def test_verify_random_shapes(tw, seed):
     # ragged everything, contiguous and paged pools, both head sizes, trees up to 64 nodes
     rng = W.HostRng(7000 + seed)
@@ -989,7 +992,7 @@ def test_score_resident_limits(tw):
     _check_score(tw, torch.bfloat16, 3, 64, 300, 33, [64, 20], [64, 20], False, q_std=4.0)
 
 
-@pytest.mark.parametrize("seed", range(8))
+@pytest.mark.parametrize("seed", range(N_RANDOM_SHAPES))
 def test_score_random_shapes(tw, seed):
     # ragged everything: heads, head size, span start and length, text lengths, scoring rows, masks
     rng = W.HostRng(9000 + seed)
