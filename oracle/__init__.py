@@ -107,11 +107,12 @@ def ttp_compact(kept: torch.Tensor, v_start: int, M: int, src: torch.Tensor) -> 
     src = src.contiguous()
     row_bytes = src[0].numel() * src.element_size() if n_tot else 0
     n_out = n_tot - M + R
-    dst = torch.empty((max(n_out, 0),) + tuple(src.shape[1:]), dtype=src.dtype)
+    # (one row more than needed: an empty result still gets a buffer to point at)
+    dst = torch.empty((max(n_out, 0) + 1,) + tuple(src.shape[1:]), dtype=src.dtype)
     rc = lib().orc_ttp_compact(_p(kept), R, int(v_start), int(M), n_tot, _p(src), _p(dst),
                                ctypes.c_size_t(row_bytes))
     _check(rc, "ttp_compact")
-    return dst
+    return dst[:max(n_out, 0)]
 
 
 def tree_ancestors(parent: Sequence[int]) -> List[int]:

@@ -667,6 +667,48 @@ def test_compact_batched_ragged_pools(tw):
             assert torch.equal(got.view(torch.int32), want.view(torch.int32))
 
 
+@pytest.mark.parametrize("seed", range(N_RANDOM_SHAPES))
+def test_integer_kernels_random_shapes(tw, seed):
+    # select, batched compaction, ancestor masks and the acceptance walk on seeded random shapes, bit-exact
+    rng = W.HostRng(12000 + seed)
+    g = torch.Generator().manual_seed(12000 + seed)
+    # select: rows of 1..5000 scores, a random number of distinct values (few: long tie runs)
+    B, M = rng.randint(1, 4), rng.randint(1, 5000)
+    levels = (2, 7, 100, 1 << 20)[rng.randint(0, 3)]
+    sc = (torch.randint(0, levels, (B, M), generator=g).float() - levels // 3) * (1.0, 1e-3, 1e-40)[rng.randint(0, 2)]
+    _check_select(tw, sc, rng.randint(0, M))
+    # compaction of ragged sequences out of shared pools, any row size
+    v0, Mc, nb = rng.randint(0, 9), rng.randint(1, 120), rng.randint(1, 5)
+    R, row = rng.randint(0, Mc), (16, 96, 7, 1030, 4096)[rng.randint(0, 4)]
+    n_tot = [v0 + Mc + rng.randint(0, 40) for _ in range(nb)]
+    n_keep = [n - Mc + R for n in n_tot]
+    src_off = [sum(n_tot[:b]) for b in range(nb)]
+    dst_off = [sum(n_keep[:b]) for b in range(nb)]
+    kept = torch.stack([torch.sort(torch.randperm(Mc, generator=g)[:R]).values for _ in n_tot]).to(torch.int32)
+    src = [torch.randint(0, 256, (sum(n_tot), row), generator=g).to(torch.uint8) for _ in range(rng.randint(1, 3))]
+    ddst = [torch.zeros(sum(n_keep) + 1, row, dtype=torch.uint8, device=DEV) for _ in src]   # (never empty)
+    tw.ttp_compact_batched(kept.to(DEV) if R else None, R, v0, Mc, _i32(n_tot), max(n_tot), _i32(src_off),
+                           _i32(dst_off), [s_.to(DEV) for s_ in src], ddst, row)
+    torch.cuda.synchronize()
+    for s_, d in zip(src, ddst):
+        for b in range(nb):
+            want = oracle.ttp_compact(kept[b], v0, Mc, s_[src_off[b]:src_off[b] + n_tot[b]])
+            assert torch.equal(d.cpu()[dst_off[b]:dst_off[b] + n_keep[b]], want)
+    # acceptance walk (and its masks) on random trees with small alphabets, so that long paths occur
+    T_max, Bt = rng.randint(1, 64), rng.randint(1, 40)
+    n_nodes = [rng.randint(1, T_max) for _ in range(Bt)]
+    trees = [W.random_parent_tree(rng, n, rng.randint(1, 8)) for n in n_nodes]
+    alpha = rng.randint(1, 4)
+    draft = [[rng.randint(0, alpha) for _ in range(n)] for n in n_nodes]
+    argmx = [[rng.randint(0, alpha) for _ in range(n)] for n in n_nodes]
+    _check_accept(tw, draft, argmx, trees, n_nodes, T_max)
+    masks = torch.zeros((Bt, T_max), dtype=torch.int64, device=DEV)
+    tw.tree_ancestor_masks(_i32(padded(trees, T_max)), _i32(n_nodes), masks)
+    got_m = masks.cpu()
+    for b, t in enumerate(trees):
+        assert [int(x) & ((1 << 64) - 1) for x in got_m[b, :len(t)].tolist()] == oracle.tree_ancestors(t)
+
+
 def test_violated_device_preconditions_stay_in_bounds(tw):
     # Lengths, offsets, parents, page ids, kept indices and paths that break the documented
     # preconditions: the kernels move every index into the buffers the arguments describe, so the
