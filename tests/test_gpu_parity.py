@@ -1135,6 +1135,29 @@ def test_draft_topk_bit_exact(tw, V, E):
     assert torch.equal(ids.cpu(), wi) and torch.equal(vals.cpu(), wv)
 
 
+@pytest.mark.parametrize("seed", range(N_RANDOM_SHAPES))
+def test_draft_topk_random_shapes(tw, seed):
+    # top-E of random rows: any vocabulary size up to 70000 (aligned or not), any E up to 64, values with few
+    # or many distinct levels -- ids and values bit-exact from probabilities; from logits the ids bit-exact
+    # and the probabilities to 2e-5 relative
+    rng = W.HostRng(15000 + seed)
+    g = torch.Generator().manual_seed(15000 + seed)
+    n, V = rng.randint(1, 5), (rng.randint(1, 70000), 4 * rng.randint(1, 17000), rng.randint(1, 300))[rng.randint(0, 2)]
+    E = rng.randint(1, min(V, 64))
+    levels = (3, 50, 1 << 22)[rng.randint(0, 2)]
+    x = torch.randint(0, levels, (n, V), generator=g).float() / levels
+    ids = torch.full((n, E), -7, dtype=torch.int32, device=DEV)
+    vals = torch.full((n, E), -7.0, dtype=torch.float32, device=DEV)
+    tw.draft_topk(x.to(DEV), E, ids, vals)
+    wi, wv = oracle.draft_topk(x, E)
+    assert torch.equal(ids.cpu(), wi) and torch.equal(vals.cpu(), wv)
+    lg = (x - 0.5) * (1.0, 12.0, 60.0)[rng.randint(0, 2)] + (0.0, 500.0)[rng.randint(0, 1)]
+    tw.draft_topk_logits(lg.to(DEV), E, ids, vals)
+    wi, wp = oracle.draft_topk_logits(lg, E)
+    assert torch.equal(ids.cpu(), wi)
+    assert float(((vals.cpu().double() - wp).abs() / (2e-5 * wp + 1e-37)).max()) <= 1.0
+
+
 @pytest.mark.parametrize("V,E", [(32000, 10), (32000, 32), (7, 1), (7, 5), (50, 32), (301, 10), (1024, 1), (4099, 3),
                                  (32768, 32), (32772, 10), (70001, 10), (151936, 10), (32000, 33), (300, 256),
                                  (40000, 100)])
