@@ -481,15 +481,12 @@ def test_chain_tree_and_accept_bit_exact(tw, delta):
 # ----------------------------------------------------------------------------
 # kv_commit (the step after the walk) and two chained draft-verify iterations
 # ----------------------------------------------------------------------------
-@pytest.mark.parametrize("paged", [False, True])
-def test_kv_commit_bit_exact(tw, paged):
-    B, H, d_h, T, pr = 6, 4, 64, 24, 16
-    rng = W.HostRng(77, int(paged))
+def _check_kv_commit(tw, rng, paged, B, H, d_h, T, pr, n_pools, need_accepts):
     ctx = [rng.randint(0, 90) for _ in range(B)]
     trees = [W.random_parent_tree(rng, T, 6) for _ in range(B)]
     toks = [W.plant_tokens(rng, t, vocab=3, p_match=0.9) for t in trees]
     n_acc, path, _ = oracle.tree_accept([x[0] for x in toks], [x[1] for x in toks], trees, [T] * B)
-    assert int(n_acc.max()) >= 2
+    assert int(n_acc.max()) >= need_accepts
     rows = [c + T for c in ctx]
     if paged:
         n_pages = [(r + pr - 1) // pr for r in rows]
@@ -506,7 +503,8 @@ def test_kv_commit_bit_exact(tw, paged):
             off.append(acc)
             acc += r + 2
         pool_rows = acc
-    pools = [W.normal(5, s, (pool_rows, H, d_h), 1.0, torch.bfloat16 if s % 2 else torch.float32) for s in range(5)]
+    pools = [W.normal(5, s, (pool_rows, H, d_h), 1.0, torch.bfloat16 if s % 2 else torch.float32)
+             for s in range(n_pools)]
     dev = [p.to(DEV) for p in pools]
     ro = None if off is None else _i32(off)
     ptd = None if pt is None else _i32(pt)
@@ -519,6 +517,20 @@ def test_kv_commit_bit_exact(tw, paged):
                                     page_rows=pr)
         assert new_len.cpu().tolist() == want_len
         assert torch.equal(p_dev.cpu().view(torch.uint8), p_host.view(torch.uint8))
+
+
+@pytest.mark.parametrize("paged", [False, True])
+def test_kv_commit_bit_exact(tw, paged):
+    _check_kv_commit(tw, W.HostRng(77, int(paged)), paged, B=6, H=4, d_h=64, T=24, pr=16, n_pools=5, need_accepts=2)
+
+
+@pytest.mark.parametrize("seed", range(N_RANDOM_SHAPES))
+def test_kv_commit_random_shapes(tw, seed):
+    # accepted paths of random trees moved through contiguous or paged pools of any head layout and page size
+    rng = W.HostRng(17000 + seed)
+    _check_kv_commit(tw, rng, paged=bool(seed & 1), B=rng.randint(1, 7), H=rng.randint(1, 5),
+                     d_h=(8, 64, 128)[rng.randint(0, 2)], T=rng.randint(1, 64), pr=(1, 4, 16, 24)[rng.randint(0, 3)],
+                     n_pools=rng.randint(1, 3), need_accepts=0)
 
 
 def test_two_chained_draft_verify_iterations(tw):
