@@ -973,10 +973,25 @@ def _check_score(tw, dtype, H, d_h, M, v0, n_text, n_q, causal, q_std=1.0, seed=
                                             (576, 100, [128, 70], [128, 70]),
                                             (2880, 320, [128, 128], [16, 16])])
 def test_score_select_in_one_call_equals_the_two_calls(tw, M, R, n_text, n_q):
+    _check_score_select(tw, M, R, n_text, n_q, H=8, d_h=128, v0=0)
+
+
+@pytest.mark.parametrize("seed", range(N_RANDOM_SHAPES))
+def test_score_select_and_phead_random_shapes(tw, seed):
+    rng = W.HostRng(21000 + seed)
+    B, M = rng.randint(1, 4), rng.randint(1, 1500)
+    n_text = [rng.randint(1, 100) for _ in range(B)]
+    _check_score_select(tw, M, rng.randint(0, M), n_text, [rng.randint(1, n) for n in n_text], H=rng.randint(1, 9),
+                        d_h=(64, 128)[seed & 1], v0=rng.randint(0, 20))
+    _check_phead(tw, (torch.bfloat16, torch.float32)[rng.randint(0, 1)], rng.randint(1, 12),
+                 (16, 40, 64, 128)[rng.randint(0, 3)], rng.randint(1, 700), rng.randint(0, 9), rng.randint(1, 3), 21000 + seed)
+
+
+def _check_score_select(tw, M, R, n_text, n_q, H, d_h, v0):
     # the launch that adds the heads also keeps the R best (rows up to 1024 scores; longer rows take the
     # separate select inside the call): scores and kept are bit-identical to tw_ttp_score + tw_ttp_select,
     # and kept is the oracle's selection on those scores
-    H, d_h, v0, B = 8, 128, 0, len(n_text)
+    B = len(n_text)
     n_tot = [v0 + M + n for n in n_text]
     off, acc = [], 0
     for n in n_tot:
@@ -1074,11 +1089,15 @@ def test_score_one_pass_boundary(tw):
 @pytest.mark.parametrize("dtype,H,d_h,M,v0,B", [(torch.bfloat16, 32, 128, 576, 0, 3), (torch.bfloat16, 5, 64, 77, 9, 2),
                                                (torch.float32, 4, 40, 130, 2, 2), (torch.bfloat16, 2, 128, 2880, 0, 1)])
 def test_score_phead_form(tw, dtype, H, d_h, M, v0, B):
+    _check_phead(tw, dtype, H, d_h, M, v0, B, 71)
+
+
+def _check_phead(tw, dtype, H, d_h, M, v0, B, seed):
     n = v0 + M + 11
-    q = W.normal(71, 1, (B, H, d_h), 1.0, dtype)
-    gq = W.normal(71, 2, (B, H, d_h), 1.0, dtype)
-    k = W.normal(71, 3, (B * n + 2, H, d_h), 1.0, dtype)
-    gk = W.normal(71, 4, (B * n + 2, H, d_h), 1.0, dtype)
+    q = W.normal(seed, 1, (B, H, d_h), 1.0, dtype)
+    gq = W.normal(seed, 2, (B, H, d_h), 1.0, dtype)
+    k = W.normal(seed, 3, (B * n + 2, H, d_h), 1.0, dtype)
+    gk = W.normal(seed, 4, (B * n + 2, H, d_h), 1.0, dtype)
     off = [1 + b * n for b in range(B)]
     scale = 1 / math.sqrt(d_h)
     want = oracle.ttp_score_phead(q, gq, k, gk, off, off, v0, M, scale)
