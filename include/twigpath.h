@@ -81,7 +81,8 @@ typedef struct tw_kv_view {
     int32_t max_pages, page_rows;
 } tw_kv_view;
 
-/* Library version, 1000*major + minor (2.0: the verification workspace carries counters that start at zero). */
+/* Library version, 1000*major + minor (2.0: the verification workspace carries counters that start at zero;
+ * 2.1: they take the first 1024 bytes whatever the shape of the launch). */
 TW_API int32_t tw_version(void);
 
 /*
@@ -93,11 +94,15 @@ TW_API int32_t tw_version(void);
  * handed to the call is device memory, 16-byte aligned, and not shared with a call that may run
  * at the same time.
  * TW_CALL_TTP_SCORE: its contents on entry do not matter and are undefined on return.
- * TW_CALL_TREE_VERIFY_ATTN: the buffer starts with one arrival counter per (sequence, head), which
- * a launch that cuts sequences into pieces needs at zero and puts back to zero as its last action.
- * Zero the buffer once, after allocating it (hipMemset); from then on it serves any number of
- * calls of any shape.  With counters that are not zero the output is unspecified (still memory-
- * safe, and no kernel waits for another).  After TW_ERR_LAUNCH zero it again.
+ * TW_CALL_TREE_VERIFY_ATTN: the first 1024 bytes of the buffer are arrival counters, one per
+ * (sequence, head) of a launch that cuts sequences into pieces (only launches with fewer than 256
+ * such units do); the launch needs them at zero and puts them back to zero as its last action.
+ * Partial results lie behind them, in whole 128-byte lines per workgroup when the buffer is
+ * 128-byte aligned (recommended).  Zero the buffer once, after allocating it (hipMemset); from
+ * then on it serves any number of calls of any shape, one after the other: whatever the shapes,
+ * no call writes partial results where another keeps counters.  With counters that are not zero
+ * the output is unspecified (still memory-safe, and no kernel waits for another).  After
+ * TW_ERR_LAUNCH zero it again.
  */
 TW_API size_t tw_workspace_bytes(int32_t which, int32_t B, int32_t rows, int32_t H, int32_t d_h,
                           int32_t max_rows);

@@ -71,12 +71,12 @@ VerifyPlan verify_plan(int B, int H, int T_max, int max_rows) {
     return p;
 }
 
-size_t verify_counter_bytes(int B, int H) { return ((size_t)B * H * sizeof(int32_t) + 255) / 256 * 256; }
 
 size_t verify_workspace_bytes(int B, int H, int T_max, int d_h, int max_rows) {
     const int ns = verify_plan(B, H, T_max, max_rows).n_splits;
     if (ns == 1) return 0;
-    return verify_counter_bytes(B, H) + (size_t)ns * B * H * T_max * (d_h + 2) * sizeof(float);
+    return kVerifyCounterBytes +
+           (size_t)ns * B * H * (partial_stride(T_max * d_h) + partial_stride(T_max * 2)) * sizeof(float);
 }
 
 }  // namespace tw
@@ -114,7 +114,7 @@ extern "C" TW_API int32_t tw_debug_stream_read(const void* src, size_t bytes, in
 
 extern "C" {
 
-int32_t tw_version(void) { return 2000; }
+int32_t tw_version(void) { return 2001; }
 
 size_t tw_workspace_bytes(int32_t which, int32_t B, int32_t rows, int32_t H, int32_t d_h,
                           int32_t max_rows) {
@@ -352,6 +352,7 @@ int32_t tw_tree_verify_attn_gqa(const void* q, const tw_kv_view* k, const tw_kv_
     a.part_o = nullptr;
     a.part_ml = nullptr;
     a.arrive = nullptr;
+    a.o_stride = a.ml_stride = 0;
 #ifdef TW_TRACE
     a.trace = g_trace;
 #endif
@@ -360,8 +361,10 @@ int32_t tw_tree_verify_attn_gqa(const void* q, const tw_kv_view* k, const tw_kv_
         if (!ws || ws_bytes < need) return TW_ERR_WORKSPACE;
         if ((uintptr_t)ws % 16) return TW_ERR_INVALID_ARG;
         a.arrive = (int32_t*)ws;
-        a.part_o = (float*)((char*)ws + verify_counter_bytes(B, a.H));
-        a.part_ml = a.part_o + (size_t)a.n_splits * B * a.H * T_max * a.d_h;
+        a.o_stride = partial_stride(T_max * a.d_h);
+        a.ml_stride = partial_stride(T_max * 2);
+        a.part_o = (float*)((char*)ws + kVerifyCounterBytes);
+        a.part_ml = a.part_o + (size_t)a.n_splits * B * a.H * a.o_stride;
     }
     hipStream_t s = (hipStream_t)stream;
     hipError_t e;

@@ -173,15 +173,16 @@ __global__ __launch_bounds__(kGenThreads) void verify_generic_kernel(VerifyArgs 
         }
     } else {
         if (t < T) {
-            const int64_t slot0 = (((int64_t)split * a.B + b) * a.H + h) * a.T_max;   // node 0 of this piece's slot
-            const __amdgpu_buffer_rsrc_t ro = raw_buffer(a.part_o + slot0 * d_h, (uint32_t)(a.T_max * d_h * 4));
+            const int64_t slot = ((int64_t)split * a.B + b) * a.H + h;   // this piece's slot
+            const __amdgpu_buffer_rsrc_t ro = raw_buffer(a.part_o + slot * a.o_stride, (uint32_t)(a.T_max * d_h * 4));
 #pragma unroll
             for (int cc = 0; cc < kCq; ++cc)
                 if (cc < cq)
                     __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, o[cc]), ro,
                                                           (t * d_h + qd + 4 * cc) * 4, 0, kAuxThrough);
             if (qd == 0)
-                store_partial2(a.part_ml + slot0 * 2, (uint32_t)(a.T_max * 8), (uint32_t)(t * 8), make_float2(run_m, l));
+                store_partial2(a.part_ml + slot * a.ml_stride, (uint32_t)(a.T_max * 8), (uint32_t)(t * 8),
+                               make_float2(run_m, l));
         }
         finish_split_unit(a, b, h, T, sq.n_b, tid, kGenThreads);
     }

@@ -297,10 +297,12 @@ __device__ __forceinline__ void epilogue_merge(const WaveState<DH>& w, const Ver
             store_out4(a.out, a.out_bf16, (((int64_t)b * a.T_max + node) * a.H + h) * DH + 4 * d4, acc.x * inv,
                        acc.y * inv, acc.z * inv, acc.w * inv, false);
         } else {
-            const int64_t slot0 = (((int64_t)split * a.B + b) * a.H + h) * a.T_max;   // node 0 of this piece's slot
-            store_partial4(a.part_o + slot0 * DH, (uint32_t)(a.T_max * DH * 4), (uint32_t)((node * DH + 4 * d4) * 4), acc);
+            const int64_t slot = ((int64_t)split * a.B + b) * a.H + h;   // this piece's slot
+            store_partial4(a.part_o + slot * a.o_stride, (uint32_t)(a.T_max * DH * 4), (uint32_t)((node * DH + 4 * d4) * 4),
+                           acc);
             if (d4 == 0)
-                store_partial2(a.part_ml + slot0 * 2, (uint32_t)(a.T_max * 8), (uint32_t)(node * 8), make_float2(m * kLn2, l));
+                store_partial2(a.part_ml + slot * a.ml_stride, (uint32_t)(a.T_max * 8), (uint32_t)(node * 8),
+                               make_float2(m * kLn2, l));
         }
     }
     if (n_b > 1) finish_split_unit(a, b, h, T, n_b, tid, kMfThreads);

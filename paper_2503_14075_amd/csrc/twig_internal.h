@@ -127,8 +127,11 @@ struct VerifyArgs {
     const int32_t* ctx_len;
     const int32_t* parent;
     const int32_t* n_nodes;
-    float* part_o;   // [n_splits][B][H][T_max][d_h] unnormalised partial outputs
-    float* part_ml;  // [n_splits][B][H][T_max][2] running max (natural-log units), running sum
+    // Partial results of split launches, one slot per (piece, sequence, head).  A slot is a whole number of
+    // 128-byte lines (o_stride, ml_stride floats): no line of it is shared with another workgroup's slot.
+    float* part_o;   // [n_splits][B][H] slots of [T_max][d_h] unnormalised partial outputs
+    float* part_ml;  // [n_splits][B][H] slots of [T_max][2]: running max (natural-log units), running sum
+    int32_t o_stride, ml_stride;
     int32_t* arrive; // [B][H] pieces of the unit that have written their partial; zero between launches
     int32_t T_max, B, H, d_h;   // H: query heads = group * (heads of a cache row, k.H)
     int32_t group;              // query heads per key/value head (1: multi-head attention)
@@ -165,7 +168,12 @@ size_t verify_workspace_bytes(int B, int H, int T_max, int d_h, int max_rows);
 hipError_t launch_verify_generic(const VerifyArgs& a, int dtype, hipStream_t s);
 bool verify_mfma_supported(const VerifyArgs& a, int dtype);
 hipError_t launch_verify_mfma(const VerifyArgs& a, hipStream_t s);
-size_t verify_counter_bytes(int B, int H);   // the arrival counters at the start of the workspace
+// The arrival counters at the start of the workspace: the same 1 KB whatever the shape of the launch (a launch is
+// only cut into pieces while it has fewer than 256 (sequence, head) units), so that launches of different
+// shapes may share a workspace: none of them writes partial results where another one keeps counters.
+constexpr size_t kVerifyCounterBytes = 256 * sizeof(int32_t);
+constexpr int kPartialLineFloats = 32;
+inline int partial_stride(int floats) { return (floats + kPartialLineFloats - 1) / kPartialLineFloats * kPartialLineFloats; }
 
 // Partial results of a piece travel between workgroups on different XCDs, whose L2s are not kept
 // coherent with each other: they are written and read with system-scope accesses (sc0 sc1: written
@@ -207,8 +215,8 @@ __device__ inline void finish_split_unit(const VerifyArgs& a, int b, int h, int 
     // the online-softmax update, one piece at a time, in piece order.
     constexpr int kItems = 4, kBatch = 2;
     const int lanes = a.d_h / 4;
-    const int64_t split_stride = (int64_t)a.B * a.H * a.T_max;
-    const int64_t unit0 = ((int64_t)b * a.H + h) * a.T_max;
+    const int64_t split_stride = (int64_t)a.B * a.H;      // slots per piece
+    const int64_t unit0 = (int64_t)b * a.H + h;
     const uint32_t o_bytes = (uint32_t)(a.T_max * a.d_h * 4), ml_bytes = (uint32_t)(a.T_max * 8);
     const int n_items = T * lanes;
     for (int idx0 = tid; idx0 < n_items; idx0 += n_threads * kItems) {
@@ -227,8 +235,8 @@ __device__ inline void finish_split_unit(const VerifyArgs& a, int b, int h, int 
             for (int i = 0; i < kBatch; ++i) {
                 const int s = s0 + i < n_b ? s0 + i : n_b - 1;   // past the last piece: re-read it, unused
                 const int64_t slot = unit0 + s * split_stride;
-                const __amdgpu_buffer_rsrc_t rml = raw_buffer(a.part_ml + slot * 2, ml_bytes);
-                const __amdgpu_buffer_rsrc_t ro = raw_buffer(a.part_o + slot * a.d_h, o_bytes);
+                const __amdgpu_buffer_rsrc_t rml = raw_buffer(a.part_ml + slot * a.ml_stride, ml_bytes);
+                const __amdgpu_buffer_rsrc_t ro = raw_buffer(a.part_o + slot * a.o_stride, o_bytes);
 #pragma unroll
                 for (int u = 0; u < kItems; ++u) {
                     // items past the end fall outside the descriptors and read zeros

@@ -43,8 +43,11 @@ def test_host_helpers():
 def test_workspace_sizes():
     # one sequence, 32 heads, long cache: the rows are split, partials need room
     n = tw.workspace_bytes(tw.TW_CALL_TREE_VERIFY_ATTN, 1, 26, 32, 128, 2076)
-    # arrival counters (one per (sequence, head), rounded up to 256 bytes) + whole pieces of partial results
-    assert n > 256 and (n - 256) % (32 * 26 * 130 * 4) == 0
+    # 1024 bytes of arrival counters + whole pieces of partial results (per head 26 x 128 floats of outputs
+    # and 26 x 2 floats of statistics, each rounded up to whole 128-byte lines)
+    assert n > 1024 and (n - 1024) % (32 * (26 * 128 + 64) * 4) == 0
+    # the counters take the same room whatever the number of (sequence, head) units
+    assert tw.workspace_bytes(tw.TW_CALL_TREE_VERIFY_ATTN, 2, 4, 100, 64, 900) % 128 == 0
     # a short cache is not worth splitting
     assert tw.workspace_bytes(tw.TW_CALL_TREE_VERIFY_ATTN, 1, 26, 32, 128, 282) == 0
     # 128 sequences fill the chip without splitting

@@ -185,11 +185,12 @@ def test_verify_split_cache_single_sequence(tw):
 
 def test_verify_workspace_serves_launch_after_launch(tw):
     # One workspace, zeroed once, serves launches of different shapes one after another: the arrival
-    # counters at its start are back at zero after every launch, and whatever else it holds does not
-    # matter (the partial results behind the counters are overwritten with NaNs between the calls).
+    # counters (its first 1024 bytes, whatever the shape) are back at zero after every launch, and
+    # whatever else it holds does not matter (the partial results behind the counters are overwritten
+    # with NaNs between the calls).  A launch with more (sequence, head) units follows one with fewer.
     H, d_h = 32, 128
     scale = 1 / math.sqrt(d_h)
-    cases = [(3, [2600, 300, 1500], 40), (1, [900], 26), (2, [700, 2050], 64), (1, [900], 26)]
+    cases = [(1, [900], 26), (3, [2600, 300, 1500], 40), (2, [700, 2050], 64), (1, [900], 26), (7, [600] * 7, 9)]
     need = [tw.workspace_bytes(tw.TW_CALL_TREE_VERIFY_ATTN, B, T, H, d_h, max(ctx) + T) for B, ctx, T in cases]
     assert min(need) > 0
     shared = torch.zeros(max(need) // 4, dtype=torch.float32, device=DEV)
@@ -206,7 +207,7 @@ def test_verify_workspace_serves_launch_after_launch(tw):
         tw.tree_verify_attn(qd, kv, vv, *args, got, shared)
         torch.cuda.synchronize()
         assert torch.equal(got, want) and torch.isfinite(got).all()
-        n_counters = (B * H * 4 + 255) // 256 * 64
+        n_counters = 256
         assert int(shared.view(torch.int32)[:n_counters].abs().max()) == 0
         shared[n_counters:] = float("nan")
         ref = oracle.tree_verify_attn(q, k, v, ctx, [T] * B, trees, scale, row_off=off)

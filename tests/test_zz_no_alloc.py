@@ -2,6 +2,7 @@
 inside the library) against tw_tree_verify_attn on the same inputs, through the C ABI, on two calls
 in a row -- the second with a smaller input, so that it meets the scratch as the first left it."""
 import math
+import os
 
 import pytest
 import torch
@@ -56,6 +57,46 @@ def test_static_scratch_entry_point_matches_the_workspace_one(tw):
         assert torch.isfinite(want).all()
         # the same kernels on the same inputs with a fixed summation order: bit-identical
         assert torch.equal(got, want)
+
+
+@pytest.mark.parametrize("seed", range(int(os.environ.get("TW_RANDOM_SHAPES", "8"))))
+def test_static_scratch_random_shapes(tw, seed):
+    # launch after launch of random shapes through the one scratch array (with and without pieces, one or
+    # several per sequence): bit-identical to the entry point that takes a workspace
+    rng = W.HostRng(23000 + seed)
+    B, H, d_h, T = rng.randint(1, 4), (rng.randint(1, 16), rng.randint(1, 63))[rng.randint(0, 1)], (64, 128)[seed & 1], rng.randint(1, 64)
+    ctx = [rng.randint(0, (300, 3000)[rng.randint(0, 1)]) for _ in range(B)]
+    nbytes = tw.workspace_bytes(tw.TW_CALL_TREE_VERIFY_ATTN, B, T, H, d_h, max(ctx) + T)
+    if nbytes > tw.TW_STATIC_SCRATCH_BYTES:
+        pytest.skip("needs more scratch than the library holds")
+    q, k, v, off, ctx_d, par, n_nodes = _case(23000 + seed, B, H, d_h, ctx, T)
+    kv, vv = tw.kv_view(k, off), tw.kv_view(v, off)
+    ws = torch.zeros(max(nbytes // 4, 1), dtype=torch.float32, device=DEV)
+    want = torch.full((B, T, H, d_h), float("nan"), dtype=torch.float32, device=DEV)
+    scale = 1 / math.sqrt(d_h)
+    tw.tree_verify_attn(q, kv, vv, ctx_d, max(ctx), par, n_nodes, scale, want, ws if nbytes else None)
+    got = torch.full_like(want, float("nan"))
+    tw.tree_verify_attn_static(q, kv, vv, ctx_d, max(ctx), par, n_nodes, scale, got)
+    torch.cuda.synchronize()
+    assert torch.isfinite(want).all() and torch.equal(got, want)
+
+
+def test_static_scratch_serves_more_units_after_fewer(tw):
+    # a launch with few (sequence, head) units, then one with many: the second one's arrival counters lie
+    # where the first one must not have left anything behind
+    for seed, B, H, ctx, T in ((31, 1, 2, [2000], 64), (32, 3, 80, [700, 40, 900], 8), (33, 2, 120, [600, 600], 3)):
+        d_h = 64
+        q, k, v, off, ctx_d, par, n_nodes = _case(seed, B, H, d_h, ctx, T)
+        kv, vv = tw.kv_view(k, off), tw.kv_view(v, off)
+        nbytes = tw.workspace_bytes(tw.TW_CALL_TREE_VERIFY_ATTN, B, T, H, d_h, max(ctx) + T)
+        assert 0 < nbytes <= tw.TW_STATIC_SCRATCH_BYTES
+        ws = torch.zeros(nbytes // 4, dtype=torch.float32, device=DEV)
+        want = torch.full((B, T, H, d_h), float("nan"), dtype=torch.float32, device=DEV)
+        tw.tree_verify_attn(q, kv, vv, ctx_d, max(ctx), par, n_nodes, 0.125, want, ws)
+        got = torch.full_like(want, float("nan"))
+        tw.tree_verify_attn_static(q, kv, vv, ctx_d, max(ctx), par, n_nodes, 0.125, got)
+        torch.cuda.synchronize()
+        assert torch.isfinite(want).all() and torch.equal(got, want)
 
 
 def test_static_scratch_rejects_what_does_not_fit(tw):
