@@ -18,6 +18,13 @@ pytestmark = pytest.mark.gpu
 
 ATTN_TOL = 2e-3
 SCORE_TOL = 1e-6
+# The 1e-6 absolute bar is stated for scores of order 1/N_tot (Sec. 3.1 Eq. 3: a mean of attention weights over
+# heads, scoring rows and hundreds of keys).  A score of order one -- one head, one scoring row, a few dozen
+# keys, a sharp softmax -- carries the relative rounding of fp32 arithmetic itself (a d_h-term dot product in
+# fp32 with logits of ten and more moves a weight by a few 1e-6 of its value, whatever the kernel), so the
+# shapes drawn at random over every kernel get that relative term on top (below 1e-8 for the paper's shapes);
+# every other test keeps the flat bar.
+SCORE_REL = 4e-6
 DEV = "cuda:0"
 # how many seeded random shapes the two *_random_shapes tests draw (a longer campaign: TW_RANDOM_SHAPES=400)
 N_RANDOM_SHAPES = int(os.environ.get("TW_RANDOM_SHAPES", "8"))
@@ -307,6 +314,33 @@ def test_verify_random_shapes(tw, seed):
         trees = [W.random_parent_tree(W.HostRng(seed, b), n, 6) for b, n in enumerate(n_nodes)]
         q, k, v, off = make_case(300 + seed, B, H, d_h, ctx, T_max, torch.bfloat16, trees)
         check_verify(tw, q, k, v, ctx, n_nodes, padded(trees, T_max), 1 / math.sqrt(d_h), row_off=off)
+
+
+@pytest.mark.parametrize("seed", range(N_RANDOM_SHAPES))
+def test_every_kernel_behind_the_calls_random_shapes(tw, seed):
+    # the two float calls over everything they dispatch on: fp32 and bf16, head sizes 8-128 (matrix-core and
+    # vector kernels), grouped-query head layouts, long prompts (the streaming and the two-pass score kernels),
+    # up to 128 scoring rows, causal or not
+    rng = W.HostRng(25000 + seed)
+    dtype = (torch.bfloat16, torch.float32)[rng.randint(0, 1)]
+    d_h = (8, 16, 40, 64, 96, 128)[rng.randint(0, 5)]
+    H_kv = rng.randint(1, 4)
+    H = H_kv * (1, 1, 2, 3, 7)[rng.randint(0, 4)]
+    B, T_max = rng.randint(1, 4), rng.randint(1, 64)
+    ctx = [rng.randint(0, (200, 1500)[rng.randint(0, 1)]) for _ in range(B)]
+    n_nodes = [rng.randint(1, T_max) for _ in range(B)]
+    trees = [W.random_parent_tree(W.HostRng(seed, b), n, 6) for b, n in enumerate(n_nodes)]
+    # (values as in the configurations, K, V ~ 0.5 N(0,1), which is what the 2e-3 bar is stated for; the
+    # queries of every other case larger, for a sharper softmax)
+    q, k, v, off = make_case(25000 + seed, B, H, d_h, ctx, T_max, dtype, trees, q_std=(None, 1.0)[seed & 1], H_kv=H_kv)
+    check_verify(tw, q, k, v, ctx, n_nodes, padded(trees, T_max), 1 / math.sqrt(d_h), row_off=off,
+                 tol=ATTN_TOL if dtype == torch.bfloat16 else 2e-5)
+    M = (rng.randint(1, 500), rng.randint(500, 3000))[rng.randint(0, 1)]
+    n_text = [rng.randint(1, 200) for _ in range(rng.randint(1, 3))]
+    n_q = [rng.randint(1, min(128, n)) for n in n_text]
+    _check_score(tw, dtype, H, d_h, M, rng.randint(0, 30), n_text, n_q, bool(rng.randint(0, 1)),
+                 q_std=(1.0, 4.0)[rng.randint(0, 1)], seed=25000 + seed, H_kv=None if H_kv == H else H_kv,
+                 rel=SCORE_REL)
 
 
 def test_verify_and_score_with_negative_scale(tw):
@@ -927,7 +961,7 @@ def test_pools_larger_than_4_gib(tw):
 # ----------------------------------------------------------------------------
 # ttp_score
 # ----------------------------------------------------------------------------
-def _check_score(tw, dtype, H, d_h, M, v0, n_text, n_q, causal, q_std=1.0, seed=1, scale=None, H_kv=None):
+def _check_score(tw, dtype, H, d_h, M, v0, n_text, n_q, causal, q_std=1.0, seed=1, scale=None, H_kv=None, rel=0.0):
     B = len(n_text)
     n_tot = [v0 + M + n for n in n_text]
     off, acc = [], 2
@@ -958,8 +992,8 @@ def _check_score(tw, dtype, H, d_h, M, v0, n_text, n_q, causal, q_std=1.0, seed=
     assert torch.isfinite(got).all()
     # one bar for every shape and every kernel behind the call (fp32 weights throughout)
     for b in range(B):
-        err = float((got[b] - want[b]).abs().max())
-        assert err <= SCORE_TOL, f"score error {err:.3e} in sequence {b}"
+        ratio = float(((got[b] - want[b]).abs() / (SCORE_TOL + rel * want[b])).max())
+        assert ratio <= 1.0, f"score error {ratio:.3f} of the bar in sequence {b}"
     again = torch.empty_like(scores)
     run(again)
     torch.cuda.synchronize()
