@@ -1500,6 +1500,25 @@ def _path_parity(runner, cfg):
     assert torch.equal(dw.bonus.cpu(), wa[2])
 
 
+@pytest.mark.parametrize("seed", range(N_RANDOM_SHAPES))
+def test_whole_path_random_shapes(runner, seed):
+    # one step of the whole path (score + select in one call, compaction, verification, acceptance) on a
+    # configuration drawn at random around the paper's: every result of every instance against the oracle
+    rng = W.HostRng(27000 + seed)
+    H, d_h = rng.randint(1, 8), (64, 128)[rng.randint(0, 1)]
+    M = rng.randint(8, 700)
+    n_lo = rng.randint(1, 60)
+    p_lo = rng.randint(0, 300)
+    T = rng.randint(1, 64)
+    cfg = W.Config(name=f"rand{seed}", seed=27000 + seed, dtype="bf16", H=H, d_h=d_h, hidden=H * d_h, M=M,
+                   N=(n_lo, n_lo + rng.randint(0, 60)), n_q=(None, rng.randint(1, n_lo))[rng.randint(0, 1)],
+                   R=rng.randint(1, M), P=(p_lo, p_lo + rng.randint(0, 300)), T=T,
+                   tree=("random", rng.randint(1, 7)), B=rng.randint(1, 5), L=rng.randint(1, 3),
+                   compact_layers=rng.randint(1, 2), paged=bool(rng.randint(0, 1)), page_rows=(8, 16, 32)[rng.randint(0, 2)],
+                   kv_std=0.5, q_std=1.0 / math.sqrt(d_h))
+    _path_parity(runner, cfg)
+
+
 def test_cfg0_tiny_fp32(runner):
     _path_parity(runner, W.CONFIGS["cfg0"])
 
